@@ -1,0 +1,199 @@
+"""CPU oracle for the quantized KV-cache write and quantized paged decode attention.
+
+TEST INFRASTRUCTURE.  Only tests, the smoke check and the benchmark's CPU-baseline
+leg import this package.  It is a thin numpy/ctypes front for `kvq_oracle.c` (plain
+C, fp64) and shares nothing with the GPU library.
+
+Arrays use the oracle's canonical layout:
+  cache  uint8   [num_blocks, 2, num_kv_heads, block_size, head_dim]   (0 = K, 1 = V)
+  scales float32 [num_blocks, 2, num_kv_heads, block_size]   mode 0 (int8 per token-head)
+         float32 [num_blocks, 2, num_kv_heads]               mode 1 (fp8-e4m3 per block-head)
+  k, v, q uint16 bf16 bit patterns [tokens, heads, head_dim]
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+MODE_INT8 = 0
+MODE_FP8 = 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        L = _lib
+        L.oracle_bf16_to_f64.restype = C.c_double
+        L.oracle_bf16_to_f64.argtypes = [C.c_uint16]
+        L.oracle_fp8_decode.restype = C.c_double
+        L.oracle_fp8_decode.argtypes = [C.c_uint8]
+        L.oracle_fp8_encode.restype = C.c_uint8
+        L.oracle_fp8_encode.argtypes = [C.c_double]
+        L.oracle_int8_encode.restype = C.c_int8
+        L.oracle_int8_encode.argtypes = [C.c_double, C.c_float]
+        L.oracle_scale.restype = C.c_float
+        L.oracle_scale.argtypes = [C.c_double, C.c_double]
+        L.oracle_kv_quant_write.restype = C.c_int
+        L.oracle_kv_quant_write.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                            C.c_void_p, C.c_void_p] + [C.c_int32] * 5
+        L.oracle_dequant_at.restype = C.c_double
+        L.oracle_dequant_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int,
+                                        C.c_int, C.c_int, C.c_int, C.c_int32, C.c_int32, C.c_int32]
+        L.oracle_gather_dequant.restype = None
+        L.oracle_gather_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                            C.c_int32, C.c_int, C.c_int, C.c_int32, C.c_int32,
+                                            C.c_int32, C.c_void_p]
+        L.oracle_paged_decode_attn.restype = C.c_int
+        L.oracle_paged_decode_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + \
+            [C.c_int32] * 5 + [C.c_void_p, C.c_int32, C.c_void_p] + [C.c_int32] * 3 + \
+            [C.c_double, C.c_void_p]
+        L.oracle_attn_weights.restype = C.c_int32
+        L.oracle_attn_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4 + \
+            [C.c_void_p] + [C.c_int32] * 6 + [C.c_double, C.c_void_p]
+        L.oracle_num_threads.restype = C.c_int
+        L.oracle_num_threads.argtypes = []
+    return _lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a, dtype, name):
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("%s must be a C-contiguous numpy array of %s" % (name, np.dtype(dtype)))
+    return a
+
+
+def bf16_to_f64(bits):
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def fp8_decode(codes):
+    codes = np.asarray(codes, dtype=np.uint8)
+    L = lib()
+    out = np.empty(codes.shape, dtype=np.float64)
+    flat, o = codes.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.oracle_fp8_decode(int(flat[i]))
+    return out
+
+
+def fp8_encode(y):
+    y = np.asarray(y, dtype=np.float64)
+    L = lib()
+    out = np.empty(y.shape, dtype=np.uint8)
+    flat, o = y.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.oracle_fp8_encode(float(flat[i]))
+    return out
+
+
+def int8_encode(x, s):
+    """RNE(x / s) clamped to [-127, 127]; x float64 array, s one fp32 scale."""
+    x = np.asarray(x, dtype=np.float64)
+    L = lib()
+    out = np.empty(x.shape, dtype=np.int8)
+    flat, o = x.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.oracle_int8_encode(float(flat[i]), float(np.float32(s)))
+    return out
+
+
+def scale(absmax, qmax):
+    return np.float32(lib().oracle_scale(float(absmax), float(qmax)))
+
+
+def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
+    """Zero-filled canonical cache and scales."""
+    cache = np.zeros((num_blocks, 2, num_kv_heads, block_size, head_dim), dtype=np.uint8)
+    if mode == MODE_INT8:
+        scales = np.zeros((num_blocks, 2, num_kv_heads, block_size), dtype=np.float32)
+    else:
+        scales = np.zeros((num_blocks, 2, num_kv_heads), dtype=np.float32)
+    return cache, scales
+
+
+def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
+    """In-place write of bf16 rows k, v [T, H_kv, D] at slot_mapping [T] (int64)."""
+    _chk(k, np.uint16, "k"), _chk(v, np.uint16, "v")
+    _chk(slot_mapping, np.int64, "slot_mapping")
+    _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    nblk, two, H, bs, D = cache.shape
+    assert two == 2 and k.shape == v.shape == (slot_mapping.shape[0], H, D)
+    assert scales.shape == ((nblk, 2, H, bs) if mode == MODE_INT8 else (nblk, 2, H))
+    live = slot_mapping[slot_mapping >= 0]
+    assert live.size == 0 or int(live.max()) < nblk * bs
+    rc = lib().oracle_kv_quant_write(_ptr(k), _ptr(v), _ptr(slot_mapping), k.shape[0],
+                                     _ptr(cache), _ptr(scales), mode, nblk, bs, H, D)
+    if rc != 0:
+        raise ValueError("oracle_kv_quant_write failed: %d" % rc)
+
+
+def dequant(cache, scales, mode):
+    """Dequantized fp64 value of every logical element, same shape as cache."""
+    nblk, _, H, bs, D = cache.shape
+    if mode == MODE_INT8:
+        return cache.view(np.int8).astype(np.float64) * scales.astype(np.float64)[..., None]
+    table = fp8_decode(np.arange(256, dtype=np.uint8))
+    return table[cache] * scales.astype(np.float64)[..., None, None]
+
+
+def gather_dequant(cache, scales, mode, block_table_row, n, kv, h):
+    """Dense fp64 [n, D] of K (kv=0) or V (kv=1) of one sequence and kv head."""
+    _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    row = np.ascontiguousarray(block_table_row, dtype=np.int32)
+    nblk, _, H, bs, D = cache.shape
+    assert (n + bs - 1) // bs <= row.shape[0]
+    assert n == 0 or (row[:(n + bs - 1) // bs].min() >= 0 and row[:(n + bs - 1) // bs].max() < nblk)
+    dense = np.empty((n, D), dtype=np.float64)
+    lib().oracle_gather_dequant(_ptr(cache), _ptr(scales), mode, _ptr(row), n, kv, h, bs, H, D,
+                                _ptr(dense))
+    return dense
+
+
+def paged_decode_attn(q, cache, scales, mode, block_tables, seq_lens, q_len, sm_scale):
+    """out float64 [batch*q_len, H_q, D]."""
+    _chk(q, np.uint16, "q"), _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    _chk(block_tables, np.int32, "block_tables"), _chk(seq_lens, np.int32, "seq_lens")
+    nblk, _, H, bs, D = cache.shape
+    batch = seq_lens.shape[0]
+    assert q.shape[0] == batch * q_len and q.shape[2] == D
+    Hq = q.shape[1]
+    assert Hq % H == 0 and block_tables.shape[0] == batch
+    for b in range(batch):
+        nb = (int(seq_lens[b]) + bs - 1) // bs
+        assert nb <= block_tables.shape[1]
+        assert block_tables[b, :nb].min() >= 0 and block_tables[b, :nb].max() < nblk
+    out = np.empty((batch * q_len, Hq, D), dtype=np.float64)
+    rc = lib().oracle_paged_decode_attn(_ptr(q), _ptr(cache), _ptr(scales), mode, nblk, bs, H, D,
+                                        _ptr(block_tables), block_tables.shape[1], _ptr(seq_lens),
+                                        batch, q_len, Hq, float(sm_scale), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_paged_decode_attn failed: %d" % rc)
+    return out
+
+
+def attn_weights(q, cache, scales, mode, block_table_row, seq_len, q_len, j, hq, q_token_index,
+                 sm_scale):
+    """Softmax weights of one (sequence, query token j, q head hq): float64 [n]."""
+    _chk(q, np.uint16, "q"), _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    row = np.ascontiguousarray(block_table_row, dtype=np.int32)
+    nblk, _, H, bs, D = cache.shape
+    n = seq_len - q_len + j + 1
+    w = np.empty(n, dtype=np.float64)
+    got = lib().oracle_attn_weights(_ptr(q), _ptr(cache), _ptr(scales), mode, bs, H, D, _ptr(row),
+                                    seq_len, q_len, j, q.shape[1], hq, q_token_index,
+                                    float(sm_scale), _ptr(w))
+    assert got == n
+    return w
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
