@@ -1,0 +1,153 @@
+/*
+ * kvq.h -- C ABI of the MI355X (gfx950) library for on-the-fly KV-cache quantization and
+ * quantized paged decode attention.
+ *
+ * The operations are the ones the paper describes in its KV Cache Quantization passage
+ * (Section 7.2.2: K and V are quantized from BF16 to INT8 or FP8 while generating, with
+ * dynamic scaling, which halves the cache and relieves the decode phase's memory-bandwidth
+ * pressure), on the paged KV cache of Section 2 (fixed-size blocks reached through
+ * per-request block tables) and for the decode phase of Section 2 (each new token attends
+ * over the whole stored history).  The paper fixes no constants; the ones below
+ * (127, 448, round-half-to-even, scale granularity) are the benchmark configurations'.
+ *
+ * Conventions for every entry point
+ *   - Every pointer marked "device" is GPU memory owned by the caller; the library
+ *     allocates nothing, frees nothing and keeps no state between calls.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and return at once: no host synchronisation, no device-to-host copy.
+ *   - Return value: KVQ_OK (0) or a negative KVQ_E_* code.  Arguments are validated on the
+ *     host before any HIP call, so a bad argument never launches anything.  Nothing is
+ *     printed and no exception crosses the boundary.
+ *   - Zero-size calls (num_tokens == 0, batch == 0) succeed without launching.
+ *   - Not checked (the caller's contract): block ids and slots in range; no duplicate slot
+ *     within one call; no NaN/Inf in k, v, q; |q| <= 65504; q_len <= seq_lens[b] <= max_seq_len;
+ *     block-table entries valid for every block below ceil(seq_lens[b] / block_size).
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVQ_INT8_TOKEN_HEAD = 0,    /* int8 codes in [-127,127], one fp32 scale per (token, kv head) */
+  KVQ_FP8E4M3_BLOCK_HEAD = 1  /* OCP E4M3 (finite-only, max 448) codes, one fp32 scale per
+                                 (cache block, kv head) */
+} kvq_mode_t;
+
+enum {
+  KVQ_OK = 0,
+  KVQ_E_NULLPTR = -1,    /* a required pointer is NULL */
+  KVQ_E_BAD_MODE = -2,   /* desc->mode is not a kvq_mode_t */
+  KVQ_E_BAD_SHAPE = -3,  /* unsupported head_dim / block_size / head counts / lengths */
+  KVQ_E_WORKSPACE = -4,  /* workspace_bytes is smaller than paged_decode_attn_workspace_bytes() */
+  KVQ_E_HIP = -5         /* a kernel launch failed (hipGetLastError was not hipSuccess) */
+};
+
+/* Shape of one layer's cache.  K and V of a layer live in one `cache` buffer and one
+ * `scales` buffer.
+ *
+ * Logical element (blk, kv, h, off, d): block blk, kv = 0 for K / 1 for V, kv head h,
+ * token offset off inside the block, channel d.  Physical byte position in `cache`:
+ *     tile  = ((blk * 2 + kv) * num_kv_heads + h) * block_size * head_dim
+ *     K:  tile + off * head_dim + d          (token-major: a token's row is contiguous)
+ *     V:  tile + d * block_size + off        (channel-major: the tokens of a channel are
+ *                                             contiguous, which is the order the P.V matrix
+ *                                             instruction consumes)
+ * kvq_cache_to_canonical / kvq_cache_from_canonical convert to and from the plain
+ * [num_blocks][2][num_kv_heads][block_size][head_dim] order.
+ * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
+ *         f32 [num_blocks][2][num_kv_heads]               for KVQ_FP8E4M3_BLOCK_HEAD
+ * Supported: head_dim 64 or 128; block_size a power of two in [16, 256]. */
+typedef struct {
+  int32_t mode;         /* kvq_mode_t */
+  int32_t num_blocks;   /* physical blocks in the pool */
+  int32_t block_size;   /* tokens per block */
+  int32_t num_kv_heads;
+  int32_t head_dim;
+} kvq_cache_desc_t;
+
+/* Buffer sizes in bytes for a descriptor (0 if the descriptor is invalid). Host only. */
+size_t kvq_cache_bytes(const kvq_cache_desc_t* desc);
+size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
+
+/* Section 7.2.2, "On-the-fly Quantization": quantize num_tokens new K and V rows and store
+ * them at their slots (slot = physical_block * block_size + offset; a negative slot skips
+ * the token).
+ *   k, v          device, bf16 [num_tokens][num_kv_heads][head_dim], read only
+ *   slot_mapping  device, int64 [num_tokens], read only
+ *   cache, scales device, layouts above, updated in place
+ * KVQ_INT8_TOKEN_HEAD: per (token, kv head), separately for K and V: scale = fp32 nearest to
+ *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
+ *   exact x/scale, clamped to [-127, 127].
+ * KVQ_FP8E4M3_BLOCK_HEAD: the tokens of this call that fall into one block must be
+ *   consecutive in token order with consecutive increasing slots (append order).  For each
+ *   such run, per kv head, separately for K and V: s_prev = the stored block scale if the
+ *   run starts above offset 0, else 0 (a write at offset 0 starts the block afresh);
+ *   s_new = max(s_prev, fp32 nearest to run absmax/448) is stored; if s_new > s_prev > 0
+ *   the codes already stored below the run's first offset are re-encoded as
+ *   encode(decode(c) * s_prev / s_new); the new codes are encode(x / s_new) (0x00 when
+ *   s_new == 0).  encode = nearest E4M3 value, ties to even, saturating at +-448.
+ * A block must not be written by two runs of one call, nor while another sequence's table
+ * references it. */
+int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
+                   int32_t num_tokens, void* cache, float* scales,
+                   const kvq_cache_desc_t* desc, void* stream);
+
+/* Split-K chunk (in tokens, a multiple of 64) that paged_decode_attn uses when its
+ * chunk_tokens argument is 0.  Host only; returns 0 on invalid arguments. */
+int32_t paged_decode_attn_default_chunk(const kvq_cache_desc_t* desc, int32_t batch,
+                                        int32_t q_len, int32_t num_q_heads,
+                                        int32_t max_seq_len);
+
+/* Bytes of device workspace paged_decode_attn needs for these arguments (split-K partial
+ * results).  Host only; returns 0 on invalid arguments or when nothing is needed. */
+size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
+                                         int32_t q_len, int32_t num_q_heads,
+                                         int32_t max_seq_len, int32_t chunk_tokens);
+
+/* Section 2, decode phase, over the quantized paged cache of Section 7.2.2: for sequence b,
+ * query token j (0 <= j < q_len) and query head hq, attend over positions
+ * 0 .. seq_lens[b] - q_len + j of kv head hq / (num_q_heads / num_kv_heads):
+ *     out = sum_p softmax_p(sm_scale * q . Khat[p]) * Vhat[p],   Xhat = code * scale.
+ * Position p lives at block_tables[b][p / block_size], offset p % block_size.
+ * seq_lens[b] counts the q_len current tokens, which must already be in the cache.
+ *   q             device, bf16 [batch*q_len][num_q_heads][head_dim], read only
+ *   block_tables  device, int32 [batch][max_blocks_per_seq], read only; entries past a
+ *                 sequence's last block are never dereferenced
+ *   seq_lens      device, int32 [batch], read only
+ *   max_seq_len   host upper bound on seq_lens (sizes the launch grid)
+ *   chunk_tokens  split-K chunk in tokens, a multiple of 64; 0 = library default
+ *   out           device, f32 [batch*q_len][num_q_heads][head_dim], written
+ *   workspace     device, >= paged_decode_attn_workspace_bytes(...) bytes, 16-byte aligned;
+ *                 contents before and after the call are unspecified
+ * The context of a sequence is cut into chunks; each chunk's workgroup leaves an
+ * unnormalised partial (running max, sum, accumulator) in the workspace and a second kernel
+ * merges them by the log-sum-exp rule.  Results are deterministic run to run (no atomics).
+ * Requires 1 <= q_len <= 16 and num_q_heads % num_kv_heads == 0. */
+int paged_decode_attn(const void* q, const void* cache, const float* scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                      int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                      int32_t q_len, int32_t num_q_heads, int32_t max_seq_len, float sm_scale,
+                      int32_t chunk_tokens, float* out, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Pure byte permutations between the physical cache layout above and the canonical
+ * [num_blocks][2][num_kv_heads][block_size][head_dim] order (both device, kvq_cache_bytes()
+ * long, must not overlap).  Used by tests and tools; not on the hot path. */
+int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,
+                           void* stream);
+int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,
+                             void* stream);
+
+/* Static, never-NULL description of a return code. */
+const char* kvq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

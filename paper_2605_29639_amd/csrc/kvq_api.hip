@@ -1,0 +1,202 @@
+// extern "C" entry points declared in include/kvq.h: host-side validation first (no HIP call
+// is made for a bad argument), then the kernel launches on the caller's stream.
+#include <math.h>
+
+#include "kvq_internal.h"
+
+namespace {
+
+bool desc_ok(const kvq_cache_desc_t* d, int* err) {
+  if (!d) { *err = KVQ_E_NULLPTR; return false; }
+  if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD) {
+    *err = KVQ_E_BAD_MODE;
+    return false;
+  }
+  const int bs = d->block_size;
+  const bool bs_ok = bs >= 16 && bs <= 256 && (bs & (bs - 1)) == 0;
+  if (d->num_blocks < 0 || !bs_ok || d->num_kv_heads <= 0 ||
+      (d->head_dim != 64 && d->head_dim != 128)) {
+    *err = KVQ_E_BAD_SHAPE;
+    return false;
+  }
+  return true;
+}
+
+int ilog2(int x) {
+  int s = 0;
+  while ((1 << s) < x) ++s;
+  return s;
+}
+
+// Everything the launch needs that depends only on host-side arguments.
+bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t num_q_heads,
+               int32_t max_seq_len, int32_t chunk_tokens, kvq::AttnPlan* plan, int* err) {
+  if (!desc_ok(d, err)) return false;
+  if (batch < 0 || q_len < 1 || q_len > 16 || num_q_heads <= 0 ||
+      num_q_heads % d->num_kv_heads != 0 || max_seq_len < 0 || chunk_tokens < 0 ||
+      chunk_tokens % 64 != 0) {
+    *err = KVQ_E_BAD_SHAPE;
+    return false;
+  }
+  const int group = num_q_heads / d->num_kv_heads;
+  plan->rows = group * q_len;
+  plan->row_tiles = plan->rows <= 16 ? 1 : 2;
+  plan->num_row_groups = (plan->rows + 16 * plan->row_tiles - 1) / (16 * plan->row_tiles);
+  int chunk = chunk_tokens;
+  if (chunk == 0) {
+    // Aim at about eight workgroups per compute unit (256 CUs) for a batch whose mean length
+    // is ~60 % of max_seq_len, with chunks between 256 and 4096 tokens (multiples of 256: four
+    // wavefronts x 64-token groups).
+    const double pairs = (double)batch * d->num_kv_heads * plan->num_row_groups;
+    const double want = 0.6 * (double)max_seq_len * pairs / 2048.0;
+    chunk = (int)(want / 256.0) * 256;
+    if (chunk < 256) chunk = 256;
+    if (chunk > 4096) chunk = 4096;
+  }
+  plan->chunk_tokens = chunk;
+  plan->num_chunks = max_seq_len > 0 ? (max_seq_len + chunk - 1) / chunk : 1;
+  const size_t items = (size_t)batch * d->num_kv_heads * plan->num_chunks * plan->rows;
+  plan->acc_floats = plan->num_chunks > 1 ? items * d->head_dim : 0;
+  plan->ml_floats = plan->num_chunks > 1 ? items * 2 : 0;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kvq_cache_bytes(const kvq_cache_desc_t* desc) {
+  int err;
+  if (!desc_ok(desc, &err)) return 0;
+  return (size_t)desc->num_blocks * 2 * desc->num_kv_heads * desc->block_size * desc->head_dim;
+}
+
+size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
+  int err;
+  if (!desc_ok(desc, &err)) return 0;
+  const size_t per_block = (size_t)2 * desc->num_kv_heads *
+                           (desc->mode == KVQ_INT8_TOKEN_HEAD ? desc->block_size : 1);
+  return (size_t)desc->num_blocks * per_block * sizeof(float);
+}
+
+int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
+                   int32_t num_tokens, void* cache, float* scales,
+                   const kvq_cache_desc_t* desc, void* stream) {
+  int err;
+  if (!desc_ok(desc, &err)) return err;
+  if (num_tokens < 0) return KVQ_E_BAD_SHAPE;
+  if (num_tokens == 0) return KVQ_OK;
+  if (!k || !v || !slot_mapping || !cache || !scales) return KVQ_E_NULLPTR;
+  const hipError_t e = kvq::launch_write(k, v, slot_mapping, num_tokens, cache, scales, *desc,
+                                         (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+int32_t paged_decode_attn_default_chunk(const kvq_cache_desc_t* desc, int32_t batch,
+                                        int32_t q_len, int32_t num_q_heads,
+                                        int32_t max_seq_len) {
+  kvq::AttnPlan plan;
+  int err;
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, 0, &plan, &err)) return 0;
+  return plan.chunk_tokens;
+}
+
+size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
+                                         int32_t q_len, int32_t num_q_heads,
+                                         int32_t max_seq_len, int32_t chunk_tokens) {
+  kvq::AttnPlan plan;
+  int err;
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
+    return 0;
+  return (plan.acc_floats + plan.ml_floats) * sizeof(float);
+}
+
+int paged_decode_attn(const void* q, const void* cache, const float* scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                      int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                      int32_t q_len, int32_t num_q_heads, int32_t max_seq_len, float sm_scale,
+                      int32_t chunk_tokens, float* out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  kvq::AttnPlan plan;
+  int err;
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
+    return err;
+  if (max_blocks_per_seq < 0 ||
+      (int64_t)max_blocks_per_seq * desc->block_size < (int64_t)max_seq_len)
+    return KVQ_E_BAD_SHAPE;
+  if (batch == 0) return KVQ_OK;
+  if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
+  if (!q || !cache || !scales || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
+  const size_t need = (plan.acc_floats + plan.ml_floats) * sizeof(float);
+  if (need > 0) {
+    if (!workspace) return KVQ_E_NULLPTR;
+    if (workspace_bytes < need) return KVQ_E_WORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return KVQ_E_BAD_SHAPE;
+  }
+  const size_t grid = (size_t)batch * plan.num_row_groups * desc->num_kv_heads * plan.num_chunks;
+  if (grid > 0x7FFFFFFFull) return KVQ_E_BAD_SHAPE;
+
+  kvq::AttnArgs a;
+  a.q = (const uint16_t*)q;
+  a.cache = (const uint8_t*)cache;
+  a.scales = scales;
+  a.block_tables = block_tables;
+  a.seq_lens = seq_lens;
+  a.out = out;
+  a.ws_acc = (float*)workspace;
+  a.ws_ml = (float*)workspace + plan.acc_floats;
+  a.max_blocks_per_seq = max_blocks_per_seq;
+  a.batch = batch;
+  a.q_len = q_len;
+  a.num_q_heads = num_q_heads;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.group = num_q_heads / desc->num_kv_heads;
+  a.rows = plan.rows;
+  a.block_size = desc->block_size;
+  a.bs_shift = ilog2(desc->block_size);
+  a.head_dim = desc->head_dim;
+  a.mode = desc->mode;
+  a.chunk_tokens = plan.chunk_tokens;
+  a.num_chunks = plan.num_chunks;
+  a.row_tiles = plan.row_tiles;
+  a.num_row_groups = plan.num_row_groups;
+  a.scale_log2 = sm_scale * 1.4426950408889634f;
+  const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,
+                           void* stream) {
+  int err;
+  if (!desc_ok(desc, &err)) return err;
+  if (kvq_cache_bytes(desc) == 0) return KVQ_OK;
+  if (!cache || !canonical) return KVQ_E_NULLPTR;
+  return kvq::launch_repack(cache, canonical, *desc, true, (hipStream_t)stream) == hipSuccess
+             ? KVQ_OK
+             : KVQ_E_HIP;
+}
+
+int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,
+                             void* stream) {
+  int err;
+  if (!desc_ok(desc, &err)) return err;
+  if (kvq_cache_bytes(desc) == 0) return KVQ_OK;
+  if (!cache || !canonical) return KVQ_E_NULLPTR;
+  return kvq::launch_repack(canonical, cache, *desc, false, (hipStream_t)stream) == hipSuccess
+             ? KVQ_OK
+             : KVQ_E_HIP;
+}
+
+const char* kvq_strerror(int code) {
+  switch (code) {
+    case KVQ_OK: return "ok";
+    case KVQ_E_NULLPTR: return "a required pointer is NULL";
+    case KVQ_E_BAD_MODE: return "unknown quantization mode";
+    case KVQ_E_BAD_SHAPE: return "unsupported shape or size argument";
+    case KVQ_E_WORKSPACE: return "workspace too small";
+    case KVQ_E_HIP: return "kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Internal declarations shared by the library's translation units (host side).
+// The device kernels live in kvq_write.hip, kvq_attn.hip and kvq_repack.hip; kvq_api.hip
+// holds the extern "C" entry points, which validate on the host and then call these.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/kvq.h"
+
+namespace kvq {
+
+// Physical position of the (blk, kv, h) tile inside the cache buffer, in bytes.
+__host__ __device__ inline size_t tile_offset(int64_t blk, int kv, int h, int num_kv_heads,
+                                              int block_size, int head_dim) {
+  return (((size_t)blk * 2 + (size_t)kv) * (size_t)num_kv_heads + (size_t)h) *
+         (size_t)block_size * (size_t)head_dim;
+}
+// Position of logical element (off, d) inside a K tile (token-major) and a V tile
+// (channel-major).
+__host__ __device__ inline int k_elem(int off, int d, int /*block_size*/, int head_dim) {
+  return off * head_dim + d;
+}
+__host__ __device__ inline int v_elem(int off, int d, int block_size, int /*head_dim*/) {
+  return d * block_size + off;
+}
+
+struct AttnPlan {
+  int32_t chunk_tokens;    // split-K chunk, multiple of 64
+  int32_t num_chunks;      // ceil(max_seq_len / chunk_tokens)
+  int32_t rows;            // (num_q_heads / num_kv_heads) * q_len query rows per kv head
+  int32_t row_tiles;       // 16-row tiles handled by one workgroup (1 or 2)
+  int32_t num_row_groups;  // ceil(rows / (16 * row_tiles))
+  size_t acc_floats;       // workspace: accumulators
+  size_t ml_floats;        // workspace: (max, sum) pairs
+};
+
+struct AttnArgs {
+  const uint16_t* q;
+  const uint8_t* cache;
+  const float* scales;
+  const int32_t* block_tables;
+  const int32_t* seq_lens;
+  float* out;
+  float* ws_acc;
+  float* ws_ml;
+  int32_t max_blocks_per_seq, batch, q_len, num_q_heads, num_kv_heads, group, rows;
+  int32_t block_size, bs_shift, head_dim, mode;
+  int32_t chunk_tokens, num_chunks, row_tiles, num_row_groups;
+  float scale_log2;  // sm_scale * log2(e)
+};
+
+hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mapping,
+                        int32_t num_tokens, void* cache, float* scales,
+                        const kvq_cache_desc_t& desc, hipStream_t stream);
+hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
+hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
+                         bool to_canonical, hipStream_t stream);
+
+}  // namespace kvq

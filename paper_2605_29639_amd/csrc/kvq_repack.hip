@@ -1,0 +1,41 @@
+// Byte permutations between the library's physical cache layout (K tiles token-major, V tiles
+// channel-major) and the canonical [block][K|V][head][token][channel] order.  Not on the hot
+// path: used to hand a cache to, or take one from, code that expects the canonical order.
+#include "kvq_internal.h"
+
+namespace kvq {
+namespace {
+
+__global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ src,
+                                                     uint8_t* __restrict__ dst, size_t total,
+                                                     int H, int bs, int D, bool to_canonical) {
+  const size_t tile_bytes = (size_t)bs * D;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    // i indexes the canonical array
+    const size_t tile = i / tile_bytes;
+    const int within = (int)(i - tile * tile_bytes);
+    const int off = within / D, d = within - off * D;
+    const int kv = (int)((tile / H) & 1);
+    const size_t phys = tile * tile_bytes + (kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D));
+    if (to_canonical) dst[i] = src[phys];
+    else dst[phys] = src[i];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
+                         bool to_canonical, hipStream_t stream) {
+  const size_t total = (size_t)desc.num_blocks * 2 * desc.num_kv_heads * desc.block_size *
+                       desc.head_dim;
+  if (total == 0) return hipSuccess;
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     (const uint8_t*)src, (uint8_t*)dst, total, desc.num_kv_heads,
+                     desc.block_size, desc.head_dim, to_canonical);
+  return hipGetLastError();
+}
+
+}  // namespace kvq

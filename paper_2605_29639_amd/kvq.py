@@ -1,0 +1,171 @@
+"""Python binding of the C-ABI library (include/kvq.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch tensors are used for
+device memory and for the current stream.  There is no CPU fallback: if the built library
+is missing, loading fails with an error.
+"""
+import ctypes as C
+import os
+
+MODE_INT8 = 0   # KVQ_INT8_TOKEN_HEAD
+MODE_FP8 = 1    # KVQ_FP8E4M3_BLOCK_HEAD
+
+OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, -5
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
+
+EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
+           "paged_decode_attn_default_chunk", "paged_decode_attn_workspace_bytes",
+           "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
+           "kvq_strerror")
+
+
+class CacheDesc(C.Structure):
+    """kvq_cache_desc_t"""
+    _fields_ = [("mode", C.c_int32), ("num_blocks", C.c_int32), ("block_size", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32)]
+
+    def cache_shape(self):
+        return (self.num_blocks, 2, self.num_kv_heads, self.block_size, self.head_dim)
+
+    def scales_shape(self):
+        if self.mode == MODE_INT8:
+            return (self.num_blocks, 2, self.num_kv_heads, self.block_size)
+        return (self.num_blocks, 2, self.num_kv_heads)
+
+
+class KvqError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__("%s failed: %d (%s)" % (what, code, strerror(code)))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (raw ctypes handle)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s is not built: run `python -m paper_2605_29639_amd.build` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        P, I32, SZ = C.c_void_p, C.c_int32, C.c_size_t
+        D = C.POINTER(CacheDesc)
+        L.kvq_cache_bytes.restype, L.kvq_cache_bytes.argtypes = SZ, [D]
+        L.kvq_scales_bytes.restype, L.kvq_scales_bytes.argtypes = SZ, [D]
+        L.kv_quant_write.restype = C.c_int
+        L.kv_quant_write.argtypes = [P, P, P, I32, P, P, D, P]
+        L.paged_decode_attn_default_chunk.restype = I32
+        L.paged_decode_attn_default_chunk.argtypes = [D, I32, I32, I32, I32]
+        L.paged_decode_attn_workspace_bytes.restype = SZ
+        L.paged_decode_attn_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32]
+        L.paged_decode_attn.restype = C.c_int
+        L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
+                                        I32, P, P, SZ, P]
+        L.kvq_cache_to_canonical.restype = C.c_int
+        L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
+        L.kvq_cache_from_canonical.restype = C.c_int
+        L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
+        L.kvq_strerror.restype, L.kvq_strerror.argtypes = C.c_char_p, [C.c_int]
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().kvq_strerror(int(code)).decode()
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(int(stream))
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous device tensor of %s" % (name, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def make_desc(mode, num_blocks, block_size, num_kv_heads, head_dim):
+    return CacheDesc(int(mode), int(num_blocks), int(block_size), int(num_kv_heads), int(head_dim))
+
+
+def alloc_cache(desc, device="cuda", zero=True):
+    """(cache uint8, scales float32) device tensors of the sizes the library reports."""
+    import torch
+    nbytes, sbytes = lib().kvq_cache_bytes(desc), lib().kvq_scales_bytes(desc)
+    make = torch.zeros if zero else torch.empty
+    cache = make(nbytes, dtype=torch.uint8, device=device)
+    scales = make(sbytes // 4, dtype=torch.float32, device=device).view(desc.scales_shape())
+    return cache, scales
+
+
+def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None):
+    import torch
+    rc = lib().kv_quant_write(_dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
+                              _dev(slot_mapping, torch.int64, "slot_mapping"), k.shape[0],
+                              _dev(cache, torch.uint8, "cache"),
+                              _dev(scales, torch.float32, "scales"), C.byref(desc),
+                              _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "kv_quant_write")
+
+
+def default_chunk(desc, batch, q_len, num_q_heads, max_seq_len):
+    return int(lib().paged_decode_attn_default_chunk(C.byref(desc), batch, q_len, num_q_heads,
+                                                     max_seq_len))
+
+
+def workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0):
+    return int(lib().paged_decode_attn_workspace_bytes(C.byref(desc), batch, q_len, num_q_heads,
+                                                       max_seq_len, chunk_tokens))
+
+
+def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0, device="cuda"):
+    import torch
+    n = workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max_seq_len,
+                      sm_scale, out, workspace, chunk_tokens=0, stream=None):
+    import torch
+    batch = seq_lens.shape[0]
+    rc = lib().paged_decode_attn(
+        _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
+        _dev(scales, torch.float32, "scales"), C.byref(desc),
+        _dev(block_tables, torch.int32, "block_tables"), block_tables.shape[1],
+        _dev(seq_lens, torch.int32, "seq_lens"), batch, q_len, q.shape[1], max_seq_len,
+        float(sm_scale), chunk_tokens, _dev(out, torch.float32, "out"),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "paged_decode_attn")
+
+
+def cache_to_canonical(cache, desc, stream=None):
+    """Canonical [num_blocks, 2, H_kv, block_size, head_dim] uint8 copy of a physical cache."""
+    import torch
+    out = torch.empty_like(cache)
+    rc = lib().kvq_cache_to_canonical(_dev(cache, torch.uint8, "cache"), C.c_void_p(out.data_ptr()),
+                                      C.byref(desc), _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "kvq_cache_to_canonical")
+    return out.view(desc.cache_shape())
+
+
+def cache_from_canonical(canonical, desc, stream=None):
+    """Physical-layout cache (flat uint8) holding the given canonical array."""
+    import torch
+    canonical = canonical.contiguous().view(-1)
+    out = torch.empty_like(canonical)
+    rc = lib().kvq_cache_from_canonical(_dev(canonical, torch.uint8, "canonical"),
+                                        C.c_void_p(out.data_ptr()), C.byref(desc), _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "kvq_cache_from_canonical")
+    return out

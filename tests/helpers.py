@@ -26,3 +26,83 @@ def oracle_fill(wl, sequences=None):
         oracle.kv_quant_write(np.concatenate(ks), np.concatenate(vs), np.concatenate(ss), cache,
                               scales, wl.mode)
     return cache, scales
+
+
+# --------------------------------------------------------------------------- GPU side
+
+def bits_to_bf16_tensor(bits, device="cuda"):
+    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 device tensor (no value change)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def gpu_desc(wl):
+    from paper_2605_29639_amd import kvq
+    return kvq.make_desc(wl.mode, wl.num_blocks, wl.block_size, wl.num_kv_heads, wl.head_dim)
+
+
+def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=None):
+    """The library writes the workload into a (zeroed unless given) device pool with the same
+    call sequence as oracle_fill.  Returns (cache, scales, desc)."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    desc = gpu_desc(wl)
+    if cache is None:
+        cache, scales = kvq.alloc_cache(desc)
+    seqs = range(wl.batch) if sequences is None else sequences
+    for b in seqs:
+        start, stop = wl.write_range(b)
+        if stop > start:
+            k, v = wl.kv_rows(b, start, stop)
+            kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
+                               torch.from_numpy(wl.slots(b, start, stop)).cuda(), cache, scales,
+                               desc)
+    if wl.append_tokens:
+        ks, vs, ss = [], [], []
+        for b in seqs:
+            p0, p1 = wl.prefill_len(b), int(wl.seq_lens[b])
+            k, v = wl.kv_rows(b, p0, p1)
+            ks.append(k), vs.append(v), ss.append(wl.slots(b, p0, p1))
+        kvq.kv_quant_write(bits_to_bf16_tensor(np.concatenate(ks)),
+                           bits_to_bf16_tensor(np.concatenate(vs)),
+                           torch.from_numpy(np.concatenate(ss)).cuda(), cache, scales, desc)
+    torch.cuda.synchronize()
+    return cache, scales, desc
+
+
+def gpu_attention(wl, cache, scales, desc, chunk_tokens=None, seq_lens=None, q=None, q_len=None):
+    """Run the library's paged_decode_attn on a device cache; returns float32 numpy out."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    q_len = wl.q_len if q_len is None else q_len
+    seq_lens = wl.seq_lens if seq_lens is None else seq_lens
+    qbits = wl.q if q is None else q
+    chunk = wl.chunk_tokens if chunk_tokens is None else chunk_tokens
+    max_len = int(seq_lens.max())
+    qd = bits_to_bf16_tensor(qbits)
+    bt = torch.from_numpy(wl.block_tables).cuda()
+    sl = torch.from_numpy(np.ascontiguousarray(seq_lens, dtype=np.int32)).cuda()
+    out = torch.full((qbits.shape[0], qbits.shape[1], wl.head_dim), float("nan"),
+                     dtype=torch.float32, device="cuda")
+    ws = kvq.alloc_workspace(desc, len(seq_lens), q_len, qbits.shape[1], max_len, chunk)
+    ws.fill_(0xFF)  # NaN patterns: the kernels must not depend on workspace contents
+    kvq.paged_decode_attn(qd, cache, scales, desc, bt, sl, q_len, max_len, wl.sm_scale, out, ws,
+                          chunk_tokens=chunk)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def upload_oracle_cache(wl, cache_np, scales_np):
+    """Oracle-written canonical cache -> device tensors in the library's physical layout."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    desc = gpu_desc(wl)
+    cache = kvq.cache_from_canonical(torch.from_numpy(cache_np).cuda(), desc)
+    scales = torch.from_numpy(scales_np).cuda()
+    torch.cuda.synchronize()
+    return cache, scales, desc
+
+
+def attn_err(got, want):
+    """max |got - want| / max |want| over the whole output tensor."""
+    return float(np.abs(got.astype(np.float64) - want).max() / np.abs(want).max())

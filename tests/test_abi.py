@@ -1,0 +1,118 @@
+"""The C-ABI library: it loads, exports every function the header declares, and rejects bad
+arguments on the host before any GPU work (so all of this runs without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_29639_amd import kvq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "kvq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)
+
+
+def test_library_loads_and_exports_every_declared_function():
+    names = header_functions()
+    assert set(names) == set(kvq.EXPORTS) and len(names) == len(kvq.EXPORTS)
+    L = kvq.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_strerror_is_static_text_for_any_code():
+    for code in (0, -1, -2, -3, -4, -5, -99, 7):
+        assert isinstance(kvq.strerror(code), str) and kvq.strerror(code)
+    assert kvq.strerror(0) == "ok"
+
+
+def d(mode=0, nblk=8, bs=16, H=2, D=64):
+    return kvq.make_desc(mode, nblk, bs, H, D)
+
+
+def test_sizes():
+    L = kvq.lib()
+    assert L.kvq_cache_bytes(C.byref(d())) == 8 * 2 * 2 * 16 * 64
+    assert L.kvq_scales_bytes(C.byref(d())) == 8 * 2 * 2 * 16 * 4
+    assert L.kvq_scales_bytes(C.byref(d(mode=1))) == 8 * 2 * 2 * 4
+    assert L.kvq_cache_bytes(C.byref(d(D=96))) == 0
+    assert L.kvq_cache_bytes(None) == 0
+
+
+FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below fails validation first
+
+
+@pytest.mark.parametrize("desc,code", [
+    (d(mode=2), kvq.E_BAD_MODE), (d(mode=-1), kvq.E_BAD_MODE),
+    (d(bs=8), kvq.E_BAD_SHAPE), (d(bs=48), kvq.E_BAD_SHAPE), (d(bs=512), kvq.E_BAD_SHAPE),
+    (d(D=96), kvq.E_BAD_SHAPE), (d(D=256), kvq.E_BAD_SHAPE), (d(H=0), kvq.E_BAD_SHAPE),
+    (d(nblk=-1), kvq.E_BAD_SHAPE),
+])
+def test_write_rejects_bad_descriptors(desc, code):
+    L = kvq.lib()
+    assert L.kv_quant_write(FAKE, FAKE, FAKE, 4, FAKE, FAKE, C.byref(desc), None) == code
+
+
+def test_write_argument_checks():
+    L = kvq.lib()
+    ok = d()
+    assert L.kv_quant_write(FAKE, FAKE, FAKE, 4, FAKE, FAKE, None, None) == kvq.E_NULLPTR
+    assert L.kv_quant_write(FAKE, FAKE, FAKE, -1, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
+    assert L.kv_quant_write(None, None, None, 0, None, None, C.byref(ok), None) == kvq.OK
+    for i in range(5):
+        args = [FAKE, FAKE, FAKE, 4, FAKE, FAKE]
+        args[i if i < 3 else i + 1] = None
+        assert L.kv_quant_write(*args, C.byref(ok), None) == kvq.E_NULLPTR
+
+
+def attn(L, desc, q=FAKE, cache=FAKE, scales=FAKE, tables=FAKE, max_blocks=8, lens=FAKE, batch=2,
+         q_len=1, Hq=4, max_len=100, chunk=0, out=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    return L.paged_decode_attn(q, cache, scales, C.byref(desc) if desc is not None else None,
+                               tables, max_blocks, lens, batch, q_len, Hq, max_len, 0.125, chunk,
+                               out, ws, ws_bytes, None)
+
+
+def test_attn_argument_checks():
+    L = kvq.lib()
+    ok = d()
+    assert attn(L, None) == kvq.E_NULLPTR
+    assert attn(L, d(mode=3)) == kvq.E_BAD_MODE
+    assert attn(L, ok, Hq=3) == kvq.E_BAD_SHAPE            # 3 % 2 != 0
+    assert attn(L, ok, q_len=0) == kvq.E_BAD_SHAPE
+    assert attn(L, ok, q_len=17) == kvq.E_BAD_SHAPE
+    assert attn(L, ok, batch=-1) == kvq.E_BAD_SHAPE
+    assert attn(L, ok, chunk=100) == kvq.E_BAD_SHAPE       # not a multiple of 64
+    assert attn(L, ok, max_blocks=6) == kvq.E_BAD_SHAPE    # 6 * 16 < 100
+    assert attn(L, ok, max_len=0) == kvq.E_BAD_SHAPE       # shorter than q_len
+    assert attn(L, ok, batch=0) == kvq.OK                  # empty batch: nothing launched
+    for name in ("q", "cache", "scales", "tables", "lens", "out"):
+        assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
+    # split into chunks of 64 -> needs a workspace
+    need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
+    assert need == 2 * 2 * 2 * 2 * (64 + 2) * 4
+    assert attn(L, ok, chunk=64, ws=None) == kvq.E_NULLPTR
+    assert attn(L, ok, chunk=64, ws_bytes=need - 1) == kvq.E_WORKSPACE
+    assert attn(L, ok, chunk=64, ws=C.c_void_p(0x1004), ws_bytes=need) == kvq.E_BAD_SHAPE
+    # a single chunk needs no workspace at all
+    assert L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 128) == 0
+
+
+def test_default_chunk_is_a_multiple_of_64_within_bounds():
+    L = kvq.lib()
+    big = kvq.make_desc(0, 1000, 16, 8, 128)
+    for batch, max_len in ((1, 100), (64, 4096), (256, 8192), (32, 65536), (1, 1 << 20)):
+        c = L.paged_decode_attn_default_chunk(C.byref(big), batch, 1, 32, max_len)
+        assert c % 64 == 0 and 256 <= c <= 4096
+    assert L.paged_decode_attn_default_chunk(C.byref(big), 1, 1, 33, 100) == 0
+
+
+def test_repack_argument_checks():
+    L = kvq.lib()
+    assert L.kvq_cache_to_canonical(None, FAKE, C.byref(d()), None) == kvq.E_NULLPTR
+    assert L.kvq_cache_from_canonical(FAKE, FAKE, C.byref(d(D=1)), None) == kvq.E_BAD_SHAPE
+    assert L.kvq_cache_to_canonical(None, None, C.byref(d(nblk=0)), None) == kvq.OK

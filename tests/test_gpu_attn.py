@@ -1,0 +1,158 @@
+"""GPU parity, paged_decode_attn: within 2e-3 of the output's max norm of the CPU checker,
+both reading the same quantized bytes (the checker's cache, uploaded)."""
+import zlib
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2605_29639_amd import workloads as W
+from helpers import (attn_err, gpu_attention, gpu_fill, oracle_fill, upload_oracle_cache)
+
+TOL = 2e-3   # max |gpu - oracle| <= TOL * max |oracle| over the call's whole output
+
+
+def oracle_out(wl, oc, osc, seq_lens=None, q=None, q_len=None):
+    return oracle.paged_decode_attn(wl.q if q is None else q, oc, osc, wl.mode, wl.block_tables,
+                                    wl.seq_lens if seq_lens is None else seq_lens,
+                                    wl.q_len if q_len is None else q_len, wl.sm_scale)
+
+
+def check(wl, chunks=(0,), tol=TOL):
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    errs = []
+    for chunk in chunks:
+        got = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk)
+        assert np.isfinite(got).all(), "non-finite output (chunk %d)" % chunk
+        e = attn_err(got, want)
+        errs.append(e)
+        assert e <= tol, "chunk %d: err %.3e" % (chunk, e)
+    return errs
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_tiny_config(mode):
+    check(W.tiny(mode), chunks=(0, 64))
+
+
+CASES = [
+    # name, seq_lens, q_len, Hq, Hkv, D, bs
+    ("ragged16", [1, 15, 16, 17, 63, 64, 65, 255, 256, 257, 700], 1, 4, 2, 64, 16),
+    ("d128_g4", [130, 333, 64, 1000, 5], 1, 32, 8, 128, 16),
+    ("g1", [100, 260], 1, 2, 2, 128, 16),
+    ("g2", [100, 260], 1, 4, 2, 64, 16),
+    ("g8", [90, 515], 1, 16, 2, 128, 16),
+    ("g16_bs64", [300, 1029, 64, 2049], 1, 64, 4, 128, 64),
+    ("bs32", [257, 33], 1, 8, 2, 64, 32),
+    ("bs128", [513, 100], 1, 8, 2, 128, 128),
+    ("qlen4_g8", [53, 20, 4, 300, 1025], 4, 16, 2, 128, 16),
+    ("qlen4_g4", [260, 7], 4, 8, 2, 64, 16),
+    ("qlen2_g16", [100, 400], 2, 32, 2, 128, 64),
+    ("qlen3_g16_rowgroups", [100, 130], 3, 32, 2, 64, 16),
+    ("qlen16_g4", [100, 16, 77], 16, 4, 1, 128, 16),
+]
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_shapes_and_splits(mode, case):
+    name, lens, q_len, Hq, Hkv, D, bs = case
+    lens = [max(l, q_len) for l in lens]
+    wl = W.custom(name, mode, lens, q_len, Hq, Hkv, D, bs, seed=zlib.crc32(name.encode()) % 1000 + mode)
+    check(wl, chunks=(0, 64, 256))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_gpu_written_cache_gives_the_same_attention(mode):
+    """End to end through both entry points: the library's own cache (bit-identical to the
+    checker's, see test_gpu_write) and the uploaded checker's cache give the same output."""
+    wl = W.custom("e2e", mode, [200, 77, 1030], 1, 8, 2, 128, 16, seed=12)
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    c1, s1, desc = gpu_fill(wl)
+    c2, s2, _ = upload_oracle_cache(wl, oc, osc)
+    a = gpu_attention(wl, c1, s1, desc)
+    b = gpu_attention(wl, c2, s2, desc)
+    assert np.array_equal(a, b)
+    assert attn_err(a, want) <= TOL
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_stale_bytes_after_the_last_position_are_never_used(mode):
+    """Unwritten slots hold NaN codes / NaN or huge scales; block-table entries past the last
+    block are -1.  The output must not change and must stay finite."""
+    import torch
+    wl = W.custom("stale", mode, [37, 100, 64, 3], 1, 4, 2, 64, 16, seed=8)
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    live = np.zeros(oc.shape[:1] + oc.shape[3:4], dtype=bool)       # [blk, off]
+    for b in range(wl.batch):
+        s = wl.slots(b, 0, int(wl.seq_lens[b]))
+        live[s // 16, s % 16] = True
+    dirty_c, dirty_s = oc.copy(), osc.copy()
+    for blk, off in np.argwhere(~live):
+        dirty_c[blk, :, :, off, :] = 0x7F if mode == W.MODE_FP8 else 0x80
+        if mode == W.MODE_INT8:
+            dirty_s[blk, :, :, off] = np.nan if (blk + off) % 2 else 3e38
+    if mode == W.MODE_FP8:
+        dead_blocks = ~live.any(axis=1)
+        dirty_s[dead_blocks] = np.nan
+    cache, scales, desc = upload_oracle_cache(wl, dirty_c, dirty_s)
+    for chunk in (0, 64):
+        got = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk)
+        assert np.isfinite(got).all()
+        assert attn_err(got, want) <= TOL
+
+
+def test_run_to_run_determinism():
+    wl = W.custom("det", W.MODE_INT8, [900, 333], 1, 8, 2, 128, 16, seed=2)
+    cache, scales, desc = gpu_fill(wl)
+    a = gpu_attention(wl, cache, scales, desc, chunk_tokens=256)
+    b = gpu_attention(wl, cache, scales, desc, chunk_tokens=256)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_degenerate_inputs(mode):
+    """All-zero V rows carrying the largest weight, zero q, huge and tiny V magnitudes."""
+    wl = W.custom("degenerate", mode, [80, 80, 80, 80], 1, 4, 2, 64, 16, seed=21, outliers=False)
+    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 64)
+    for b in range(4):
+        k, v = wl.kv_rows(b, 0, 80)
+        kf, vf = W.bf16_bits_to_f32(k), W.bf16_bits_to_f32(v)
+        if b == 0:      # an "attention sink": strongest key, zero value
+            kf[0, :] = W.bf16_bits_to_f32(wl.q[0]).reshape(2, 2, 64)[:, 0] * 3
+            vf[0] = 0
+        if b == 1:      # zero query
+            wl.q[1] = 0
+        if b == 2:      # V spans 40 binades across tokens
+            vf *= (2.0 ** np.linspace(-20, 20, 80)).astype(np.float32)[:, None, None]
+        if b == 3:      # everything tiny
+            vf *= np.float32(2.0 ** -60)
+            kf *= np.float32(2.0 ** -30)
+        oracle.kv_quant_write(W.to_bf16_bits(kf), W.to_bf16_bits(vf), wl.slots(b, 0, 80), oc, osc,
+                              mode)
+    want = oracle_out(wl, oc, osc)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    got = gpu_attention(wl, cache, scales, desc)
+    assert np.isfinite(got).all()
+    for b in range(4):   # per sequence, since their magnitudes differ by design
+        assert attn_err(got[b], want[b]) <= TOL, b
+
+
+def test_empty_batch():
+    import torch
+    from paper_2605_29639_amd import kvq
+    desc = kvq.make_desc(0, 4, 16, 2, 64)
+    cache, scales = kvq.alloc_cache(desc)
+    q = torch.empty((0, 4, 64), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((0, 4, 64), dtype=torch.float32, device="cuda")
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    kvq.paged_decode_attn(q, cache, scales, desc,
+                          torch.empty((0, 4), dtype=torch.int32, device="cuda"),
+                          torch.empty(0, dtype=torch.int32, device="cuda"), 1, 0, 0.125, out, ws)
+    torch.cuda.synchronize()

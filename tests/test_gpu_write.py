@@ -1,0 +1,182 @@
+"""GPU parity, kv_quant_write: codes, scales and slot indexing must equal the CPU checker's
+bit for bit, over the whole pool (both sides start from a zero-filled pool)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2605_29639_amd import workloads as W
+from helpers import bits_to_bf16_tensor, gpu_desc, gpu_fill, oracle_fill
+
+
+def fetch(cache, scales, desc):
+    from paper_2605_29639_amd import kvq
+    return kvq.cache_to_canonical(cache, desc).cpu().numpy(), scales.cpu().numpy()
+
+
+def assert_pool_equal(wl, got, want):
+    (gc, gs), (wc, ws) = got, want
+    assert gc.shape == wc.shape and gs.shape == ws.shape
+    bad = np.argwhere(gc != wc)
+    assert bad.size == 0, "codes differ at (blk,kv,h,off,d) %s: gpu %s oracle %s (%d total)" % (
+        bad[0], gc[tuple(bad[0])], wc[tuple(bad[0])], len(bad))
+    sb = np.argwhere(gs.view(np.uint32) != ws.view(np.uint32))
+    assert sb.size == 0, "scales differ at %s: gpu %r oracle %r" % (
+        sb[0], gs[tuple(sb[0])], ws[tuple(sb[0])])
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_tiny_config(mode):
+    wl = W.tiny(mode)
+    cache, scales, desc = gpu_fill(wl)
+    assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
+
+
+SHAPES = [
+    # seq_lens, H_kv, D, bs
+    ([1, 15, 16, 17, 31, 32, 33, 200], 2, 64, 16),
+    ([130, 64, 65, 63, 1], 3, 128, 16),
+    ([300, 129, 64], 2, 128, 64),
+    ([257, 5], 1, 64, 32),
+    ([513], 4, 128, 128),
+]
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_ragged_shapes_bulk_write(mode, shape):
+    lens, H, D, bs = shape
+    wl = W.custom("ragged", mode, lens, 1, H * 2, H, D, bs, seed=1000 + D + bs + mode)
+    cache, scales, desc = gpu_fill(wl)
+    assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
+
+
+@pytest.mark.parametrize("bs,D", [(16, 128), (64, 64)])
+def test_fp8_token_by_token_append_with_rescale(bs, D):
+    """Decode-style appends: each call adds one token per sequence; magnitudes vary so that the
+    block scale grows several times and earlier codes are re-encoded."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    wl = W.custom("append", W.MODE_FP8, [40, 70, 19], 1, 4, 2, D, bs, seed=77)
+    rng = np.random.default_rng(5)
+    desc = gpu_desc(wl)
+    cache, scales = kvq.alloc_cache(desc)
+    oc, osc = oracle.alloc_cache(wl.mode, wl.num_blocks, bs, 2, D)
+    rows = {b: wl.kv_rows(b, 0, int(wl.seq_lens[b])) for b in range(wl.batch)}
+    gain = {b: rng.choice([0.05, 0.3, 1.0, 4.0, 30.0], size=int(wl.seq_lens[b])) for b in range(3)}
+    for step in range(int(wl.seq_lens.max())):
+        ks, vs, ss = [], [], []
+        for b in range(wl.batch):
+            if step < wl.seq_lens[b]:
+                k = W.to_bf16_bits(W.bf16_bits_to_f32(rows[b][0][step:step + 1]) * np.float32(gain[b][step]))
+                v = W.to_bf16_bits(W.bf16_bits_to_f32(rows[b][1][step:step + 1]) * np.float32(gain[b][step]))
+                ks.append(k), vs.append(v), ss.append(wl.slots(b, step, step + 1))
+        k, v, s = np.concatenate(ks), np.concatenate(vs), np.concatenate(ss)
+        oracle.kv_quant_write(k, v, s, oc, osc, wl.mode)
+        kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
+                           torch.from_numpy(s).cuda(), cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_chunked_prefill_then_appends(mode):
+    """A sequence written in uneven pieces (block-aligned or not) and then appended to."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    wl = W.custom("pieces", mode, [150], 1, 4, 2, 128, 16, seed=9)
+    desc = gpu_desc(wl)
+    cache, scales = kvq.alloc_cache(desc)
+    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 128)
+    for lo, hi in ((0, 16), (16, 37), (37, 38), (38, 96), (96, 149), (149, 150)):
+        k, v = wl.kv_rows(0, lo, hi)
+        s = wl.slots(0, lo, hi)
+        oracle.kv_quant_write(k, v, s, oc, osc, mode)
+        kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
+                           torch.from_numpy(s).cuda(), cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
+    import torch
+    from paper_2605_29639_amd import kvq
+    wl = W.custom("edge", mode, [48], 1, 2, 2, 64, 16, seed=3)
+    k, v = wl.kv_rows(0, 0, 48)
+    k[3] = 0                     # all-zero K row (both heads)
+    v[3, 0] = 0x8000             # all negative-zero V row for head 0
+    k[16:32, 1] = 0              # a whole block of zeros for head 1 (fp8: block scale 0)
+    v[40, :, :] = 0
+    v[40, 0, 5] = 0x8000
+    slots = wl.slots(0, 0, 48)
+    slots[7] = -1                # skipped token
+    slots[47] = -1
+    desc = gpu_desc(wl)
+    cache, scales = kvq.alloc_cache(desc)
+    cache.fill_(0x7F)            # stale pool: NaN codes and a garbage scale
+    scales.fill_(123.0)
+    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 64)
+    oc[:] = 0x7F
+    osc[:] = 123.0
+    # the library's pool is physical-layout: make the stale bytes identical logically (they are
+    # all equal, so any permutation of them is the same pool)
+    oracle.kv_quant_write(k, v, slots, oc, osc, mode)
+    kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
+                       torch.from_numpy(slots).cuda(), cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
+
+
+def test_extreme_magnitudes_int8_and_fp8():
+    """Rows near the top and bottom of the bf16 range, and values that land on rounding ties."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    for mode in (W.MODE_INT8, W.MODE_FP8):
+        wl = W.custom("extreme", mode, [64], 1, 1, 1, 128, 16, seed=4, outliers=False)
+        k, v = wl.kv_rows(0, 0, 64)
+        kf, vf = W.bf16_bits_to_f32(k), W.bf16_bits_to_f32(v)
+        kf[0:16] *= np.float32(2.0 ** 100)
+        kf[16:32] *= np.float32(2.0 ** -110)
+        vf[0:16] = np.round(vf[0:16] * 16) / 2          # half-integers
+        vf[0:16, 0, 0] = 127.0 if mode == 0 else 448.0  # scale exactly 1: ties everywhere
+        vf[16:32] = np.round(vf[16:32] * 64) / 64
+        vf[16:32, 0, 1] = 254.0 if mode == 0 else 224.0
+        k, v = W.to_bf16_bits(kf), W.to_bf16_bits(vf)
+        desc = gpu_desc(wl)
+        cache, scales = kvq.alloc_cache(desc)
+        oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 1, 128)
+        s = wl.slots(0, 0, 64)
+        oracle.kv_quant_write(k, v, s, oc, osc, mode)
+        kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
+                           torch.from_numpy(s).cuda(), cache, scales, desc)
+        torch.cuda.synchronize()
+        assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
+
+
+def test_repack_round_trip_and_layout():
+    """to_canonical(from_canonical(x)) = x, and the physical layout is the documented one:
+    K tiles token-major, V tiles channel-major."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    desc = kvq.make_desc(0, 5, 32, 3, 64)
+    rng = np.random.default_rng(0)
+    canon = rng.integers(0, 256, size=desc.cache_shape(), dtype=np.uint8)
+    phys = kvq.cache_from_canonical(torch.from_numpy(canon).cuda(), desc)
+    back = kvq.cache_to_canonical(phys, desc).cpu().numpy()
+    assert np.array_equal(back, canon)
+    p = phys.cpu().numpy().reshape(5, 2, 3, 32 * 64)
+    assert np.array_equal(p[:, 0].reshape(5, 3, 32, 64), canon[:, 0])
+    assert np.array_equal(p[:, 1].reshape(5, 3, 64, 32), canon[:, 1].transpose(0, 1, 3, 2))
+
+
+def test_empty_write_is_a_no_op():
+    import torch
+    from paper_2605_29639_amd import kvq
+    desc = kvq.make_desc(1, 4, 16, 2, 64)
+    cache, scales = kvq.alloc_cache(desc)
+    k = torch.empty((0, 2, 64), dtype=torch.bfloat16, device="cuda")
+    kvq.kv_quant_write(k, k, torch.empty(0, dtype=torch.int64, device="cuda"), cache, scales, desc)
+    torch.cuda.synchronize()
+    assert not cache.any() and not scales.any()
