@@ -1,0 +1,213 @@
+"""Benchmark of the hot path on one MI355X: quantized paged decode attention, achieved HBM
+GB/s and microseconds per layer, next to the CPU checker timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama8b|fp8_append|long_gqa]
+
+One step = one decode step of one layer over the whole batch: kv_quant_write of each
+sequence's newest token, then paged_decode_attn over the layer's cache.  Successive steps
+cycle through several layers' caches so that every step streams from HBM rather than from
+the 256 MB last-level cache.  Prints ONE JSON line.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+
+
+class HipEvents:
+    """Raw HIP events (ctypes over libamdhip64), recorded by the library on its own stream."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+
+    def create(self):
+        e = C.c_void_p()
+        assert self.hip.hipEventCreate(C.byref(e)) == 0
+        return e
+
+    def elapsed_ms(self, a, b):
+        assert self.hip.hipEventSynchronize(b) == 0
+        ms = C.c_float()
+        assert self.hip.hipEventElapsedTime(C.byref(ms), a, b) == 0
+        return ms.value
+
+
+def make_workload(name):
+    from paper_2605_29639_amd import workloads as W
+    if name == "llama8b":
+        return W.llama8b()
+    if name == "fp8_append":
+        return W.fp8_append()
+    if name == "long_gqa":
+        return W.long_gqa()
+    raise SystemExit("unknown workload %s" % name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
+    ap.add_argument("--chunk", type=int, default=-1, help="split-K chunk (-1 = workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this build measures one GPU only: run with --gpus 1 "
+                         "(no collectives or sharding are part of it)")
+
+    import numpy as np
+    import torch
+    from paper_2605_29639_amd import kvq
+    from helpers import bits_to_bf16_tensor, gpu_fill, attn_err
+    kvq.lib()  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    wl = make_workload(args.workload)
+    chunk = wl.chunk_tokens if args.chunk < 0 else args.chunk
+    alg = wl.algorithmic_bytes()
+    # enough layer caches that the cycled live bytes exceed 4 x the 256 MB last-level cache
+    layers = args.layers or max(2, int(np.ceil(4 * 256e6 / alg["kv"])))
+    t_setup = time.time()
+    caches = []
+    desc = None
+    for _ in range(layers):
+        cache, scales, desc = gpu_fill(wl)
+        caches.append((cache, scales))
+    setup_s = time.time() - t_setup
+
+    B, Hq, D = wl.batch, wl.num_q_heads, wl.head_dim
+    max_len = wl.max_seq_len
+    q = bits_to_bf16_tensor(wl.q)
+    bt = torch.from_numpy(wl.block_tables).cuda()
+    sl = torch.from_numpy(wl.seq_lens).cuda()
+    out = torch.empty((B * wl.q_len, Hq, D), dtype=torch.float32, device="cuda")
+    ws = kvq.alloc_workspace(desc, B, wl.q_len, Hq, max_len, chunk)
+    # the newest token of every sequence: what a decode step appends before attending
+    newest = [wl.kv_rows(b, int(wl.seq_lens[b]) - wl.q_len, int(wl.seq_lens[b])) for b in range(B)]
+    k_new = bits_to_bf16_tensor(np.concatenate([n[0] for n in newest]))
+    v_new = bits_to_bf16_tensor(np.concatenate([n[1] for n in newest]))
+    slots_new = torch.from_numpy(np.concatenate(
+        [wl.slots(b, int(wl.seq_lens[b]) - wl.q_len, int(wl.seq_lens[b])) for b in range(B)])).cuda()
+
+    def step(i, write=True):
+        cache, scales = caches[i % layers]
+        if write:
+            kvq.kv_quant_write(k_new, v_new, slots_new, cache, scales, desc, stream=stream)
+        kvq.paged_decode_attn(q, cache, scales, desc, bt, sl, wl.q_len, max_len, wl.sm_scale, out,
+                              ws, chunk_tokens=chunk, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    step_s = (time.perf_counter() - t0) / args.steps
+
+    # the dominant kernel (the split kernel of paged_decode_attn) timed by HIP events that the
+    # library records around its launch, on the same stream, over an identical run of steps
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    L = kvq.lib()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        L.kvq_profile_split_events(pairs[i][0], pairs[i][1])
+        step(i)
+    L.kvq_profile_split_events(None, None)
+    torch.cuda.synchronize()
+    step_ev_s = (time.perf_counter() - t0) / args.steps
+    kern_ms = np.array([ev.elapsed_ms(a, b) for a, b in pairs])
+    kern_s = float(kern_ms.mean()) * 1e-3
+
+    # attention alone (no write), for the record
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, write=False)
+    torch.cuda.synchronize()
+    attn_s = (time.perf_counter() - t0) / args.steps
+
+    result = {
+        "metric": "quantized paged decode attention: achieved HBM GB/s",
+        "value": alg["total"] / step_s / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": step_s * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8 codes, f16 MFMA operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "mode": "int8_token_head" if wl.mode == 0 else "fp8e4m3_block_head",
+                   "batch": B, "q_len": wl.q_len, "num_q_heads": Hq, "num_kv_heads": wl.num_kv_heads,
+                   "head_dim": D, "block_size": wl.block_size, "sum_seq_lens": int(wl.seq_lens.sum()),
+                   "max_seq_len": max_len, "chunk_tokens": chunk or kvq.default_chunk(desc, B, wl.q_len, Hq, max_len),
+                   "layers_cycled": layers, "step": "kv_quant_write(newest token) + paged_decode_attn"},
+        "us_per_layer": step_s * 1e6,
+        "pct_of_hbm_peak": 100.0 * alg["total"] / step_s / 1e9 / HBM_PEAK_GBPS,
+        "attn_only_us_per_layer": attn_s * 1e6,
+        "algorithmic_bytes": alg,
+        "roofline": {"bound": "hbm", "kernel": "attn_split_kernel",
+                     "achieved": alg["total"] / kern_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": alg["total"] / kern_s / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel_us_mean": kern_s * 1e6, "kernel_us_p10": float(np.percentile(kern_ms, 10)) * 1e3,
+                     "kernel_us_p90": float(np.percentile(kern_ms, 90)) * 1e3,
+                     "step_us_with_events": step_ev_s * 1e6},
+        "setup_s": setup_s,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from helpers import oracle_fill
+        # bounded sample: the first sequences of the same workload, up to ~1/4 of its tokens
+        budget = int(wl.seq_lens.sum()) // 4
+        n_seq, tok = 0, 0
+        while n_seq < B and (tok + int(wl.seq_lens[n_seq]) <= budget or n_seq == 0):
+            tok += int(wl.seq_lens[n_seq])
+            n_seq += 1
+        seqs = list(range(n_seq))
+        oc, osc = oracle_fill(wl, sequences=seqs)
+        qs = np.ascontiguousarray(wl.q[:n_seq * wl.q_len])
+        bts = np.ascontiguousarray(wl.block_tables[:n_seq])
+        sls = np.ascontiguousarray(wl.seq_lens[:n_seq])
+        ks = np.concatenate([n[0] for n in newest[:n_seq]])
+        vs = np.concatenate([n[1] for n in newest[:n_seq]])
+        ss = np.concatenate([wl.slots(b, int(wl.seq_lens[b]) - wl.q_len, int(wl.seq_lens[b]))
+                             for b in seqs])
+        times = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.kv_quant_write(ks, vs, ss, oc, osc, wl.mode)
+            want = oracle.paged_decode_attn(qs, oc, osc, wl.mode, bts, sls, wl.q_len, wl.sm_scale)
+            times.append(time.perf_counter() - t0)
+        cpu_s = float(np.median(times))
+        frac = tok / float(wl.seq_lens.sum())
+        sample_bytes = alg["total"] * frac
+        got = out.cpu().numpy()[:n_seq * wl.q_len]
+        result["cpu_baseline"] = {
+            "value": sample_bytes / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "first %d of %d sequences (%d of %d tokens), same step, median of 3; "
+                      "%.3f s per sampled step" % (n_seq, B, tok, int(wl.seq_lens.sum()), cpu_s),
+            "us_per_layer_scaled_to_full": cpu_s / frac * 1e6}
+        result["parity_vs_oracle_on_sample"] = attn_err(got, want)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -144,6 +144,13 @@ int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_d
 int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,
                              void* stream);
 
+/* Measurement hook, not part of the path: while `before` and `after` (hipEvent_t handles
+ * created by the caller) are set, every paged_decode_attn call records `before` on its stream
+ * immediately ahead of its split kernel (the kernel that streams the K/V codes) and `after`
+ * immediately behind it, so that a benchmark can time that kernel alone.  Pass NULL, NULL to
+ * switch the hook off (the initial state).  Process-global and not thread-safe. */
+void kvq_profile_split_events(void* before, void* after);
+
 /* Static, never-NULL description of a return code. */
 const char* kvq_strerror(int code);
 

@@ -187,6 +187,10 @@ int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache
              : KVQ_E_HIP;
 }
 
+void kvq_profile_split_events(void* before, void* after) {
+  kvq::set_profile_events((hipEvent_t)before, (hipEvent_t)after);
+}
+
 const char* kvq_strerror(int code) {
   switch (code) {
     case KVQ_OK: return "ok";

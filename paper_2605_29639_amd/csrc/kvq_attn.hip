@@ -439,16 +439,27 @@ __global__ __launch_bounds__(D) void attn_reduce_kernel(const AttnArgs p) {
   p.out[(((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + d] = num / den;
 }
 
+// measurement hook: events recorded around the split kernel (see kvq_profile_split_events)
+hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+
 template <int MODE, int D>
 hipError_t launch_split(const AttnArgs& a, unsigned grid, hipStream_t stream) {
+  if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
   if (a.row_tiles == 1)
     hipLaunchKernelGGL((attn_split_kernel<MODE, D, 1>), dim3(grid), dim3(kWaves * 64), 0, stream, a);
   else
     hipLaunchKernelGGL((attn_split_kernel<MODE, D, 2>), dim3(grid), dim3(kWaves * 64), 0, stream, a);
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
+  return e;
 }
 
 }  // namespace
+
+void set_profile_events(hipEvent_t before, hipEvent_t after) {
+  g_ev_before = before;
+  g_ev_after = after;
+}
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   const unsigned grid =

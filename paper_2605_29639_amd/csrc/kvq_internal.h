@@ -55,6 +55,7 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
                         int32_t num_tokens, void* cache, float* scales,
                         const kvq_cache_desc_t& desc, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
+void set_profile_events(hipEvent_t before, hipEvent_t after);
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_default_chunk", "paged_decode_attn_workspace_bytes",
            "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
-           "kvq_strerror")
+           "kvq_profile_split_events", "kvq_strerror")
 
 
 class CacheDesc(C.Structure):
@@ -69,6 +69,8 @@ def lib():
         L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
         L.kvq_cache_from_canonical.restype = C.c_int
         L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
+        L.kvq_profile_split_events.restype = None
+        L.kvq_profile_split_events.argtypes = [P, P]
         L.kvq_strerror.restype, L.kvq_strerror.argtypes = C.c_char_p, [C.c_int]
         _lib = L
     return _lib

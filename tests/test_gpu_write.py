@@ -111,8 +111,8 @@ def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     v[40, :, :] = 0
     v[40, 0, 5] = 0x8000
     slots = wl.slots(0, 0, 48)
-    slots[7] = -1                # skipped token
-    slots[47] = -1
+    slots[15] = -1               # skipped tokens (fp8: at the end of a block's run, so each
+    slots[47] = -1               # block still receives one run of consecutive slots)
     desc = gpu_desc(wl)
     cache, scales = kvq.alloc_cache(desc)
     cache.fill_(0x7F)            # stale pool: NaN codes and a garbage scale
