@@ -99,13 +99,6 @@ __device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
   return r;
 }
 
-template <int D>
-struct Tile {
-  uintx4 k[4][D / 64];  // [token quad u][64-channel half j]
-  uintx4 v[D / 16];     // [channel tile t]
-  float sk, sv;         // this lane's K / V scale (token lane%16 of sub-block lane/16, or the block's)
-};
-
 template <int MODE, int D, int NT>
 __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs p) {
   constexpr int DT = D / 16;
@@ -173,48 +166,46 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
     for (int t = 0; t < DT; ++t) acc[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // block-table entries of the four sub-blocks of a group (wave-uniform)
-  auto fetch_entries = [&](int gidx, int (&ent)[4]) {
+  // per-lane constants of the address arithmetic
+  const int sbk = m16 >> 2;                                   // sub-block this lane reads K from
+  const uint32_t block_stride = 2u * (uint32_t)H * (uint32_t)tile_bytes;  // bytes per cache block
+  const uint32_t k_lane = (uint32_t)h * (uint32_t)tile_bytes + (uint32_t)(m16 & 3) * D + 16u * g4;
+  const uint32_t v_lane = ((uint32_t)H + (uint32_t)h) * (uint32_t)tile_bytes + (uint32_t)m16 * bs;
+  const uint32_t s_block_stride = (MODE == KVQ_INT8_TOKEN_HEAD) ? 2u * H * bs : 2u * H;
+  const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? (uint32_t)h * bs + m16 : (uint32_t)h;
+  const uint32_t s_kv = (MODE == KVQ_INT8_TOKEN_HEAD) ? (uint32_t)H * bs : (uint32_t)H;
+
+  // block-table entries of the sub-blocks this lane reads K and V from
+  auto fetch_entries = [&](int gidx, int& blk_k, int& blk_v) {
     const int pos0 = start + (gidx << 6);
-#pragma unroll
-    for (int sb = 0; sb < 4; ++sb) ent[sb] = table[min(pos0 + 16 * sb, last_sb) >> bs_shift];
+    blk_k = table[min(pos0 + 16 * sbk, last_sb) >> bs_shift];
+    blk_v = table[min(pos0 + 16 * g4, last_sb) >> bs_shift];
   };
 
-  auto load_tile = [&](Tile<D>& t, int gidx, const int (&ent)[4]) {
+  // K codes and both scales of a group; also works out where the group's V codes are
+  auto load_k = [&](uintx4 (&kt)[4][KJ], float& sk, float& sv, const uint8_t*& vbase, int gidx,
+                    int blk_k, int blk_v) {
     const int pos0 = start + (gidx << 6);
-    const int sbk = m16 >> 2;
-    const int blk_k = sbk == 0 ? ent[0] : sbk == 1 ? ent[1] : sbk == 2 ? ent[2] : ent[3];
-    const int blk_v = g4 == 0 ? ent[0] : g4 == 1 ? ent[1] : g4 == 2 ? ent[2] : ent[3];
-    const int off_k = min(pos0 + 16 * sbk, last_sb) & (bs - 1);
-    const int off_v = min(pos0 + 16 * g4, last_sb) & (bs - 1);
-    const uint8_t* kbase = cache + ((size_t)blk_k * 2 * H + h) * tile_bytes +
-                           (size_t)(off_k + (m16 & 3)) * D + 16 * g4;
-    const uint8_t* vbase =
-        cache + (((size_t)blk_v * 2 + 1) * H + h) * tile_bytes + (size_t)m16 * bs + off_v;
+    const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
+    const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
+    const uint8_t* kbase = cache + (size_t)blk_k * block_stride + (off_k * D + k_lane);
+    vbase = cache + (size_t)blk_v * block_stride + (v_lane + off_v);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int j = 0; j < KJ; ++j) t.k[u][j] = *(const uintx4*)(kbase + u * 4 * D + 64 * j);
+      for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * 4 * D + 64 * j);
+    const float* sp = scales + (size_t)blk_v * s_block_stride +
+                      (s_lane + (MODE == KVQ_INT8_TOKEN_HEAD ? off_v : 0u));
+    sk = sp[0];
+    sv = sp[s_kv];
+  };
+  auto load_v = [&](uintx4 (&vt)[DT], const uint8_t* vbase) {
 #pragma unroll
-    for (int tt = 0; tt < DT; ++tt) t.v[tt] = *(const uintx4*)(vbase + (size_t)tt * 16 * bs);
-    if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
-      const size_t si = ((size_t)blk_v * 2 * H + h) * bs + off_v + m16;
-      t.sk = scales[si];
-      t.sv = scales[si + (size_t)H * bs];
-    } else {
-      const size_t si = (size_t)blk_v * 2 * H + h;
-      t.sk = scales[si];
-      t.sv = scales[si + H];
-    }
+    for (int tt = 0; tt < DT; ++tt) vt[tt] = *(const uintx4*)(vbase + (size_t)tt * 16 * bs);
   };
 
-  auto compute_tile = [&](const Tile<D>& t, int gidx) {
-    const int pos0 = start + (gidx << 6);
-    // a group is a "tail" if some row's causal length ends inside it
-    const bool tail = pos0 + 64 > L - p.q_len + 1;
-
-    // ---- S^T = K q^T ----
-    floatx4 S[NT][4];
+  // ---- S^T = K q^T ----
+  auto qk = [&](const uintx4 (&kt)[4][KJ], floatx4 (&S)[NT][4]) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -223,7 +214,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int j = 0; j < KJ; ++j) {
-        const uintx4 raw = t.k[u][j];
+        const uintx4 raw = kt[u][j];
         const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
         const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
 #pragma unroll
@@ -232,22 +223,24 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
           S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, qb[nt][2 * j + 1], S[nt][u], 0, 0, 0);
         }
       }
+  };
 
-    // ---- this lane's scales: logit factor, log2 of the V scale and its inverse ----
-    float skp, lsv, rsv;
-    {
-      const float fold = (MODE == KVQ_FP8E4M3_BLOCK_HEAD) ? 256.0f : 1.0f;  // 2^8 of the f16 trick
-      skp = t.sk * (p.scale_log2 * fold);
-      lsv = __builtin_amdgcn_logf(fmaxf(t.sv * fold, kMinVScale));
-      rsv = __builtin_amdgcn_exp2f(-lsv);
-      if (MODE == KVQ_INT8_TOKEN_HEAD && tail && pos0 + 16 * g4 + m16 >= L) {
-        skp = 0.0f;  // a slot that was never written: its scales are not data
-        lsv = 0.0f;
-        rsv = 0.0f;
-      }
+  // ---- online softmax of a group: S (logits) -> pb (f16 probabilities x V scale) ----
+  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, int gidx, half8 (&pb)[NT][2]) {
+    const int pos0 = start + (gidx << 6);
+    // a group is a "tail" if some row's causal length ends inside it
+    const bool tail = pos0 + 64 > L - p.q_len + 1;
+    // this lane's scales: logit factor, log2 of the V scale and its inverse
+    const float fold = (MODE == KVQ_FP8E4M3_BLOCK_HEAD) ? 256.0f : 1.0f;  // 2^8 of the f16 trick
+    float skp = sk * (p.scale_log2 * fold);
+    float lsv = __builtin_amdgcn_logf(fmaxf(sv * fold, kMinVScale));
+    float rsv = __builtin_amdgcn_exp2f(-lsv);
+    if (MODE == KVQ_INT8_TOKEN_HEAD && tail && pos0 + 16 * g4 + m16 >= L) {
+      skp = 0.0f;  // a slot that was never written: its scales are not data
+      lsv = 0.0f;
+      rsv = 0.0f;
     }
-
-    // ---- logits in base 2, shifted by log2 of the V scale; row maximum ----
+    // logits in base 2, shifted by log2 of the V scale; row maximum
     float mx[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
@@ -269,8 +262,6 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
         mx[nt] = fmaxf(mx[nt], ze);
       }
     });
-
-    half8 pb[NT][2];
     bool rescale = false;
     float alpha[NT];
 #pragma unroll
@@ -299,11 +290,13 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
 #pragma unroll
         for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
     }
+  };
 
-    // ---- acc^T += V^T P^T ----
+  // ---- acc^T += V^T P^T ----
+  auto pv = [&](const uintx4 (&vt)[DT], const half8 (&pb)[NT][2]) {
 #pragma unroll
     for (int tt = 0; tt < DT; ++tt) {
-      const uintx4 raw = t.v[tt];
+      const uintx4 raw = vt[tt];
       const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
       const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
 #pragma unroll
@@ -314,32 +307,42 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
     }
   };
 
-  // ---- main loop: this wave takes groups wave, wave + 4, ...; the loads of a group are
-  // issued before the previous group is computed, and the block-table entries are fetched
-  // one group further ahead so that they never sit in front of the loads ----
-  {
-    Tile<D> ta, tb;
-    int ent[4];
+  // ---- main loop: this wave takes groups wave, wave + 4, ...  K and V each live in one
+  // register buffer: the next group's K codes are requested as soon as QK^T has consumed the
+  // current ones, the next V codes as soon as P.V has, so loads stay in flight behind the
+  // arithmetic; block-table entries are fetched one group further ahead ----
+  if (wave < ngroups) {
+    uintx4 kt[4][KJ], vt[DT];
+    float sk, sv;
+    const uint8_t* vbase;
+    int blk_k, blk_v;
     int g = wave;
-    if (g < ngroups) {
-      const int last = ngroups - 1;  // indices past the end re-read the wave's last group
-      fetch_entries(g, ent);
-      load_tile(ta, g, ent);
-      fetch_entries(min(g + kWaves, last), ent);
-      while (true) {
-        const int g1 = g + kWaves;
-        load_tile(tb, min(g1, last), ent);
-        fetch_entries(min(g1 + kWaves, last), ent);
-        compute_tile(ta, g);
-        if (g1 >= ngroups) break;
-        const int g2 = g1 + kWaves;
-        load_tile(ta, min(g2, last), ent);
-        fetch_entries(min(g2 + kWaves, last), ent);
-        compute_tile(tb, g1);
-        if (g2 >= ngroups) break;
-        g = g2;
-      }
+    // The table entries of a group are requested one group ahead and always before the
+    // loads that follow them in program order (here: both requests first, then the codes), so
+    // that waiting for an entry never waits for code loads issued behind it.
+    {
+      int bk0, bv0;
+      fetch_entries(g, bk0, bv0);
+      fetch_entries(min(g + kWaves, ngroups - 1), blk_k, blk_v);
+      __builtin_amdgcn_sched_barrier(0);
+      load_k(kt, sk, sv, vbase, g, bk0, bv0);
+      load_v(vt, vbase);
     }
+    floatx4 S[NT][4];
+    half8 pb[NT][2];
+    for (; g + kWaves < ngroups; g += kWaves) {  // steady state: a next group exists
+      const int gn = g + kWaves;
+      qk(kt, S);
+      const float sk_cur = sk, sv_cur = sv;
+      load_k(kt, sk, sv, vbase, gn, blk_k, blk_v);
+      fetch_entries(min(gn + kWaves, ngroups - 1), blk_k, blk_v);
+      softmax(S, sk_cur, sv_cur, g, pb);
+      pv(vt, pb);
+      load_v(vt, vbase);
+    }
+    qk(kt, S);  // the wave's last group: nothing left to request
+    softmax(S, sk, sv, g, pb);
+    pv(vt, pb);
   }
 
   // ---- merge the four waves through LDS ----
