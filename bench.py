@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
     ap.add_argument("--chunk", type=int, default=-1, help="split-K chunk (-1 = workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run plain device-to-device copies of this many MiB (a known-size "
+                         "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build measures one GPU only: run with --gpus 1 "
@@ -135,6 +138,20 @@ def main():
     kern_ms = np.array([ev.elapsed_ms(a, b) for a, b in pairs])
     kern_s = float(kern_ms.mean()) * 1e-3
 
+    # read ceiling of the same access pattern: the streaming kernel's loads without its
+    # arithmetic, timed the same way
+    pairs_c = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    L.kvq_profile_read_ceiling(1)
+    for i in range(args.warmup):
+        step(i, write=False)
+    for i in range(args.steps):
+        L.kvq_profile_split_events(pairs_c[i][0], pairs_c[i][1])
+        step(i, write=False)
+    L.kvq_profile_split_events(None, None)
+    L.kvq_profile_read_ceiling(0)
+    torch.cuda.synchronize()
+    ceil_s = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs_c])) * 1e-3
+
     # attention alone (no write), for the record
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -142,6 +159,14 @@ def main():
         step(i, write=False)
     torch.cuda.synchronize()
     attn_s = (time.perf_counter() - t0) / args.steps
+
+    if args.calibrate_copy_mib:
+        src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     result = {
         "metric": "quantized paged decode attention: achieved HBM GB/s",
@@ -155,7 +180,7 @@ def main():
         "config": {"workload": wl.name, "mode": "int8_token_head" if wl.mode == 0 else "fp8e4m3_block_head",
                    "batch": B, "q_len": wl.q_len, "num_q_heads": Hq, "num_kv_heads": wl.num_kv_heads,
                    "head_dim": D, "block_size": wl.block_size, "sum_seq_lens": int(wl.seq_lens.sum()),
-                   "max_seq_len": max_len, "chunk_tokens": chunk or kvq.default_chunk(desc, B, wl.q_len, Hq, max_len),
+                   "max_seq_len": max_len, "chunk_tokens": chunk or "auto (even split over 2048 wavefronts)",
                    "layers_cycled": layers, "step": "kv_quant_write(newest token) + paged_decode_attn"},
         "us_per_layer": step_s * 1e6,
         "pct_of_hbm_peak": 100.0 * alg["total"] / step_s / 1e9 / HBM_PEAK_GBPS,
@@ -166,7 +191,10 @@ def main():
                      "frac": alg["total"] / kern_s / 1e9 / HBM_PEAK_GBPS, "traffic": None,
                      "kernel_us_mean": kern_s * 1e6, "kernel_us_p10": float(np.percentile(kern_ms, 10)) * 1e3,
                      "kernel_us_p90": float(np.percentile(kern_ms, 90)) * 1e3,
-                     "step_us_with_events": step_ev_s * 1e6},
+                     "step_us_with_events": step_ev_s * 1e6,
+                     "read_ceiling_us": ceil_s * 1e6,
+                     "read_ceiling_gbps": alg["total"] / ceil_s / 1e9,
+                     "frac_of_read_ceiling": ceil_s / kern_s},
         "setup_s": setup_s,
     }
 

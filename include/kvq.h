@@ -54,10 +54,13 @@ enum {
  * Logical element (blk, kv, h, off, d): block blk, kv = 0 for K / 1 for V, kv head h,
  * token offset off inside the block, channel d.  Physical byte position in `cache`:
  *     tile  = ((blk * 2 + kv) * num_kv_heads + h) * block_size * head_dim
- *     K:  tile + off * head_dim + d          (token-major: a token's row is contiguous)
- *     V:  tile + d * block_size + off        (channel-major: the tokens of a channel are
- *                                             contiguous, which is the order the P.V matrix
- *                                             instruction consumes)
+ *     K:  tile + (off/4) * 4*head_dim + (d/16) * 64 + (off%4) * 16 + d%16
+ *         (quads of 4 tokens; inside a quad: 16-channel slices x 4 tokens x 16 channels)
+ *     V:  tile + (off/16) * 16*head_dim + d * 16 + off%16
+ *         (sub-blocks of 16 tokens; inside one: channel-major rows of 16 tokens, the order
+ *          the P.V matrix instruction consumes)
+ * Both orders make the 16-byte piece one lane feeds to a matrix instruction contiguous and
+ * let the four lanes of a quad read 64 contiguous bytes.
  * kvq_cache_to_canonical / kvq_cache_from_canonical convert to and from the plain
  * [num_blocks][2][num_kv_heads][block_size][head_dim] order.
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
@@ -98,14 +101,8 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
                    int32_t num_tokens, void* cache, float* scales,
                    const kvq_cache_desc_t* desc, void* stream);
 
-/* Split-K chunk (in tokens, a multiple of 64) that paged_decode_attn uses when its
- * chunk_tokens argument is 0.  Host only; returns 0 on invalid arguments. */
-int32_t paged_decode_attn_default_chunk(const kvq_cache_desc_t* desc, int32_t batch,
-                                        int32_t q_len, int32_t num_q_heads,
-                                        int32_t max_seq_len);
-
 /* Bytes of device workspace paged_decode_attn needs for these arguments (split-K partial
- * results).  Host only; returns 0 on invalid arguments or when nothing is needed. */
+ * results).  Host only; returns 0 on invalid arguments. */
 size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
                                          int32_t q_len, int32_t num_q_heads,
                                          int32_t max_seq_len, int32_t chunk_tokens);
@@ -121,13 +118,16 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
  *                 sequence's last block are never dereferenced
  *   seq_lens      device, int32 [batch], read only
  *   max_seq_len   host upper bound on seq_lens (sizes the launch grid)
- *   chunk_tokens  split-K chunk in tokens, a multiple of 64; 0 = library default
+ *   chunk_tokens  split-K granule: tokens of context per wavefront range, a multiple of 64;
+ *                 0 = divide the work evenly over the wavefronts the GPU holds at once
  *   out           device, f32 [batch*q_len][num_q_heads][head_dim], written
  *   workspace     device, >= paged_decode_attn_workspace_bytes(...) bytes, 16-byte aligned;
  *                 contents before and after the call are unspecified
- * The context of a sequence is cut into chunks; each chunk's workgroup leaves an
+ * Split-K: the 64-token groups of all (sequence, kv head) pairs form one flat list that is
+ * cut into equal ranges, one per wavefront; a range that ends inside a pair leaves an
  * unnormalised partial (running max, sum, accumulator) in the workspace and a second kernel
- * merges them by the log-sum-exp rule.  Results are deterministic run to run (no atomics).
+ * merges a pair's partials by the log-sum-exp rule.  Results are deterministic run to run
+ * (no atomics).
  * Requires 1 <= q_len <= 16 and num_q_heads % num_kv_heads == 0. */
 int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       const kvq_cache_desc_t* desc, const int32_t* block_tables,
@@ -150,6 +150,13 @@ int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache
  * immediately behind it, so that a benchmark can time that kernel alone.  Pass NULL, NULL to
  * switch the hook off (the initial state).  Process-global and not thread-safe. */
 void kvq_profile_split_events(void* before, void* after);
+
+/* Measurement hook, not part of the path: while switched on, paged_decode_attn launches a
+ * read-only twin of its streaming kernel (same work split, addresses, load instructions and
+ * software pipeline, the arithmetic replaced by an XOR of the loaded words) and skips the
+ * reduce; `out` is not written and the workspace is scribbled on.  Its duration is the
+ * read ceiling of this access pattern on the machine at hand.  Process-global; off initially. */
+void kvq_profile_read_ceiling(int on);
 
 /* Static, never-NULL description of a return code. */
 const char* kvq_strerror(int code);

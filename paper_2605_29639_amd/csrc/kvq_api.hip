@@ -22,6 +22,8 @@ bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   return true;
 }
 
+constexpr int64_t kAutoWaves = 2048;
+
 int ilog2(int x) {
   int s = 0;
   while ((1 << s) < x) ++s;
@@ -42,22 +44,29 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   plan->rows = group * q_len;
   plan->row_tiles = plan->rows <= 16 ? 1 : 2;
   plan->num_row_groups = (plan->rows + 16 * plan->row_tiles - 1) / (16 * plan->row_tiles);
-  int chunk = chunk_tokens;
-  if (chunk == 0) {
-    // Aim at about eight workgroups per compute unit (256 CUs) for a batch whose mean length
-    // is ~60 % of max_seq_len, with chunks between 256 and 4096 tokens (multiples of 256: four
-    // wavefronts x 64-token groups).
-    const double pairs = (double)batch * d->num_kv_heads * plan->num_row_groups;
-    const double want = 0.6 * (double)max_seq_len * pairs / 2048.0;
-    chunk = (int)(want / 256.0) * 256;
-    if (chunk < 256) chunk = 256;
-    if (chunk > 4096) chunk = 4096;
+  plan->pairs_per_seq = d->num_kv_heads * plan->num_row_groups;
+  // the flat list of 64-token groups can be no longer than this
+  const int64_t flat_max =
+      (int64_t)batch * ((max_seq_len + 63) / 64) * plan->pairs_per_seq;
+  if (flat_max > 0x7FFFFFFF) {
+    *err = KVQ_E_BAD_SHAPE;
+    return false;
   }
-  plan->chunk_tokens = chunk;
-  plan->num_chunks = max_seq_len > 0 ? (max_seq_len + chunk - 1) / chunk : 1;
-  const size_t items = (size_t)batch * d->num_kv_heads * plan->num_chunks * plan->rows;
-  plan->acc_floats = plan->num_chunks > 1 ? items * d->head_dim : 0;
-  plan->ml_floats = plan->num_chunks > 1 ? items * 2 : 0;
+  if (chunk_tokens == 0) {
+    // even split over as many wavefronts as an MI355X keeps resident at this kernel's
+    // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
+    plan->range_groups = 0;
+    plan->num_waves = (int32_t)(flat_max < kAutoWaves ? flat_max : kAutoWaves);
+  } else {
+    plan->range_groups = chunk_tokens / 64;
+    plan->num_waves = (int32_t)((flat_max + plan->range_groups - 1) / plan->range_groups);
+  }
+  if (plan->num_waves < 1) plan->num_waves = 1;
+  // one partial per (wavefront range, pair) crossing: numbered wave + pair index
+  const size_t slots = (size_t)plan->num_waves + (size_t)batch * plan->pairs_per_seq;
+  const size_t rows = slots * 16 * plan->row_tiles;
+  plan->acc_floats = rows * d->head_dim;
+  plan->ml_floats = rows * 2;
   return true;
 }
 
@@ -92,15 +101,6 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
-int32_t paged_decode_attn_default_chunk(const kvq_cache_desc_t* desc, int32_t batch,
-                                        int32_t q_len, int32_t num_q_heads,
-                                        int32_t max_seq_len) {
-  kvq::AttnPlan plan;
-  int err;
-  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, 0, &plan, &err)) return 0;
-  return plan.chunk_tokens;
-}
-
 size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
                                          int32_t q_len, int32_t num_q_heads,
                                          int32_t max_seq_len, int32_t chunk_tokens) {
@@ -133,8 +133,6 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
     if (workspace_bytes < need) return KVQ_E_WORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return KVQ_E_BAD_SHAPE;
   }
-  const size_t grid = (size_t)batch * plan.num_row_groups * desc->num_kv_heads * plan.num_chunks;
-  if (grid > 0x7FFFFFFFull) return KVQ_E_BAD_SHAPE;
 
   kvq::AttnArgs a;
   a.q = (const uint16_t*)q;
@@ -156,10 +154,11 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   a.bs_shift = ilog2(desc->block_size);
   a.head_dim = desc->head_dim;
   a.mode = desc->mode;
-  a.chunk_tokens = plan.chunk_tokens;
-  a.num_chunks = plan.num_chunks;
   a.row_tiles = plan.row_tiles;
   a.num_row_groups = plan.num_row_groups;
+  a.pairs_per_seq = plan.pairs_per_seq;
+  a.range_groups = plan.range_groups;
+  a.num_waves = plan.num_waves;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
@@ -190,6 +189,8 @@ int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache
 void kvq_profile_split_events(void* before, void* after) {
   kvq::set_profile_events((hipEvent_t)before, (hipEvent_t)after);
 }
+
+void kvq_profile_read_ceiling(int on) { kvq::set_read_ceiling(on != 0); }
 
 const char* kvq_strerror(int code) {
   switch (code) {

@@ -1,15 +1,24 @@
 // paged_decode_attn kernels (gfx950): decode attention (Section 2) over the quantized paged
-// cache (Section 7.2.2).  Two launches: a split kernel over (sequence, kv head, chunk) that
-// streams K/V codes from HBM once, and a small log-sum-exp reduce over the chunks.
+// cache (Section 7.2.2).  Two launches: a streaming kernel that reads every K/V code from HBM
+// once, and a small log-sum-exp reduce over the pieces a (sequence, kv head) was cut into.
 //
-// Split kernel, per 64-lane wavefront and per 64-token group (four 16-token sub-blocks):
+// Work split.  All 64-token groups of all (sequence, kv head[, row group]) pairs form one flat
+// list (sequence-major).  It is cut into equal ranges, one per wavefront (one wavefront = one
+// workgroup), so every wavefront streams the same number of bytes whatever the mix of
+// sequence lengths; a range that crosses from one pair into the next leaves a partial
+// (max, sum, accumulator) for the pair it leaves.  A pair that lies inside one range is
+// written to `out` directly.  Partial number (wave + pair index) is unique because ranges and
+// pairs are both ordered cuts of the same list.
+//
+// Per wavefront and 64-token group (four 16-token sub-blocks):
 //   * K codes: lane (m = lane%16, c = lane/16) loads 16-byte pieces of token
-//     (sub-block m/4, token 4u + m%4) for u = 0..3, channels [64j + 16c, +16).
+//     (sub-block m/4, token 4u + m%4) for u = 0..3, channels [64j + 16c, +16); the cache
+//     keeps K in quads of 4 tokens so that the 4 lanes of a quad read 64 contiguous bytes.
 //     That is directly the A operand (M = 16 tokens, K = 32 channels per instruction) of
-//     v_mfma_f32_16x16x32_f16; q (f16, loaded once) is the B operand with the G*q_len query
-//     rows that share the kv head as the N columns.  The accumulator then holds, in lane
+//     v_mfma_f32_16x16x32_f16; q (f16) is the B operand with the G*q_len query rows that share
+//     the kv head as the N columns.  The accumulator then holds, in lane
 //     (row n = lane%16, g = lane/16), the logits of the 16 tokens of sub-block g.
-//   * V codes are stored channel-major, so lane (m, g) loads 16 bytes = 16 tokens of
+//   * V codes are stored channel-major per 16-token sub-block, so lane (m, g) loads 16 bytes = 16 tokens of
 //     sub-block g for channel 16t + m: the A operand (M = 16 channels, K = tokens) of the
 //     P.V instruction, whose B operand is exactly the lane's own 16 probabilities.  No
 //     shuffle, LDS transpose or re-layout sits between the two contractions.
@@ -19,9 +28,8 @@
 //   * Online softmax in base 2.  The running reference m is the maximum of
 //     (logit + log2 V-scale), so the f16 probabilities p*sV stay in (0, 2^10] whatever the
 //     magnitude of V; the plain softmax denominator is recovered as sum(P * 2^-lsv).
-//   * The four wavefronts of a workgroup take the chunk's groups round-robin and merge their
-//     (m, l, acc) through LDS; the workgroup writes one partial, or the final rows when the
-//     sequence has a single chunk.
+//   * K and V each live in one register buffer: the next group's K codes are requested as
+//     soon as QK^T has consumed the current ones, the next V codes as soon as P.V has.
 #include <utility>
 
 #include "kvq_internal.h"
@@ -36,7 +44,6 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;
 constexpr float kPOffset = 10.0f;   // probabilities are scaled by 2^10 (cancels in acc / l)
 constexpr float kMinVScale = 7.888609052210118e-31f;  // 2^-100
 
@@ -99,113 +106,214 @@ __device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
   return r;
 }
 
-template <int MODE, int D, int NT>
-__global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs p) {
+// Position in the flat list of groups: sequence b, pair pr inside the sequence
+// (pr = kv head * row groups + row group), group g of ng, sequence length L.  Wave-uniform.
+struct Cursor {
+  int b, pr, g, ng, L;
+};
+
+__device__ inline int wave_sum(int v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+__device__ inline int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    const int o = __shfl_up(v, s, 64);
+    v += (lane >= s) ? o : 0;
+  }
+  return v;
+}
+__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// groups per wavefront range: the caller's, or an even split of the flat list over the grid
+__device__ inline int range_groups(int requested, int flat_groups, int num_waves) {
+  return requested > 0 ? requested : max(1, (flat_groups + num_waves - 1) / num_waves);
+}
+
+// CEIL = true builds the read-ceiling twin used for measurement only: same ranges, same
+// addresses, same load instructions and the same pipeline, but the arithmetic is replaced by
+// an XOR of the loaded words (one dword per wavefront is stored so that the loads stay).
+template <int MODE, int D, int NT, bool CEIL>
+__global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   constexpr int DT = D / 16;
   constexpr int KJ = D / 64;
   constexpr int KS = D / 32;  // MFMA steps over the channels
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x;
   const int m16 = lane & 15, g4 = lane >> 4;
+  const int w = blockIdx.x;
+  const int B = p.batch, Hp = p.pairs_per_seq;
+  const int32_t* __restrict__ seq_lens = p.seq_lens;
 
-  int id = blockIdx.x;
-  const int c = id % p.num_chunks;
-  id /= p.num_chunks;
-  const int h = id % p.num_kv_heads;
-  id /= p.num_kv_heads;
-  const int rg = id % p.num_row_groups;
-  const int b = id / p.num_row_groups;
+  // ---- this wave's range [f0, f1) of the flat list, and where it starts ----
+  int total = 0;
+  for (int k0 = 0; k0 < B; k0 += 64) {
+    const int i = k0 + lane;
+    total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
+  }
+  const int flat = uni(wave_sum(total)) * Hp;
+  const int R = range_groups(p.range_groups, flat, p.num_waves);
+  const int f0 = w * R;
+  if (f0 >= flat) return;
+  const int f1 = min(f0 + R, flat);
 
-  const int L = p.seq_lens[b];
-  const int start = c * p.chunk_tokens;
-  if (start >= L) return;
-  const int end = min(start + p.chunk_tokens, L);
-  const int ngroups = (end - start + 63) >> 6;
-  const int last_sb = ((L - 1) >> 4) << 4;  // first position of the last 16-token sub-block
-  const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads;
-  const int32_t* __restrict__ table = p.block_tables + (size_t)b * p.max_blocks_per_seq;
+  Cursor cur;
+  {
+    int base = 0, b0 = 0, before = 0, L0 = 0;
+    for (int k0 = 0; k0 < B; k0 += 64) {
+      const int i = k0 + lane;
+      const int Li = (i < B) ? seq_lens[i] : 0;
+      const int incl = wave_incl_scan((Li + 63) >> 6, lane);
+      const int cnt = __popcll(__ballot((base + incl) * Hp <= f0));  // sequences wholly before f0
+      if (cnt < 64) {
+        b0 = k0 + cnt;
+        before = base + (cnt ? __shfl(incl, cnt - 1, 64) : 0);
+        L0 = __shfl(Li, cnt, 64);
+        break;
+      }
+      base += __shfl(incl, 63, 64);
+    }
+    cur.b = uni(b0);
+    cur.L = uni(L0);
+    cur.ng = (cur.L + 63) >> 6;
+    const int local = f0 - uni(before) * Hp;
+    cur.pr = local / cur.ng;
+    cur.g = local - cur.pr * cur.ng;
+  }
+  auto advance = [&](Cursor& c) {
+    if (++c.g < c.ng) return;
+    c.g = 0;
+    if (++c.pr < Hp) return;
+    c.pr = 0;
+    do {
+      ++c.b;
+      c.L = (c.b < B) ? seq_lens[c.b] : 64;
+      c.ng = (c.L + 63) >> 6;
+    } while (c.b < B && c.ng == 0);
+  };
+
+  const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads, NRG = p.num_row_groups;
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
-  const size_t tile_bytes = (size_t)bs * D;
-
-  // ---- q: B operand of the QK^T instruction, and each row's causal length ----
-  half8 qb[NT][KS];
-  int nrow[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int r = (rg * NT + nt) * 16 + m16;
-    const bool live = r < p.rows;
-    const int j = live ? r / p.group : 0;
-    const int gi = live ? r - j * p.group : 0;
-    nrow[nt] = live ? L - p.q_len + j + 1 : L;
-    const uint16_t* qrow =
-        p.q + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * p.group + gi) * D;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const int d0 = 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
-      const uintx4 raw = *(const uintx4*)(qrow + d0);
-      half8 x;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        x[2 * e] = (_Float16)__uint_as_float(raw[e] << 16);
-        x[2 * e + 1] = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qb[nt][s][e] = live ? x[e] : (_Float16)0.0f;
-    }
-  }
-
-  // ---- running state ----
-  floatx4 acc[NT][DT];
-  float m_run[NT], l_run[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    m_run[nt] = -INFINITY;
-    l_run[nt] = 0.0f;
-#pragma unroll
-    for (int t = 0; t < DT; ++t) acc[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  // per-lane constants of the address arithmetic
-  const int sbk = m16 >> 2;                                   // sub-block this lane reads K from
-  const uint32_t block_stride = 2u * (uint32_t)H * (uint32_t)tile_bytes;  // bytes per cache block
-  const uint32_t k_lane = (uint32_t)h * (uint32_t)tile_bytes + (uint32_t)(m16 & 3) * D + 16u * g4;
-  const uint32_t v_lane = ((uint32_t)H + (uint32_t)h) * (uint32_t)tile_bytes + (uint32_t)m16 * bs;
+  const uint32_t tile_bytes = (uint32_t)bs * D;
+  const int sbk = m16 >> 2;  // sub-block this lane reads K from
+  const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;  // bytes per cache block
+  const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3);  // inside a 4-token quad
+  const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16;  // inside a 16-token sub-block
   const uint32_t s_block_stride = (MODE == KVQ_INT8_TOKEN_HEAD) ? 2u * H * bs : 2u * H;
-  const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? (uint32_t)h * bs + m16 : (uint32_t)h;
   const uint32_t s_kv = (MODE == KVQ_INT8_TOKEN_HEAD) ? (uint32_t)H * bs : (uint32_t)H;
 
   // block-table entries of the sub-blocks this lane reads K and V from
-  auto fetch_entries = [&](int gidx, int& blk_k, int& blk_v) {
-    const int pos0 = start + (gidx << 6);
+  auto fetch_entries = [&](const Cursor& c, int& blk_k, int& blk_v) {
+    const int32_t* __restrict__ table = p.block_tables + (size_t)c.b * p.max_blocks_per_seq;
+    const int pos0 = c.g << 6, last_sb = ((c.L - 1) >> 4) << 4;
     blk_k = table[min(pos0 + 16 * sbk, last_sb) >> bs_shift];
     blk_v = table[min(pos0 + 16 * g4, last_sb) >> bs_shift];
   };
 
   // K codes and both scales of a group; also works out where the group's V codes are
-  auto load_k = [&](uintx4 (&kt)[4][KJ], float& sk, float& sv, const uint8_t*& vbase, int gidx,
-                    int blk_k, int blk_v) {
-    const int pos0 = start + (gidx << 6);
+  auto load_k = [&](uintx4 (&kt)[4][KJ], float& sk, float& sv, const uint8_t*& vbase,
+                    const Cursor& c, int blk_k, int blk_v) {
+    const int pos0 = c.g << 6, last_sb = ((c.L - 1) >> 4) << 4;
+    const uint32_t h = (uint32_t)(c.pr / NRG);
     const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
     const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
-    const uint8_t* kbase = cache + (size_t)blk_k * block_stride + (off_k * D + k_lane);
-    vbase = cache + (size_t)blk_v * block_stride + (v_lane + off_v);
+    const uint8_t* kbase =
+        cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * D + k_lane);
+    vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * D);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * 4 * D + 64 * j);
-    const float* sp = scales + (size_t)blk_v * s_block_stride +
-                      (s_lane + (MODE == KVQ_INT8_TOKEN_HEAD ? off_v : 0u));
+      for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * 4 * D + 256 * j);
+    const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? h * bs + m16 + off_v : h;
+    const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
     sk = sp[0];
     sv = sp[s_kv];
   };
   auto load_v = [&](uintx4 (&vt)[DT], const uint8_t* vbase) {
 #pragma unroll
-    for (int tt = 0; tt < DT; ++tt) vt[tt] = *(const uintx4*)(vbase + (size_t)tt * 16 * bs);
+    for (int tt = 0; tt < DT; ++tt) vt[tt] = *(const uintx4*)(vbase + 256 * tt);
+  };
+
+  // ---- per-pair state: q as the B operand of QK^T, each row's causal length, the running
+  // maximum / sum / accumulator ----
+  half8 qb[NT][KS];
+  int nrow[NT];
+  floatx4 acc[NT][DT];
+  float m_run[NT], l_run[NT];
+  uint32_t ceil_x = 0;
+  auto begin_pair = [&](const Cursor& c) {
+    if constexpr (CEIL) return;
+    const int h = c.pr / NRG, rg = c.pr - h * NRG;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int r = (rg * NT + nt) * 16 + m16;
+      const bool live = r < p.rows;
+      const int j = live ? r / p.group : 0;
+      const int gi = live ? r - j * p.group : 0;
+      nrow[nt] = live ? c.L - p.q_len + j + 1 : c.L;
+      const uint16_t* qrow =
+          p.q + (((size_t)c.b * p.q_len + j) * p.num_q_heads + (size_t)h * p.group + gi) * D;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int d0 = 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+        const uintx4 raw = *(const uintx4*)(qrow + d0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
+          const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
+          qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
+          qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+        }
+      }
+      m_run[nt] = -INFINITY;
+      l_run[nt] = 0.0f;
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt) acc[nt][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+
+  // leave a pair: final rows if this wave saw all of it, else a partial
+  auto end_pair = [&](const Cursor& c, bool whole) {
+    if constexpr (CEIL) return;
+    const int h = c.pr / NRG, rg = c.pr - h * NRG;
+    const size_t slot = (size_t)w + (size_t)c.b * Hp + c.pr;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const float l = xor16_sum(l_run[nt]);
+      const int rl = nt * 16 + m16;
+      const int r = rg * NT * 16 + rl;
+      if (r >= p.rows) continue;
+      if (whole) {
+        const int j = r / p.group, gi = r - j * p.group;
+        float* orow =
+            p.out + (((size_t)c.b * p.q_len + j) * p.num_q_heads + (size_t)h * p.group + gi) * D;
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int tt = 0; tt < DT; ++tt) *(floatx4*)(orow + 16 * tt + 4 * g4) = acc[nt][tt] * inv;
+      } else {
+        const size_t row = slot * (NT * 16) + rl;
+        float* arow = p.ws_acc + row * D;
+#pragma unroll
+        for (int tt = 0; tt < DT; ++tt) *(floatx4*)(arow + 16 * tt + 4 * g4) = acc[nt][tt];
+        if (g4 == 0) {
+          p.ws_ml[row * 2] = m_run[nt];
+          p.ws_ml[row * 2 + 1] = l;
+        }
+      }
+    }
   };
 
   // ---- S^T = K q^T ----
   auto qk = [&](const uintx4 (&kt)[4][KJ], floatx4 (&S)[NT][4]) {
+    if constexpr (CEIL) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) ceil_x ^= kt[u][j][0] ^ kt[u][j][1] ^ kt[u][j][2] ^ kt[u][j][3];
+      return;
+    }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -226,8 +334,13 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
   };
 
   // ---- online softmax of a group: S (logits) -> pb (f16 probabilities x V scale) ----
-  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, int gidx, half8 (&pb)[NT][2]) {
-    const int pos0 = start + (gidx << 6);
+  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
+                     half8 (&pb)[NT][2]) {
+    if constexpr (CEIL) {
+      ceil_x ^= __float_as_uint(sk) ^ __float_as_uint(sv);
+      return;
+    }
+    const int pos0 = c.g << 6, L = c.L;
     // a group is a "tail" if some row's causal length ends inside it
     const bool tail = pos0 + 64 > L - p.q_len + 1;
     // this lane's scales: logit factor, log2 of the V scale and its inverse
@@ -294,6 +407,11 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
 
   // ---- acc^T += V^T P^T ----
   auto pv = [&](const uintx4 (&vt)[DT], const half8 (&pb)[NT][2]) {
+    if constexpr (CEIL) {
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt) ceil_x ^= vt[tt][0] ^ vt[tt][1] ^ vt[tt][2] ^ vt[tt][3];
+      return;
+    }
 #pragma unroll
     for (int tt = 0; tt < DT; ++tt) {
       const uintx4 raw = vt[tt];
@@ -307,115 +425,57 @@ __global__ __launch_bounds__(kWaves * 64) void attn_split_kernel(const AttnArgs 
     }
   };
 
-  // ---- main loop: this wave takes groups wave, wave + 4, ...  K and V each live in one
-  // register buffer: the next group's K codes are requested as soon as QK^T has consumed the
-  // current ones, the next V codes as soon as P.V has, so loads stay in flight behind the
-  // arithmetic; block-table entries are fetched one group further ahead ----
-  if (wave < ngroups) {
-    uintx4 kt[4][KJ], vt[DT];
-    float sk, sv;
-    const uint8_t* vbase;
-    int blk_k, blk_v;
-    int g = wave;
-    // The table entries of a group are requested one group ahead and always before the
-    // loads that follow them in program order (here: both requests first, then the codes), so
-    // that waiting for an entry never waits for code loads issued behind it.
-    {
-      int bk0, bv0;
-      fetch_entries(g, bk0, bv0);
-      fetch_entries(min(g + kWaves, ngroups - 1), blk_k, blk_v);
-      __builtin_amdgcn_sched_barrier(0);
-      load_k(kt, sk, sv, vbase, g, bk0, bv0);
-      load_v(vt, vbase);
-    }
-    floatx4 S[NT][4];
-    half8 pb[NT][2];
-    for (; g + kWaves < ngroups; g += kWaves) {  // steady state: a next group exists
-      const int gn = g + kWaves;
-      qk(kt, S);
-      const float sk_cur = sk, sv_cur = sv;
-      load_k(kt, sk, sv, vbase, gn, blk_k, blk_v);
-      fetch_entries(min(gn + kWaves, ngroups - 1), blk_k, blk_v);
-      softmax(S, sk_cur, sv_cur, g, pb);
-      pv(vt, pb);
-      load_v(vt, vbase);
-    }
-    qk(kt, S);  // the wave's last group: nothing left to request
-    softmax(S, sk, sv, g, pb);
+  // ---- main loop over the range.  Three cursors: cur (being computed), nxt (its codes are
+  // being loaded), nn (its block-table entries are being fetched).  The table entries of a
+  // group are always requested before the code loads that follow them in program order, so
+  // waiting for an entry never waits for code loads issued behind it. ----
+  uintx4 kt[4][KJ], vt[DT];
+  float sk, sv;
+  const uint8_t* vbase;
+  int blk_k, blk_v;
+  floatx4 S[NT][4];
+  half8 pb[NT][2];
+  const int count = f1 - f0;
+  Cursor nxt = cur;
+  if (count > 1) advance(nxt);
+  Cursor nn = nxt;
+  {
+    int bk0, bv0;
+    fetch_entries(cur, bk0, bv0);
+    fetch_entries(nxt, blk_k, blk_v);
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(kt, sk, sv, vbase, cur, bk0, bv0);
+    load_v(vt, vbase);
+  }
+  begin_pair(cur);
+  bool from_start = cur.g == 0;  // did this wave see the current pair from its first group
+  for (int i = 0; i + 1 < count; ++i) {  // steady state: a next group exists
+    qk(kt, S);
+    const float sk_cur = sk, sv_cur = sv;
+    load_k(kt, sk, sv, vbase, nxt, blk_k, blk_v);
+    if (i + 2 < count) advance(nn);
+    fetch_entries(nn, blk_k, blk_v);
+    softmax(S, sk_cur, sv_cur, cur, pb);
     pv(vt, pb);
-  }
-
-  // ---- merge the four waves through LDS ----
-  constexpr int RS = D + 4;  // padded row stride (floats)
-  __shared__ float sm_m[kWaves][NT * 16];
-  __shared__ float sm_l[kWaves][NT * 16];
-  __shared__ float sm_acc[kWaves - 1][NT * 16][RS];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    l_run[nt] = xor16_sum(l_run[nt]);
-    if (g4 == 0) {
-      sm_m[wave][nt * 16 + m16] = m_run[nt];
-      sm_l[wave][nt * 16 + m16] = l_run[nt];
+    load_v(vt, vbase);
+    if (nxt.g == 0) {  // the next group opens another pair
+      end_pair(cur, from_start);
+      begin_pair(nxt);
+      from_start = true;
     }
+    cur = nxt;
+    nxt = nn;
   }
-  __syncthreads();
-  float m_all[NT], l_all[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    float mm = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, sm_m[w][nt * 16 + m16]);
-    const float mm_safe = (mm == -INFINITY) ? 0.0f : mm;
-    float ll = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w)
-      ll += sm_l[w][nt * 16 + m16] * __builtin_amdgcn_exp2f(sm_m[w][nt * 16 + m16] - mm_safe);
-    const float f = __builtin_amdgcn_exp2f(m_run[nt] - mm_safe);
-    m_all[nt] = mm;
-    l_all[nt] = ll;
-#pragma unroll
-    for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= f;
-    if (wave > 0) {
-#pragma unroll
-      for (int tt = 0; tt < DT; ++tt)
-        *(floatx4*)&sm_acc[wave - 1][nt * 16 + m16][16 * tt + 4 * g4] = acc[nt][tt];
-    }
-  }
-  __syncthreads();
-  if (wave != 0) return;
-
-  const int chunks_of_seq = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int r = (rg * NT + nt) * 16 + m16;
-#pragma unroll
-    for (int tt = 0; tt < DT; ++tt)
-#pragma unroll
-      for (int w = 0; w < kWaves - 1; ++w)
-        acc[nt][tt] += *(const floatx4*)&sm_acc[w][nt * 16 + m16][16 * tt + 4 * g4];
-    if (r >= p.rows) continue;
-    if (chunks_of_seq == 1) {
-      const int j = r / p.group, gi = r - j * p.group;
-      float* orow =
-          p.out + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * p.group + gi) * D;
-      const float inv = 1.0f / l_all[nt];
-#pragma unroll
-      for (int tt = 0; tt < DT; ++tt) *(floatx4*)(orow + 16 * tt + 4 * g4) = acc[nt][tt] * inv;
-    } else {
-      const size_t item = (((size_t)b * H + h) * p.num_chunks + c) * p.rows + r;
-      float* arow = p.ws_acc + item * D;
-#pragma unroll
-      for (int tt = 0; tt < DT; ++tt) *(floatx4*)(arow + 16 * tt + 4 * g4) = acc[nt][tt];
-      if (g4 == 0) {
-        p.ws_ml[item * 2] = m_all[nt];
-        p.ws_ml[item * 2 + 1] = l_all[nt];
-      }
-    }
-  }
+  qk(kt, S);  // the range's last group: nothing left to request
+  softmax(S, sk, sv, cur, pb);
+  pv(vt, pb);
+  end_pair(cur, from_start && cur.g == cur.ng - 1);
+  if constexpr (CEIL) p.ws_ml[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
 
-// ---- log-sum-exp merge of the chunk partials: one workgroup per (sequence, query token,
-// query head), one thread per channel ----
+// ---- log-sum-exp merge of a pair's partials: one workgroup per (sequence, query token,
+// query head), one thread per channel.  It recomputes where the pair lies in the flat list
+// and which wavefront ranges cover it. ----
 template <int D>
 __global__ __launch_bounds__(D) void attn_reduce_kernel(const AttnArgs p) {
   int id = blockIdx.x;
@@ -423,35 +483,67 @@ __global__ __launch_bounds__(D) void attn_reduce_kernel(const AttnArgs p) {
   id /= p.num_q_heads;
   const int j = id % p.q_len;
   const int b = id / p.q_len;
-  const int L = p.seq_lens[b];
-  const int nc = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-  if (nc <= 1) return;  // the split kernel already wrote the final rows
+  const int d = threadIdx.x;
+  __shared__ int sm[2][D / 64];
+  int before = 0, total = 0;
+  for (int i = d; i < p.batch; i += D) {
+    const int n = (p.seq_lens[i] + 63) >> 6;
+    total += n;
+    before += (i < b) ? n : 0;
+  }
+  before = wave_sum(before);
+  total = wave_sum(total);
+  if ((d & 63) == 0) {
+    sm[0][d >> 6] = before;
+    sm[1][d >> 6] = total;
+  }
+  __syncthreads();
+  before = 0;
+  total = 0;
+#pragma unroll
+  for (int k = 0; k < D / 64; ++k) {
+    before += sm[0][k];
+    total += sm[1][k];
+  }
+  const int Hp = p.pairs_per_seq;
+  const int R = range_groups(p.range_groups, total * Hp, p.num_waves);
+  const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
   const int r = j * p.group + (hq - h * p.group);
-  const int d = threadIdx.x;
-  const size_t item0 = (((size_t)b * p.num_kv_heads + h) * p.num_chunks) * p.rows + r;
+  const int rg = r / rt, rl = r - rg * rt;
+  const int pr = h * p.num_row_groups + rg;
+  const int ng = (p.seq_lens[b] + 63) >> 6;
+  const int start = before * Hp + pr * ng;
+  const int w_first = start / R, w_last = (start + ng - 1) / R;
+  if (w_first == w_last) return;  // the streaming kernel already wrote the final rows
+  const size_t pair = (size_t)b * Hp + pr;
   float M = -INFINITY;
-  for (int c = 0; c < nc; ++c) M = fmaxf(M, p.ws_ml[(item0 + (size_t)c * p.rows) * 2]);
+  for (int w = w_first; w <= w_last; ++w)
+    M = fmaxf(M, p.ws_ml[(((size_t)w + pair) * rt + rl) * 2]);
   float num = 0.0f, den = 0.0f;
-  for (int c = 0; c < nc; ++c) {
-    const size_t item = item0 + (size_t)c * p.rows;
-    const float w = __builtin_amdgcn_exp2f(p.ws_ml[item * 2] - M);
-    num += w * p.ws_acc[item * D + d];
-    den += w * p.ws_ml[item * 2 + 1];
+  for (int w = w_first; w <= w_last; ++w) {
+    const size_t row = ((size_t)w + pair) * rt + rl;
+    const float wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
+    num += wgt * p.ws_acc[row * D + d];
+    den += wgt * p.ws_ml[row * 2 + 1];
   }
   p.out[(((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + d] = num / den;
 }
 
-// measurement hook: events recorded around the split kernel (see kvq_profile_split_events)
+// measurement hooks: events recorded around the streaming kernel (kvq_profile_split_events)
+// and the read-ceiling twin in place of the real kernel (kvq_profile_read_ceiling)
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+bool g_read_ceiling = false;
 
 template <int MODE, int D>
-hipError_t launch_split(const AttnArgs& a, unsigned grid, hipStream_t stream) {
+hipError_t launch_stream(const AttnArgs& a, hipStream_t stream) {
   if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
-  if (a.row_tiles == 1)
-    hipLaunchKernelGGL((attn_split_kernel<MODE, D, 1>), dim3(grid), dim3(kWaves * 64), 0, stream, a);
+  if (g_read_ceiling)
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  else if (a.row_tiles == 1)
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else
-    hipLaunchKernelGGL((attn_split_kernel<MODE, D, 2>), dim3(grid), dim3(kWaves * 64), 0, stream, a);
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false>), dim3(a.num_waves), dim3(64), 0, stream, a);
   const hipError_t e = hipGetLastError();
   if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
   return e;
@@ -464,26 +556,23 @@ void set_profile_events(hipEvent_t before, hipEvent_t after) {
   g_ev_after = after;
 }
 
+void set_read_ceiling(bool on) { g_read_ceiling = on; }
+
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
-  const unsigned grid =
-      (unsigned)((size_t)a.batch * a.num_row_groups * a.num_kv_heads * a.num_chunks);
   hipError_t e;
   if (a.mode == KVQ_INT8_TOKEN_HEAD)
-    e = a.head_dim == 128 ? launch_split<KVQ_INT8_TOKEN_HEAD, 128>(a, grid, stream)
-                          : launch_split<KVQ_INT8_TOKEN_HEAD, 64>(a, grid, stream);
+    e = a.head_dim == 128 ? launch_stream<KVQ_INT8_TOKEN_HEAD, 128>(a, stream)
+                          : launch_stream<KVQ_INT8_TOKEN_HEAD, 64>(a, stream);
   else
-    e = a.head_dim == 128 ? launch_split<KVQ_FP8E4M3_BLOCK_HEAD, 128>(a, grid, stream)
-                          : launch_split<KVQ_FP8E4M3_BLOCK_HEAD, 64>(a, grid, stream);
-  if (e != hipSuccess) return e;
-  if (a.num_chunks > 1) {
-    const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
-    if (a.head_dim == 128)
-      hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(128), 0, stream, a);
-    else
-      hipLaunchKernelGGL((attn_reduce_kernel<64>), dim3(rgrid), dim3(64), 0, stream, a);
-    e = hipGetLastError();
-  }
-  return e;
+    e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 128>(a, stream)
+                          : launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 64>(a, stream);
+  if (e != hipSuccess || g_read_ceiling) return e;
+  const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
+  if (a.head_dim == 128)
+    hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(128), 0, stream, a);
+  else
+    hipLaunchKernelGGL((attn_reduce_kernel<64>), dim3(rgrid), dim3(64), 0, stream, a);
+  return hipGetLastError();
 }
 
 }  // namespace kvq

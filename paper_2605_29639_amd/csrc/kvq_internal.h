@@ -17,21 +17,25 @@ __host__ __device__ inline size_t tile_offset(int64_t blk, int kv, int h, int nu
   return (((size_t)blk * 2 + (size_t)kv) * (size_t)num_kv_heads + (size_t)h) *
          (size_t)block_size * (size_t)head_dim;
 }
-// Position of logical element (off, d) inside a K tile (token-major) and a V tile
-// (channel-major).
+// Position of logical element (off, d) inside a (block, K|V, head) tile.  Both orders are
+// chosen so that the 16-byte piece one lane feeds to a matrix instruction is contiguous and
+// the four lanes of a quad read 64 contiguous bytes:
+//   K: quads of 4 tokens; inside a quad, 16-channel slices, then the 4 tokens, then 16 channels
+//   V: sub-blocks of 16 tokens; inside one, channel-major rows of 16 tokens
 __host__ __device__ inline int k_elem(int off, int d, int /*block_size*/, int head_dim) {
-  return off * head_dim + d;
+  return (off >> 2) * (4 * head_dim) + (d >> 4) * 64 + (off & 3) * 16 + (d & 15);
 }
-__host__ __device__ inline int v_elem(int off, int d, int block_size, int /*head_dim*/) {
-  return d * block_size + off;
+__host__ __device__ inline int v_elem(int off, int d, int /*block_size*/, int head_dim) {
+  return (off >> 4) * (16 * head_dim) + d * 16 + (off & 15);
 }
 
 struct AttnPlan {
-  int32_t chunk_tokens;    // split-K chunk, multiple of 64
-  int32_t num_chunks;      // ceil(max_seq_len / chunk_tokens)
   int32_t rows;            // (num_q_heads / num_kv_heads) * q_len query rows per kv head
-  int32_t row_tiles;       // 16-row tiles handled by one workgroup (1 or 2)
+  int32_t row_tiles;       // 16-row tiles handled by one wavefront (1 or 2)
   int32_t num_row_groups;  // ceil(rows / (16 * row_tiles))
+  int32_t pairs_per_seq;   // num_kv_heads * num_row_groups
+  int32_t range_groups;    // 64-token groups per wavefront range; 0 = even split on the device
+  int32_t num_waves;       // wavefronts launched (= grid size)
   size_t acc_floats;       // workspace: accumulators
   size_t ml_floats;        // workspace: (max, sum) pairs
 };
@@ -47,7 +51,7 @@ struct AttnArgs {
   float* ws_ml;
   int32_t max_blocks_per_seq, batch, q_len, num_q_heads, num_kv_heads, group, rows;
   int32_t block_size, bs_shift, head_dim, mode;
-  int32_t chunk_tokens, num_chunks, row_tiles, num_row_groups;
+  int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;
   float scale_log2;  // sm_scale * log2(e)
 };
 
@@ -56,6 +60,7 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
                         const kvq_cache_desc_t& desc, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
 void set_profile_events(hipEvent_t before, hipEvent_t after);
+void set_read_ceiling(bool on);
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream);
 

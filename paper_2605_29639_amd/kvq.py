@@ -15,9 +15,9 @@ OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
-           "paged_decode_attn_default_chunk", "paged_decode_attn_workspace_bytes",
+           "paged_decode_attn_workspace_bytes",
            "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
-           "kvq_profile_split_events", "kvq_strerror")
+           "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_strerror")
 
 
 class CacheDesc(C.Structure):
@@ -58,8 +58,6 @@ def lib():
         L.kvq_scales_bytes.restype, L.kvq_scales_bytes.argtypes = SZ, [D]
         L.kv_quant_write.restype = C.c_int
         L.kv_quant_write.argtypes = [P, P, P, I32, P, P, D, P]
-        L.paged_decode_attn_default_chunk.restype = I32
-        L.paged_decode_attn_default_chunk.argtypes = [D, I32, I32, I32, I32]
         L.paged_decode_attn_workspace_bytes.restype = SZ
         L.paged_decode_attn_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32]
         L.paged_decode_attn.restype = C.c_int
@@ -71,6 +69,8 @@ def lib():
         L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
         L.kvq_profile_split_events.restype = None
         L.kvq_profile_split_events.argtypes = [P, P]
+        L.kvq_profile_read_ceiling.restype = None
+        L.kvq_profile_read_ceiling.argtypes = [C.c_int]
         L.kvq_strerror.restype, L.kvq_strerror.argtypes = C.c_char_p, [C.c_int]
         _lib = L
     return _lib
@@ -117,11 +117,6 @@ def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None):
                               _stream(stream))
     if rc != OK:
         raise KvqError(rc, "kv_quant_write")
-
-
-def default_chunk(desc, batch, q_len, num_q_heads, max_seq_len):
-    return int(lib().paged_decode_attn_default_chunk(C.byref(desc), batch, q_len, num_q_heads,
-                                                     max_seq_len))
 
 
 def workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0):

@@ -92,23 +92,19 @@ def test_attn_argument_checks():
     assert attn(L, ok, batch=0) == kvq.OK                  # empty batch: nothing launched
     for name in ("q", "cache", "scales", "tables", "lens", "out"):
         assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
-    # split into chunks of 64 -> needs a workspace
+    # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each
     need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
-    assert need == 2 * 2 * 2 * 2 * (64 + 2) * 4
+    flat_max = 2 * 2 * 2                                   # batch * ceil(100/64) * kv heads
+    assert need == (flat_max + 2 * 2) * 16 * (64 + 2) * 4
     assert attn(L, ok, chunk=64, ws=None) == kvq.E_NULLPTR
     assert attn(L, ok, chunk=64, ws_bytes=need - 1) == kvq.E_WORKSPACE
     assert attn(L, ok, chunk=64, ws=C.c_void_p(0x1004), ws_bytes=need) == kvq.E_BAD_SHAPE
-    # a single chunk needs no workspace at all
-    assert L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 128) == 0
-
-
-def test_default_chunk_is_a_multiple_of_64_within_bounds():
-    L = kvq.lib()
+    auto = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 0)
+    assert auto == need                                    # fewer groups than resident waves
     big = kvq.make_desc(0, 1000, 16, 8, 128)
-    for batch, max_len in ((1, 100), (64, 4096), (256, 8192), (32, 65536), (1, 1 << 20)):
-        c = L.paged_decode_attn_default_chunk(C.byref(big), batch, 1, 32, max_len)
-        assert c % 64 == 0 and 256 <= c <= 4096
-    assert L.paged_decode_attn_default_chunk(C.byref(big), 1, 1, 33, 100) == 0
+    assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
+        (2048 + 64 * 8) * 16 * (128 + 2) * 4
+    assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
 
 
 def test_repack_argument_checks():

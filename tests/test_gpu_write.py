@@ -157,18 +157,25 @@ def test_extreme_magnitudes_int8_and_fp8():
 
 def test_repack_round_trip_and_layout():
     """to_canonical(from_canonical(x)) = x, and the physical layout is the documented one:
-    K tiles token-major, V tiles channel-major."""
+    K in 4-token quads of 16-channel slices, V channel-major per 16-token sub-block."""
     import torch
     from paper_2605_29639_amd import kvq
-    desc = kvq.make_desc(0, 5, 32, 3, 64)
+    nblk, bs, H, D = 5, 32, 3, 64
+    desc = kvq.make_desc(0, nblk, bs, H, D)
     rng = np.random.default_rng(0)
     canon = rng.integers(0, 256, size=desc.cache_shape(), dtype=np.uint8)
     phys = kvq.cache_from_canonical(torch.from_numpy(canon).cuda(), desc)
     back = kvq.cache_to_canonical(phys, desc).cpu().numpy()
     assert np.array_equal(back, canon)
-    p = phys.cpu().numpy().reshape(5, 2, 3, 32 * 64)
-    assert np.array_equal(p[:, 0].reshape(5, 3, 32, 64), canon[:, 0])
-    assert np.array_equal(p[:, 1].reshape(5, 3, 64, 32), canon[:, 1].transpose(0, 1, 3, 2))
+    p = phys.cpu().numpy().reshape(nblk, 2, H, bs * D)
+    # K: [quad][slice][token in quad][16 channels]
+    k = p[:, 0].reshape(nblk, H, bs // 4, D // 16, 4, 16)
+    want_k = canon[:, 0].reshape(nblk, H, bs // 4, 4, D // 16, 16).transpose(0, 1, 2, 4, 3, 5)
+    assert np.array_equal(k, want_k)
+    # V: [sub-block][channel][16 tokens]
+    v = p[:, 1].reshape(nblk, H, bs // 16, D, 16)
+    want_v = canon[:, 1].reshape(nblk, H, bs // 16, 16, D).transpose(0, 1, 2, 4, 3)
+    assert np.array_equal(v, want_v)
 
 
 def test_empty_write_is_a_no_op():
