@@ -43,14 +43,17 @@ class HipEvents:
         return ms.value
 
 
-def make_workload(name):
+def make_workload(name, mode):
     from paper_2605_29639_amd import workloads as W
+    kw = {} if mode is None else {"mode": {"int8": W.MODE_INT8, "fp8": W.MODE_FP8}[mode]}
     if name == "llama8b":
-        return W.llama8b()
+        return W.llama8b(**kw)
     if name == "fp8_append":
-        return W.fp8_append()
+        return W.fp8_append(**kw)
     if name == "long_gqa":
-        return W.long_gqa()
+        return W.long_gqa(**kw)
+    if name == "verify_prefix":
+        return W.verify_prefix(**kw)
     raise SystemExit("unknown workload %s" % name)
 
 
@@ -60,6 +63,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--mode", default=None, choices=["int8", "fp8"],
+                    help="override the workload's quantization mode")
     ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
     ap.add_argument("--chunk", type=int, default=-1, help="split-K chunk (-1 = workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -79,7 +84,7 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
 
-    wl = make_workload(args.workload)
+    wl = make_workload(args.workload, args.mode)
     chunk = wl.chunk_tokens if args.chunk < 0 else args.chunk
     alg = wl.algorithmic_bytes()
     # enough layer caches that the cycled live bytes exceed 4 x the 256 MB last-level cache

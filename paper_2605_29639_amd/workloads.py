@@ -183,13 +183,13 @@ def llama8b(batch=64, lo=512, hi=4096, mode=MODE_INT8, seed_offset=0):
     return _finish("llama3_8b_layer", mode, rng, seed, seq_lens, 1, 32, 8, 128, 16)
 
 
-def fp8_append(batch=256, lo=1024, hi=8192):
+def fp8_append(batch=256, lo=1024, hi=8192, mode=MODE_FP8):
     """Same heads, fp8-e4m3 per block-head; cache holds L tokens, then one token per sequence
     is appended; seq_lens here already count the appended token."""
     seed = BASE_SEED + 3
     rng = np.random.default_rng(seed)
     seq_lens = rng.integers(lo, hi + 1, size=batch) + 1
-    return _finish("fp8_append", MODE_FP8, rng, seed, seq_lens, 1, 32, 8, 128, 16,
+    return _finish("fp8_append", mode, rng, seed, seq_lens, 1, 32, 8, 128, 16,
                    append_tokens=1)
 
 
