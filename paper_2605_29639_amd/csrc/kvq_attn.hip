@@ -32,6 +32,7 @@
 //     caches measures ~6.9 TB/s on this machine against ~6.1 TB/s for ordinary loads.
 //   * K and V each live in one register buffer: the next group's K codes are requested as
 //     soon as QK^T has consumed the current ones, the next V codes as soon as P.V has.
+#include <cstdlib>
 #include <utility>
 
 #include "kvq_internal.h"
@@ -62,7 +63,7 @@ __device__ inline void static_for(F&& f) {
 template <int I>
 __device__ inline float row_bcast(float x) {
   return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + I, 0xF, 0xF, false));
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + I, 0xF, 0xF, true));
 }
 
 __device__ inline float xor16_max(float v) {
@@ -137,7 +138,7 @@ __device__ inline int range_groups(int requested, int flat_groups, int num_waves
 // CEIL = true builds the read-ceiling twin used for measurement only: same ranges, same
 // addresses, same load instructions and the same pipeline, but the arithmetic is replaced by
 // an XOR of the loaded words (one dword per wavefront is stored so that the loads stay).
-template <int MODE, int D, int NT, bool CEIL>
+template <int MODE, int D, int NT, bool CEIL, int DEPTH>
 __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   constexpr int DT = D / 16;
   constexpr int KJ = D / 64;
@@ -336,21 +337,25 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   };
 
   // ---- online softmax of a group: S (logits) -> pb (f16 probabilities x V scale) ----
-  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
-                     half8 (&pb)[NT][2]) {
+  // TAIL = some row's causal length ends inside the group: positions past a row's length are
+  // masked and scales of never-written slots are ignored.  The arithmetic on broadcast
+  // operands is kept as separate multiply / add so that the row broadcast rides on the
+  // instruction itself (v_mul_f32_dpp, v_add_f32_dpp) instead of costing moves.
+  auto softmax_impl = [&](auto TAILC, floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
+                          half8 (&pb)[NT][2]) {
+#pragma clang fp contract(off)
+    constexpr bool TAIL = decltype(TAILC)::value;
     if constexpr (CEIL) {
       ceil_x ^= __float_as_uint(sk) ^ __float_as_uint(sv);
       return;
     }
     const int pos0 = c.g << 6, L = c.L;
-    // a group is a "tail" if some row's causal length ends inside it
-    const bool tail = pos0 + 64 > L - p.q_len + 1;
     // this lane's scales: logit factor, log2 of the V scale and its inverse
     const float fold = (MODE == KVQ_FP8E4M3_BLOCK_HEAD) ? 256.0f : 1.0f;  // 2^8 of the f16 trick
     float skp = sk * (p.scale_log2 * fold);
     float lsv = __builtin_amdgcn_logf(fmaxf(sv * fold, kMinVScale));
     float rsv = __builtin_amdgcn_exp2f(-lsv);
-    if (MODE == KVQ_INT8_TOKEN_HEAD && tail && pos0 + 16 * g4 + m16 >= L) {
+    if (MODE == KVQ_INT8_TOKEN_HEAD && TAIL && pos0 + 16 * g4 + m16 >= L) {
       skp = 0.0f;  // a slot that was never written: its scales are not data
       lsv = 0.0f;
       rsv = 0.0f;
@@ -361,18 +366,16 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
     static_for<16>([&](auto I) {
       constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
-      float ks, ls;
-      if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
-        ks = row_bcast<tix>(skp);
-        ls = row_bcast<tix>(lsv);
-      } else {
-        ks = skp;
-        ls = lsv;
-      }
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        float ze = S[nt][u][i] * ks + ls;
-        if (tail) ze = (pos0 + 16 * g4 + tix < nrow[nt]) ? ze : -INFINITY;
+        float ze;
+        if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
+          ze = S[nt][u][i] * row_bcast<tix>(skp);
+          ze = ze + row_bcast<tix>(lsv);
+        } else {
+          ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
+        }
+        if constexpr (TAIL) ze = (pos0 + 16 * g4 + tix < nrow[nt]) ? ze : -INFINITY;
         S[nt][u][i] = ze;
         mx[nt] = fmaxf(mx[nt], ze);
       }
@@ -391,12 +394,15 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       static_for<16>([&](auto I) {
         constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
         const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
-        float rs;
-        if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) rs = row_bcast<tix>(rsv);
-        else rs = rsv;
-        lsum += pr * rs;
+        if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
+          const float t = pr * row_bcast<tix>(rsv);
+          lsum = lsum + t;
+        } else {
+          lsum = lsum + pr;
+        }
         pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
       });
+      if constexpr (MODE == KVQ_FP8E4M3_BLOCK_HEAD) lsum = lsum * rsv;  // one scale per lane
       l_run[nt] = l_run[nt] * alpha[nt] + lsum;
     }
     if (__any(rescale)) {
@@ -405,6 +411,13 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
         for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
     }
+  };
+  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
+                     half8 (&pb)[NT][2]) {
+    if ((c.g << 6) + 64 > c.L - p.q_len + 1)
+      softmax_impl(std::true_type{}, S, sk, sv, c, pb);
+    else
+      softmax_impl(std::false_type{}, S, sk, sv, c, pb);
   };
 
   // ---- acc^T += V^T P^T ----
@@ -431,9 +444,6 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   // being loaded), nn (its block-table entries are being fetched).  The table entries of a
   // group are always requested before the code loads that follow them in program order, so
   // waiting for an entry never waits for code loads issued behind it. ----
-  uintx4 kt[4][KJ], vt[DT];
-  float sk, sv;
-  const uint8_t* vbase;
   int blk_k, blk_v;
   floatx4 S[NT][4];
   half8 pb[NT][2];
@@ -441,36 +451,86 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   Cursor nxt = cur;
   if (count > 1) advance(nxt);
   Cursor nn = nxt;
-  {
-    int bk0, bv0;
-    fetch_entries(cur, bk0, bv0);
-    fetch_entries(nxt, blk_k, blk_v);
-    __builtin_amdgcn_sched_barrier(0);
-    load_k(kt, sk, sv, vbase, cur, bk0, bv0);
-    load_v(vt, vbase);
-  }
-  begin_pair(cur);
   bool from_start = cur.g == 0;  // did this wave see the current pair from its first group
-  for (int i = 0; i + 1 < count; ++i) {  // steady state: a next group exists
-    qk(kt, S);
-    const float sk_cur = sk, sv_cur = sv;
-    load_k(kt, sk, sv, vbase, nxt, blk_k, blk_v);
-    if (i + 2 < count) advance(nn);
-    fetch_entries(nn, blk_k, blk_v);
-    softmax(S, sk_cur, sv_cur, cur, pb);
-    pv(vt, pb);
-    load_v(vt, vbase);
-    if (nxt.g == 0) {  // the next group opens another pair
-      end_pair(cur, from_start);
-      begin_pair(nxt);
-      from_start = true;
+  if constexpr (DEPTH == 1) {
+    uintx4 kt[4][KJ], vt[DT];
+    float sk, sv;
+    const uint8_t* vbase;
+    {
+      int bk0, bv0;
+      fetch_entries(cur, bk0, bv0);
+      fetch_entries(nxt, blk_k, blk_v);
+      __builtin_amdgcn_sched_barrier(0);
+      load_k(kt, sk, sv, vbase, cur, bk0, bv0);
+      load_v(vt, vbase);
     }
-    cur = nxt;
-    nxt = nn;
+    begin_pair(cur);
+    for (int i = 0; i + 1 < count; ++i) {  // steady state: a next group exists
+      qk(kt, S);
+      const float sk_cur = sk, sv_cur = sv;
+      load_k(kt, sk, sv, vbase, nxt, blk_k, blk_v);
+      if (i + 2 < count) advance(nn);
+      fetch_entries(nn, blk_k, blk_v);
+      softmax(S, sk_cur, sv_cur, cur, pb);
+      pv(vt, pb);
+      load_v(vt, vbase);
+      if (nxt.g == 0) {  // the next group opens another pair
+        end_pair(cur, from_start);
+        begin_pair(nxt);
+        from_start = true;
+      }
+      cur = nxt;
+      nxt = nn;
+    }
+    qk(kt, S);  // the range's last group: nothing left to request
+    softmax(S, sk, sv, cur, pb);
+    pv(vt, pb);
+  } else {
+    // two full register buffers: the whole next group is requested before the current one is
+    // touched (one wavefront per SIMD; the 512-register file holds both)
+    uintx4 kta[4][KJ], vta[DT], ktb[4][KJ], vtb[DT];
+    float ska, sva, skb, svb;
+    const uint8_t* vbase;
+    {
+      int bk0, bv0;
+      fetch_entries(cur, bk0, bv0);
+      fetch_entries(nxt, blk_k, blk_v);
+      __builtin_amdgcn_sched_barrier(0);
+      load_k(kta, ska, sva, vbase, cur, bk0, bv0);
+      load_v(vta, vbase);
+    }
+    begin_pair(cur);
+    int i = 0;
+    auto half = [&](uintx4 (&ktx)[4][KJ], uintx4 (&vtx)[DT], float skx, float svx,
+                    uintx4 (&kty)[4][KJ], uintx4 (&vty)[DT], float& sky, float& svy) -> bool {
+      const bool more = i + 1 < count;
+      if (more) {
+        if (i + 2 < count) advance(nn);
+        int nk, nv;
+        fetch_entries(nn, nk, nv);  // entries first: see the ordering rule above
+        load_k(kty, sky, svy, vbase, nxt, blk_k, blk_v);
+        load_v(vty, vbase);
+        blk_k = nk;
+        blk_v = nv;
+      }
+      qk(ktx, S);
+      softmax(S, skx, svx, cur, pb);
+      pv(vtx, pb);
+      if (!more) return false;
+      if (nxt.g == 0) {
+        end_pair(cur, from_start);
+        begin_pair(nxt);
+        from_start = true;
+      }
+      cur = nxt;
+      nxt = nn;
+      ++i;
+      return true;
+    };
+    while (half(kta, vta, ska, sva, ktb, vtb, skb, svb) &&
+           half(ktb, vtb, skb, svb, kta, vta, ska, sva)) {
+    }
   }
-  qk(kt, S);  // the range's last group: nothing left to request
-  softmax(S, sk, sv, cur, pb);
-  pv(vt, pb);
   end_pair(cur, from_start && cur.g == cur.ng - 1);
   if constexpr (CEIL) p.ws_ml[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
@@ -540,12 +600,15 @@ bool g_read_ceiling = false;
 template <int MODE, int D>
 hipError_t launch_stream(const AttnArgs& a, hipStream_t stream) {
   if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
+  static const bool deep = getenv("KVQ_DEPTH2") != nullptr;  // experiment switch
   if (g_read_ceiling)
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  else if (a.row_tiles == 1 && deep)
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 2>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else if (a.row_tiles == 1)
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false>), dim3(a.num_waves), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false>), dim3(a.num_waves), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
   const hipError_t e = hipGetLastError();
   if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
   return e;
