@@ -68,6 +68,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
     ap.add_argument("--chunk", type=int, default=-1, help="split-K chunk (-1 = workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alias-blocks", type=int, default=0,
+                    help="diagnostic: fold every block-table entry modulo this many blocks so that "
+                         "all reads hit the caches (shows the kernel's pure issue time); the "
+                         "result line is then not a valid measurement")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run plain device-to-device copies of this many MiB (a known-size "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -101,6 +105,8 @@ def main():
     max_len = wl.max_seq_len
     q = bits_to_bf16_tensor(wl.q)
     bt = torch.from_numpy(wl.block_tables).cuda()
+    if args.alias_blocks:
+        bt = torch.where(bt >= 0, bt % args.alias_blocks, bt).contiguous()
     sl = torch.from_numpy(wl.seq_lens).cuda()
     out = torch.empty((B * wl.q_len, Hq, D), dtype=torch.float32, device="cuda")
     ws = kvq.alloc_workspace(desc, B, wl.q_len, Hq, max_len, chunk)
@@ -181,7 +187,7 @@ def main():
         "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8 codes, f16 MFMA operands, f32 accumulate",
-        "data": "synthetic",
+        "data": "synthetic" if not args.alias_blocks else "INVALID: aliased block tables (diagnostic)",
         "config": {"workload": wl.name, "mode": "int8_token_head" if wl.mode == 0 else "fp8e4m3_block_head",
                    "batch": B, "q_len": wl.q_len, "num_q_heads": Hq, "num_kv_heads": wl.num_kv_heads,
                    "head_dim": D, "block_size": wl.block_size, "sum_seq_lens": int(wl.seq_lens.sum()),

@@ -60,7 +60,8 @@ enum {
  *         (sub-blocks of 16 tokens; inside one: channel-major rows of 16 tokens, the order
  *          the P.V matrix instruction consumes)
  * Both orders make the 16-byte piece one lane feeds to a matrix instruction contiguous and
- * let the four lanes of a quad read 64 contiguous bytes.
+ * let the four lanes of a quad read 64 contiguous bytes.  int8 codes are stored in
+ * offset-binary form (stored byte = code XOR 0x80 = code + 128); e4m3 codes are stored as is.
  * kvq_cache_to_canonical / kvq_cache_from_canonical convert to and from the plain
  * [num_blocks][2][num_kv_heads][block_size][head_dim] order.
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
@@ -136,9 +137,10 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       int32_t chunk_tokens, float* out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
-/* Pure byte permutations between the physical cache layout above and the canonical
- * [num_blocks][2][num_kv_heads][block_size][head_dim] order (both device, kvq_cache_bytes()
- * long, must not overlap).  Used by tests and tools; not on the hot path. */
+/* Conversions between the physical cache above and the canonical
+ * [num_blocks][2][num_kv_heads][block_size][head_dim] array of plain codes (int8 two's
+ * complement / e4m3 bytes); both device, kvq_cache_bytes() long, must not overlap.  Used by
+ * tests and tools; not on the hot path. */
 int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,
                            void* stream);
 int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,

@@ -22,9 +22,10 @@
 //     sub-block g for channel 16t + m: the A operand (M = 16 channels, K = tokens) of the
 //     P.V instruction, whose B operand is exactly the lane's own 16 probabilities.  No
 //     shuffle, LDS transpose or re-layout sits between the two contractions.
-//   * Codes become f16 exactly (int8: magic-number bytes; e4m3: exponent re-bias by shifting,
-//     which leaves a factor 2^8 that is folded into the scale), the K scale multiplies the
-//     logit after the contraction and the V scale is folded into the probability.
+//   * Codes become f16 exactly (int8, stored as code + 128: the byte is dropped into the
+//     mantissa of 1024.0 and 1152 subtracted; e4m3: gfx950's packed fp8 -> f16 conversion), the
+//     K scale multiplies the logit after the contraction and the V scale is folded into the
+//     probability.
 //   * Online softmax in base 2.  The running reference m is the maximum of
 //     (logit + log2 V-scale), so the f16 probabilities p*sV stay in (0, 2^10] whatever the
 //     magnitude of V; the plain softmax denominator is recovered as sum(P * 2^-lsv).
@@ -75,26 +76,20 @@ __device__ inline float xor16_sum(float v) {
   return v + __shfl_xor(v, 32, 64);
 }
 
-// Four code bytes (one dword) -> four f16, in byte order.
+// Four stored code bytes (one dword) -> four f16, in byte order.
 template <int MODE>
 __device__ inline void cvt4(uint32_t x, half2v& lo, half2v& hi) {
   if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
-    // byte b (two's complement) ^ 0x80 = b + 128 as unsigned; 0x6400 | u is the f16 1024 + u
-    const uint32_t y = x ^ 0x80808080u;
-    const uint32_t a = __builtin_amdgcn_perm(0x64646464u, y, 0x04010400u);
-    const uint32_t b = __builtin_amdgcn_perm(0x64646464u, y, 0x04030402u);
+    // stored byte u = code + 128; 0x6400 | u is the f16 1024 + u, so subtracting 1152 gives code
+    const uint32_t a = __builtin_amdgcn_perm(0x64646464u, x, 0x04010400u);
+    const uint32_t b = __builtin_amdgcn_perm(0x64646464u, x, 0x04030402u);
     const half2v bias = {(_Float16)1152.0f, (_Float16)1152.0f};
     lo = __builtin_bit_cast(half2v, a) - bias;
     hi = __builtin_bit_cast(half2v, b) - bias;
   } else {
-    // S.EEEE.MMM placed as S.0EEEE.MMM0000000: the f16 with value e4m3 * 2^-8 (subnormals too)
-    const uint32_t a = __builtin_amdgcn_perm(0u, x, 0x010c000cu);  // (b1 << 24) | (b0 << 8)
-    const uint32_t b = __builtin_amdgcn_perm(0u, x, 0x030c020cu);  // (b3 << 24) | (b2 << 8)
-    const short2v one = {1, 1};
-    const uint32_t sa = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, a) >> one);
-    const uint32_t sb = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, b) >> one);
-    lo = __builtin_bit_cast(half2v, sa & 0xBFFFBFFFu);
-    hi = __builtin_bit_cast(half2v, sb & 0xBFFFBFFFu);
+    // gfx950's packed e4m3 -> f16 conversion (exact); NaN codes must not reach it as V data
+    lo = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(x, 1.0f, false);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(x, 1.0f, true);
   }
 }
 
@@ -351,9 +346,8 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     }
     const int pos0 = c.g << 6, L = c.L;
     // this lane's scales: logit factor, log2 of the V scale and its inverse
-    const float fold = (MODE == KVQ_FP8E4M3_BLOCK_HEAD) ? 256.0f : 1.0f;  // 2^8 of the f16 trick
-    float skp = sk * (p.scale_log2 * fold);
-    float lsv = __builtin_amdgcn_logf(fmaxf(sv * fold, kMinVScale));
+    float skp = sk * p.scale_log2;
+    float lsv = __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
     float rsv = __builtin_amdgcn_exp2f(-lsv);
     if (MODE == KVQ_INT8_TOKEN_HEAD && TAIL && pos0 + 16 * g4 + m16 >= L) {
       skp = 0.0f;  // a slot that was never written: its scales are not data
@@ -421,15 +415,33 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   };
 
   // ---- acc^T += V^T P^T ----
-  auto pv = [&](const uintx4 (&vt)[DT], const half8 (&pb)[NT][2]) {
+  // In a group that reaches past the sequence's last position the V bytes of the missing
+  // tokens are whatever the pool holds; their probabilities are exactly 0, but an e4m3 NaN
+  // code times 0 would still poison the sum, so those bytes are cleared first.
+  auto pv_impl = [&](auto CLEARC, const uintx4 (&vt)[DT], const half8 (&pb)[NT][2],
+                     const Cursor& c) {
+    constexpr bool CLEAR = decltype(CLEARC)::value;
     if constexpr (CEIL) {
 #pragma unroll
       for (int tt = 0; tt < DT; ++tt) ceil_x ^= vt[tt][0] ^ vt[tt][1] ^ vt[tt][2] ^ vt[tt][3];
       return;
     }
+    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
+    if constexpr (CLEAR) {
+      const int live = c.L - ((c.g << 6) + 16 * g4);  // tokens of this lane's sub-block below L
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int n = min(max(live - 4 * e, 0), 4);
+        keep[e] = n == 4 ? ~0u : (1u << (8 * n)) - 1u;
+      }
+    }
 #pragma unroll
     for (int tt = 0; tt < DT; ++tt) {
-      const uintx4 raw = vt[tt];
+      uintx4 raw = vt[tt];
+      if constexpr (CLEAR) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) raw[e] &= keep[e];
+      }
       const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
       const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
 #pragma unroll
@@ -438,6 +450,12 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
         acc[nt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, pb[nt][1], acc[nt][tt], 0, 0, 0);
       }
     }
+  };
+  auto pv = [&](const uintx4 (&vt)[DT], const half8 (&pb)[NT][2], const Cursor& c) {
+    if (MODE == KVQ_FP8E4M3_BLOCK_HEAD && (c.g << 6) + 64 > c.L)
+      pv_impl(std::true_type{}, vt, pb, c);
+    else
+      pv_impl(std::false_type{}, vt, pb, c);
   };
 
   // ---- main loop over the range.  Three cursors: cur (being computed), nxt (its codes are
@@ -472,7 +490,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       if (i + 2 < count) advance(nn);
       fetch_entries(nn, blk_k, blk_v);
       softmax(S, sk_cur, sv_cur, cur, pb);
-      pv(vt, pb);
+      pv(vt, pb, cur);
       load_v(vt, vbase);
       if (nxt.g == 0) {  // the next group opens another pair
         end_pair(cur, from_start);
@@ -484,7 +502,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     }
     qk(kt, S);  // the range's last group: nothing left to request
     softmax(S, sk, sv, cur, pb);
-    pv(vt, pb);
+    pv(vt, pb, cur);
   } else {
     // two full register buffers: the whole next group is requested before the current one is
     // touched (one wavefront per SIMD; the 512-register file holds both)
@@ -515,7 +533,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       }
       qk(ktx, S);
       softmax(S, skx, svx, cur, pb);
-      pv(vtx, pb);
+      pv(vtx, pb, cur);
       if (!more) return false;
       if (nxt.g == 0) {
         end_pair(cur, from_start);

@@ -29,6 +29,13 @@ __host__ __device__ inline int v_elem(int off, int d, int /*block_size*/, int he
   return (off >> 4) * (16 * head_dim) + d * 16 + (off & 15);
 }
 
+// int8 codes are kept in the cache in offset-binary form (stored byte = code XOR 0x80, i.e.
+// code + 128), which is the form the byte -> f16 conversion in the attention kernel consumes
+// directly; e4m3 codes are stored as they are.
+__host__ __device__ inline uint8_t stored_byte(uint8_t code, int mode) {
+  return mode == KVQ_INT8_TOKEN_HEAD ? (uint8_t)(code ^ 0x80) : code;
+}
+
 struct AttnPlan {
   int32_t rows;            // (num_q_heads / num_kv_heads) * q_len query rows per kv head
   int32_t row_tiles;       // 16-row tiles handled by one wavefront (1 or 2)

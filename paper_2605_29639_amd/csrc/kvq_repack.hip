@@ -1,5 +1,6 @@
-// Byte permutations between the library's physical cache layout (K tiles token-major, V tiles
-// channel-major) and the canonical [block][K|V][head][token][channel] order.  Not on the hot
+// Conversions between the library's physical cache (K in 4-token quads, V channel-major per
+// 16-token sub-block, int8 codes in offset-binary form) and the canonical
+// [block][K|V][head][token][channel] array of plain codes.  Not on the hot
 // path: used to hand a cache to, or take one from, code that expects the canonical order.
 #include "kvq_internal.h"
 
@@ -8,7 +9,8 @@ namespace {
 
 __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ src,
                                                      uint8_t* __restrict__ dst, size_t total,
-                                                     int H, int bs, int D, bool to_canonical) {
+                                                     int H, int bs, int D, int mode,
+                                                     bool to_canonical) {
   const size_t tile_bytes = (size_t)bs * D;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
        i += (size_t)gridDim.x * blockDim.x) {
@@ -18,8 +20,9 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
     const int off = within / D, d = within - off * D;
     const int kv = (int)((tile / H) & 1);
     const size_t phys = tile * tile_bytes + (kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D));
-    if (to_canonical) dst[i] = src[phys];
-    else dst[phys] = src[i];
+    // stored_byte is its own inverse
+    if (to_canonical) dst[i] = stored_byte(src[phys], mode);
+    else dst[phys] = stored_byte(src[i], mode);
   }
 }
 
@@ -34,7 +37,7 @@ hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& des
   if (blocks > 65536) blocks = 65536;
   hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                      (const uint8_t*)src, (uint8_t*)dst, total, desc.num_kv_heads,
-                     desc.block_size, desc.head_dim, to_canonical);
+                     desc.block_size, desc.head_dim, desc.mode, to_canonical);
   return hipGetLastError();
 }
 

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
   for (int e = 0; e < E; ++e) {
     const int d = lane * E + e;
     const uint8_t c = (amax == 0) ? (uint8_t)0 : int8_code(bf16_bits_to_float(bits[e]), s);
-    tile[kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D)] = c;
+    tile[kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D)] = stored_byte(c, KVQ_INT8_TOKEN_HEAD);
   }
   if (lane == 0) scales[(((size_t)blk * 2 + kv) * H + h) * bs + off] = s;
 }

@@ -99,11 +99,15 @@ def make_desc(mode, num_blocks, block_size, num_kv_heads, head_dim):
 
 
 def alloc_cache(desc, device="cuda", zero=True):
-    """(cache uint8, scales float32) device tensors of the sizes the library reports."""
+    """(cache uint8, scales float32) device tensors of the sizes the library reports.  With
+    zero=True every logical code and scale is 0 (int8 codes are stored as code + 128, so the
+    bytes of an all-zero int8 cache are 0x80)."""
     import torch
     nbytes, sbytes = lib().kvq_cache_bytes(desc), lib().kvq_scales_bytes(desc)
     make = torch.zeros if zero else torch.empty
     cache = make(nbytes, dtype=torch.uint8, device=device)
+    if zero and desc.mode == MODE_INT8:
+        cache.fill_(0x80)
     scales = make(sbytes // 4, dtype=torch.float32, device=device).view(desc.scales_shape())
     return cache, scales
 

@@ -114,14 +114,12 @@ def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     slots[15] = -1               # skipped tokens (fp8: at the end of a block's run, so each
     slots[47] = -1               # block still receives one run of consecutive slots)
     desc = gpu_desc(wl)
-    cache, scales = kvq.alloc_cache(desc)
-    cache.fill_(0x7F)            # stale pool: NaN codes and a garbage scale
-    scales.fill_(123.0)
+    # stale pool on both sides: NaN codes and a garbage scale everywhere
     oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 64)
     oc[:] = 0x7F
     osc[:] = 123.0
-    # the library's pool is physical-layout: make the stale bytes identical logically (they are
-    # all equal, so any permutation of them is the same pool)
+    cache = kvq.cache_from_canonical(torch.from_numpy(oc).cuda(), desc)
+    scales = torch.from_numpy(osc).cuda()
     oracle.kv_quant_write(k, v, slots, oc, osc, mode)
     kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
                        torch.from_numpy(slots).cuda(), cache, scales, desc)
@@ -157,7 +155,8 @@ def test_extreme_magnitudes_int8_and_fp8():
 
 def test_repack_round_trip_and_layout():
     """to_canonical(from_canonical(x)) = x, and the physical layout is the documented one:
-    K in 4-token quads of 16-channel slices, V channel-major per 16-token sub-block."""
+    K in 4-token quads of 16-channel slices, V channel-major per 16-token sub-block, int8
+    codes stored as code XOR 0x80."""
     import torch
     from paper_2605_29639_amd import kvq
     nblk, bs, H, D = 5, 32, 3, 64
@@ -171,11 +170,16 @@ def test_repack_round_trip_and_layout():
     # K: [quad][slice][token in quad][16 channels]
     k = p[:, 0].reshape(nblk, H, bs // 4, D // 16, 4, 16)
     want_k = canon[:, 0].reshape(nblk, H, bs // 4, 4, D // 16, 16).transpose(0, 1, 2, 4, 3, 5)
-    assert np.array_equal(k, want_k)
+    assert np.array_equal(k, want_k ^ 0x80)
     # V: [sub-block][channel][16 tokens]
     v = p[:, 1].reshape(nblk, H, bs // 16, D, 16)
     want_v = canon[:, 1].reshape(nblk, H, bs // 16, 16, D).transpose(0, 1, 2, 4, 3)
-    assert np.array_equal(v, want_v)
+    assert np.array_equal(v, want_v ^ 0x80)
+    # e4m3 codes are stored as they are
+    desc8 = kvq.make_desc(1, nblk, bs, H, D)
+    phys8 = kvq.cache_from_canonical(torch.from_numpy(canon).cuda(), desc8)
+    assert np.array_equal(phys8.cpu().numpy(), phys.cpu().numpy() ^ 0x80)
+    assert np.array_equal(kvq.cache_to_canonical(phys8, desc8).cpu().numpy(), canon)
 
 
 def test_empty_write_is_a_no_op():
