@@ -160,6 +160,15 @@ void kvq_profile_split_events(void* before, void* after);
  * read ceiling of this access pattern on the machine at hand.  Process-global; off initially. */
 void kvq_profile_read_ceiling(int on);
 
+/* Measurement hook, not part of the path: while `buf` (device, 8 x uint64 per launched
+ * wavefront, i.e. 8 * 8 * (number of wavefronts) bytes) is registered, every wavefront of the
+ * streaming kernel stores in buf[8*w + k]: the shader clock at entry (k = 0), after its first
+ * loads are issued (2), after its steady loop (3), after its last group (4) and after its
+ * results are stored (5); its hardware placement XCC_ID << 32 | HW_ID (1); and the constant
+ * 100 MHz clock at entry (6) and exit (7).
+ * Pass NULL to switch off (the initial state).  Process-global. */
+void kvq_profile_wave_clock(void* buf);
+
 /* Static, never-NULL description of a return code. */
 const char* kvq_strerror(int code);
 

@@ -160,6 +160,7 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   a.range_groups = plan.range_groups;
   a.num_waves = plan.num_waves;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
+  a.wave_clock = nullptr;
   const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
@@ -191,6 +192,8 @@ void kvq_profile_split_events(void* before, void* after) {
 }
 
 void kvq_profile_read_ceiling(int on) { kvq::set_read_ceiling(on != 0); }
+
+void kvq_profile_wave_clock(void* buf) { kvq::set_wave_clock((unsigned long long*)buf); }
 
 const char* kvq_strerror(int code) {
   switch (code) {

@@ -115,6 +115,11 @@ __device__ inline int wave_sum(int v) {
   for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
   return v;
 }
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
 __device__ inline int wave_incl_scan(int v, int lane) {
 #pragma unroll
   for (int s = 1; s < 64; s <<= 1) {
@@ -125,9 +130,18 @@ __device__ inline int wave_incl_scan(int v, int lane) {
 }
 __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// groups per wavefront range: the caller's, or an even split of the flat list over the grid
-__device__ inline int range_groups(int requested, int flat_groups, int num_waves) {
-  return requested > 0 ? requested : max(1, (flat_groups + num_waves - 1) / num_waves);
+// First flat group of wavefront w's range.  With a caller-given granule every range has
+// `requested` groups; otherwise the list is cut into num_waves ranges whose sizes differ by at
+// most one group (floor(w * flat / num_waves)), so that every compute unit, which holds the
+// same number of wavefronts, streams the same number of bytes.
+__device__ inline int range_begin(int w, int requested, int flat_groups, int num_waves) {
+  if (requested > 0) return (int)min((long long)w * requested, (long long)flat_groups);
+  return (int)(((long long)w * flat_groups) / num_waves);
+}
+// The wavefront whose range holds flat group f.
+__device__ inline int range_of(int f, int requested, int flat_groups, int num_waves) {
+  if (requested > 0) return f / requested;
+  return (int)((((long long)f + 1) * num_waves + flat_groups - 1) / flat_groups) - 1;
 }
 
 // CEIL = true builds the read-ceiling twin used for measurement only: same ranges, same
@@ -142,6 +156,16 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   const int m16 = lane & 15, g4 = lane >> 4;
   const int w = blockIdx.x;
   const int B = p.batch, Hp = p.pairs_per_seq;
+  auto stamp = [&](int k) {  // measurement hook, off unless a buffer was registered
+    if (p.wave_clock) {
+      // slots 0..5: shader clock; slots 6, 7: the constant 100 MHz clock at entry and exit
+      const unsigned long long t =
+          k < 6 ? __builtin_amdgcn_s_memtime() : __builtin_amdgcn_s_memrealtime();
+      if (lane == 0) p.wave_clock[(size_t)w * 8 + k] = t;
+    }
+  };
+  stamp(6);
+  stamp(0);
   const int32_t* __restrict__ seq_lens = p.seq_lens;
 
   // ---- this wave's range [f0, f1) of the flat list, and where it starts ----
@@ -151,10 +175,9 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
   }
   const int flat = uni(wave_sum(total)) * Hp;
-  const int R = range_groups(p.range_groups, flat, p.num_waves);
-  const int f0 = w * R;
-  if (f0 >= flat) return;
-  const int f1 = min(f0 + R, flat);
+  const int f0 = range_begin(w, p.range_groups, flat, p.num_waves);
+  const int f1 = range_begin(w + 1, p.range_groups, flat, p.num_waves);
+  if (f0 >= f1) return;
 
   Cursor cur;
   {
@@ -191,6 +214,10 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     } while (c.b < B && c.ng == 0);
   };
 
+  if (p.wave_clock && lane == 0)  // slot 1: where the wavefront runs (XCC_ID << 32 | HW_ID)
+    p.wave_clock[(size_t)w * 8 + 1] =
+        ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
+        (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
   const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads, NRG = p.num_row_groups;
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
@@ -478,12 +505,22 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       int bk0, bv0;
       fetch_entries(cur, bk0, bv0);
       fetch_entries(nxt, blk_k, blk_v);
+      begin_pair(cur);  // q is requested ahead of the codes so that it is not queued behind them
       __builtin_amdgcn_sched_barrier(0);
       load_k(kt, sk, sv, vbase, cur, bk0, bv0);
       load_v(vt, vbase);
     }
-    begin_pair(cur);
+    stamp(2);
+    // Two wavefronts share a SIMD and the hardware serves the older one first, so left alone
+    // one of them races ahead and the other finishes late on a half-empty machine.  Each
+    // wavefront therefore lowers its own issue priority as it progresses through its range:
+    // whichever lags is served first and the two stay abreast.
+    __builtin_amdgcn_s_setprio(3);
+    const int q1 = count / 4, q2 = count / 2, q3 = count - count / 4;
     for (int i = 0; i + 1 < count; ++i) {  // steady state: a next group exists
+      if (i == q1) __builtin_amdgcn_s_setprio(2);
+      if (i == q2) __builtin_amdgcn_s_setprio(1);
+      if (i == q3) __builtin_amdgcn_s_setprio(0);
       qk(kt, S);
       const float sk_cur = sk, sv_cur = sv;
       load_k(kt, sk, sv, vbase, nxt, blk_k, blk_v);
@@ -500,9 +537,11 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       cur = nxt;
       nxt = nn;
     }
+    stamp(3);
     qk(kt, S);  // the range's last group: nothing left to request
     softmax(S, sk, sv, cur, pb);
     pv(vt, pb, cur);
+    stamp(4);
   } else {
     // two full register buffers: the whole next group is requested before the current one is
     // touched (one wavefront per SIMD; the 512-register file holds both)
@@ -550,43 +589,35 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     }
   }
   end_pair(cur, from_start && cur.g == cur.ng - 1);
+  stamp(5);
+  stamp(7);
   if constexpr (CEIL) p.ws_ml[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
 
-// ---- log-sum-exp merge of a pair's partials: one workgroup per (sequence, query token,
-// query head), one thread per channel.  It recomputes where the pair lies in the flat list
-// and which wavefront ranges cover it. ----
+// ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query token,
+// query head), each lane owning D/64 channels.  It recomputes where the pair lies in the flat
+// list and which wavefront ranges cover it; the (max, sum) pairs of up to 64 ranges are
+// fetched by 64 lanes at once, so the chain of dependent memory round trips stays short. ----
 template <int D>
-__global__ __launch_bounds__(D) void attn_reduce_kernel(const AttnArgs p) {
+__global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
+  constexpr int E = D / 64;
+  typedef float floatE __attribute__((ext_vector_type(E)));
   int id = blockIdx.x;
   const int hq = id % p.num_q_heads;
   id /= p.num_q_heads;
   const int j = id % p.q_len;
   const int b = id / p.q_len;
-  const int d = threadIdx.x;
-  __shared__ int sm[2][D / 64];
+  const int lane = threadIdx.x;
   int before = 0, total = 0;
-  for (int i = d; i < p.batch; i += D) {
+  for (int i = lane; i < p.batch; i += 64) {
     const int n = (p.seq_lens[i] + 63) >> 6;
     total += n;
     before += (i < b) ? n : 0;
   }
-  before = wave_sum(before);
-  total = wave_sum(total);
-  if ((d & 63) == 0) {
-    sm[0][d >> 6] = before;
-    sm[1][d >> 6] = total;
-  }
-  __syncthreads();
-  before = 0;
-  total = 0;
-#pragma unroll
-  for (int k = 0; k < D / 64; ++k) {
-    before += sm[0][k];
-    total += sm[1][k];
-  }
+  before = uni(wave_sum(before));
+  total = uni(wave_sum(total));
   const int Hp = p.pairs_per_seq;
-  const int R = range_groups(p.range_groups, total * Hp, p.num_waves);
+  const int flat = total * Hp;
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
   const int r = j * p.group + (hq - h * p.group);
@@ -594,29 +625,61 @@ __global__ __launch_bounds__(D) void attn_reduce_kernel(const AttnArgs p) {
   const int pr = h * p.num_row_groups + rg;
   const int ng = (p.seq_lens[b] + 63) >> 6;
   const int start = before * Hp + pr * ng;
-  const int w_first = start / R, w_last = (start + ng - 1) / R;
+  const int w_first = range_of(start, p.range_groups, flat, p.num_waves);
+  const int w_last = range_of(start + ng - 1, p.range_groups, flat, p.num_waves);
   if (w_first == w_last) return;  // the streaming kernel already wrote the final rows
   const size_t pair = (size_t)b * Hp + pr;
+
+  // pass 1: the maximum over all partials
   float M = -INFINITY;
-  for (int w = w_first; w <= w_last; ++w)
-    M = fmaxf(M, p.ws_ml[(((size_t)w + pair) * rt + rl) * 2]);
-  float num = 0.0f, den = 0.0f;
-  for (int w = w_first; w <= w_last; ++w) {
-    const size_t row = ((size_t)w + pair) * rt + rl;
-    const float wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
-    num += wgt * p.ws_acc[row * D + d];
-    den += wgt * p.ws_ml[row * 2 + 1];
+  for (int w0 = w_first; w0 <= w_last; w0 += 64) {
+    const int w = w0 + lane;
+    // wavefronts whose range is empty left no partial
+    const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
+                                         range_begin(w + 1, p.range_groups, flat, p.num_waves);
+    const float m = live ? p.ws_ml[(((size_t)w + pair) * rt + rl) * 2] : -INFINITY;
+    M = fmaxf(M, m);
   }
-  p.out[(((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + d] = num / den;
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) M = fmaxf(M, __shfl_xor(M, s, 64));
+
+  // pass 2: weights, denominator and the weighted sum of the accumulators
+  floatE num = {};
+  float den = 0.0f;
+  for (int w0 = w_first; w0 <= w_last; w0 += 64) {
+    const int w = w0 + lane;
+    const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
+                                         range_begin(w + 1, p.range_groups, flat, p.num_waves);
+    float wgt = 0.0f;
+    if (live) {
+      const size_t row = ((size_t)w + pair) * rt + rl;
+      wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
+      den += wgt * p.ws_ml[row * 2 + 1];
+    }
+    const int n = min(64, w_last - w0 + 1);
+    for (int k = 0; k < n; ++k) {
+      const float wk = __shfl(wgt, k, 64);
+      if (wk == 0.0f) continue;  // empty range (or a partial that carries no weight)
+      const size_t row = ((size_t)(w0 + k) + pair) * rt + rl;
+      const floatE a = *(const floatE*)(p.ws_acc + row * D + lane * E);
+      num += wk * a;
+    }
+  }
+  den = wave_sum_f(den);
+  float* o = p.out + (((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + lane * E;
+  *(floatE*)o = num * (1.0f / den);
 }
 
 // measurement hooks: events recorded around the streaming kernel (kvq_profile_split_events)
 // and the read-ceiling twin in place of the real kernel (kvq_profile_read_ceiling)
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 bool g_read_ceiling = false;
+unsigned long long* g_wave_clock = nullptr;
 
 template <int MODE, int D>
-hipError_t launch_stream(const AttnArgs& a, hipStream_t stream) {
+hipError_t launch_stream(const AttnArgs& a0, hipStream_t stream) {
+  AttnArgs a = a0;
+  a.wave_clock = g_wave_clock;
   if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
   static const bool deep = getenv("KVQ_DEPTH2") != nullptr;  // experiment switch
   if (g_read_ceiling)
@@ -640,6 +703,7 @@ void set_profile_events(hipEvent_t before, hipEvent_t after) {
 }
 
 void set_read_ceiling(bool on) { g_read_ceiling = on; }
+void set_wave_clock(unsigned long long* buf) { g_wave_clock = buf; }
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   hipError_t e;
@@ -652,7 +716,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   if (e != hipSuccess || g_read_ceiling) return e;
   const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
   if (a.head_dim == 128)
-    hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(128), 0, stream, a);
+    hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(64), 0, stream, a);
   else
     hipLaunchKernelGGL((attn_reduce_kernel<64>), dim3(rgrid), dim3(64), 0, stream, a);
   return hipGetLastError();

@@ -60,6 +60,7 @@ struct AttnArgs {
   int32_t block_size, bs_shift, head_dim, mode;
   int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;
   float scale_log2;  // sm_scale * log2(e)
+  unsigned long long* wave_clock;  // measurement hook: 8 timestamps per wavefront, or null
 };
 
 hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mapping,
@@ -68,6 +69,7 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
 void set_profile_events(hipEvent_t before, hipEvent_t after);
 void set_read_ceiling(bool on);
+void set_wave_clock(unsigned long long* buf);
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream);
 
