@@ -160,6 +160,11 @@ void kvq_profile_split_events(void* before, void* after);
  * read ceiling of this access pattern on the machine at hand.  Process-global; off initially. */
 void kvq_profile_read_ceiling(int on);
 
+/* Measurement hook, not part of the path: while switched on, paged_decode_attn launches only
+ * its streaming kernel and skips the reduce (`out` is then incomplete), so that a run of calls
+ * is a run of back-to-back streaming kernels that two events can bracket.  Off initially. */
+void kvq_profile_skip_reduce(int on);
+
 /* Measurement hook, not part of the path: while `buf` (device, 8 x uint64 per launched
  * wavefront, i.e. 8 * 8 * (number of wavefronts) bytes) is registered, every wavefront of the
  * streaming kernel stores in buf[8*w + k]: the shader clock at entry (k = 0), after its first

@@ -674,6 +674,7 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
 // and the read-ceiling twin in place of the real kernel (kvq_profile_read_ceiling)
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 bool g_read_ceiling = false;
+bool g_skip_reduce = false;
 unsigned long long* g_wave_clock = nullptr;
 
 template <int MODE, int D>
@@ -703,6 +704,7 @@ void set_profile_events(hipEvent_t before, hipEvent_t after) {
 }
 
 void set_read_ceiling(bool on) { g_read_ceiling = on; }
+void set_skip_reduce(bool on) { g_skip_reduce = on; }
 void set_wave_clock(unsigned long long* buf) { g_wave_clock = buf; }
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
@@ -713,7 +715,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   else
     e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 128>(a, stream)
                           : launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 64>(a, stream);
-  if (e != hipSuccess || g_read_ceiling) return e;
+  if (e != hipSuccess || g_read_ceiling || g_skip_reduce) return e;
   const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
   if (a.head_dim == 128)
     hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(64), 0, stream, a);

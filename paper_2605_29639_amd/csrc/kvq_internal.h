@@ -69,6 +69,7 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
 void set_profile_events(hipEvent_t before, hipEvent_t after);
 void set_read_ceiling(bool on);
+void set_skip_reduce(bool on);
 void set_wave_clock(unsigned long long* buf);
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream);

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_workspace_bytes",
            "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
-           "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_wave_clock",
+           "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
+           "kvq_profile_wave_clock",
            "kvq_strerror")
 
 
@@ -70,6 +71,8 @@ def lib():
         L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
         L.kvq_profile_split_events.restype = None
         L.kvq_profile_split_events.argtypes = [P, P]
+        L.kvq_profile_skip_reduce.restype = None
+        L.kvq_profile_skip_reduce.argtypes = [C.c_int]
         L.kvq_profile_wave_clock.restype = None
         L.kvq_profile_wave_clock.argtypes = [P]
         L.kvq_profile_read_ceiling.restype = None
