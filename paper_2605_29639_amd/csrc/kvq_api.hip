@@ -55,8 +55,9 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   if (chunk_tokens == 0) {
     // even split over as many wavefronts as an MI355X keeps resident at this kernel's
     // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
+    const int64_t resident = plan->row_tiles == 1 ? kAutoWaves : kAutoWaves / 2;
     plan->range_groups = 0;
-    plan->num_waves = (int32_t)(flat_max < kAutoWaves ? flat_max : kAutoWaves);
+    plan->num_waves = (int32_t)(flat_max < resident ? flat_max : resident);
   } else {
     plan->range_groups = chunk_tokens / 64;
     plan->num_waves = (int32_t)((flat_max + plan->range_groups - 1) / plan->range_groups);

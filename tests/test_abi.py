@@ -105,6 +105,9 @@ def test_attn_argument_checks():
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
         (2048 + 64 * 8) * 16 * (128 + 2) * 4
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
+    # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
+    assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
+        (1024 + 128 * 8) * 32 * (128 + 2) * 4
 
 
 def test_repack_argument_checks():
