@@ -55,48 +55,101 @@ __device__ inline double fp8_value(uint32_t c) {
   return (c & 0x80) ? -mag : mag;
 }
 
+// A lane owns E = D/64 adjacent channels.  K bytes of a token for those channels are adjacent
+// in the quad order (one 1- or 2-byte store).  V bytes of consecutive tokens for one channel
+// are adjacent in the sub-block order, so a run of tokens is gathered per channel into one
+// 16-byte row image and stored once: a whole sub-block as one 16-byte store per channel,
+// a shorter run byte by byte (other slots of the row keep their contents).
+struct RowImage {
+  unsigned long long lo = 0, hi = 0;  // bytes 0..7 and 8..15 of a 16-token V row
+  __device__ void put(int pos, uint8_t b) {
+    if (pos < 8) lo |= (unsigned long long)b << (8 * pos);
+    else hi |= (unsigned long long)b << (8 * (pos - 8));
+  }
+  __device__ uint8_t get(int pos) const {
+    return (uint8_t)(pos < 8 ? lo >> (8 * pos) : hi >> (8 * (pos - 8)));
+  }
+};
+
+// store bytes [first, first + n) of a 16-token V row
+__device__ inline void store_v_row(uint8_t* row, const RowImage& img, int first, int n) {
+  if (n == 16) {
+    *(uint4*)row = make_uint4((uint32_t)img.lo, (uint32_t)(img.lo >> 32), (uint32_t)img.hi,
+                              (uint32_t)(img.hi >> 32));
+  } else {
+    for (int j = first; j < first + n; ++j) row[j] = img.get(j);
+  }
+}
+
+template <int E>
+__device__ inline void store_k(uint8_t* p, const uint8_t (&c)[E]) {
+  if constexpr (E == 2) *(uint16_t*)p = (uint16_t)(c[0] | (c[1] << 8));
+  else p[0] = c[0];
+}
+
 // ---- int8, one scale per (token, kv head) -------------------------------------------------
+// unit = (run, kv head, K|V): the consecutive tokens of the call that fall into one 16-token
+// sub-block with consecutive slots; the wavefront of the run's first token does the work.
 template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
     float* __restrict__ scales, int32_t H, int32_t bs) {
-  constexpr int E = D / 64;  // elements per lane
+  constexpr int E = D / 64;  // channels per lane
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   if (unit >= (int64_t)num_tokens * H * 2) return;
   const int kv = (int)(unit & 1);
   const int h = (int)((unit >> 1) % H);
-  const int t = (int)((unit >> 1) / H);
-  const int64_t slot = slot_mapping[t];
-  if (slot < 0) return;
-  const int64_t blk = slot / bs;
-  const int off = (int)(slot - blk * bs);
-
-  const uint16_t* row = (kv ? v : k) + ((size_t)t * H + h) * D + lane * E;
-  uint32_t bits[E];
-  uint32_t amax = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    bits[e] = row[e];
-    const uint32_t a = bits[e] & 0x7FFF;
-    amax = a > amax ? a : amax;
-  }
-  amax = wave_max_u32(amax);  // |bf16| orders like its bit pattern
-  const float m = bf16_bits_to_float(amax);
-  const float s = (amax == 0) ? 0.0f : (float)((double)m / 127.0);
+  const int t0 = (int)((unit >> 1) / H);
+  const int64_t slot0 = slot_mapping[t0];
+  if (slot0 < 0) return;
+  const int64_t blk = slot0 / bs;
+  const int off0 = (int)(slot0 - blk * bs);
+  const int so = off0 & 15;  // position inside the sub-block
+  if (t0 > 0 && so > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
+  int run = 1;
+  while (run < 16 - so && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
 
   uint8_t* tile = cache + tile_offset(blk, kv, h, H, bs, D);
+  float* srow = scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0;
+  const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * E;
+  const size_t tstride = (size_t)H * D;
+  RowImage img[E];
+  for (int i = 0; i < run; ++i) {
+    uint32_t bits[E];
+    uint32_t amax = 0;
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int d = lane * E + e;
-    const uint8_t c = (amax == 0) ? (uint8_t)0 : int8_code(bf16_bits_to_float(bits[e]), s);
-    tile[kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D)] = stored_byte(c, KVQ_INT8_TOKEN_HEAD);
+    for (int e = 0; e < E; ++e) {
+      bits[e] = src[i * tstride + e];
+      const uint32_t a = bits[e] & 0x7FFF;
+      amax = a > amax ? a : amax;
+    }
+    amax = wave_max_u32(amax);  // |bf16| orders like its bit pattern
+    const float s = (amax == 0) ? 0.0f : (float)((double)bf16_bits_to_float(amax) / 127.0);
+    uint8_t c[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const uint8_t code = (amax == 0) ? (uint8_t)0 : int8_code(bf16_bits_to_float(bits[e]), s);
+      c[e] = stored_byte(code, KVQ_INT8_TOKEN_HEAD);
+    }
+    if (kv == 0) {
+      store_k<E>(tile + k_elem(off0 + i, lane * E, bs, D), c);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) img[e].put(so + i, c[e]);
+    }
+    if (lane == 0) srow[i] = s;
   }
-  if (lane == 0) scales[(((size_t)blk * 2 + kv) * H + h) * bs + off] = s;
+  if (kv == 1) {
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      store_v_row(tile + v_elem(off0 - so, lane * E + e, bs, D), img[e], so, run);
+  }
 }
 
 // ---- fp8-e4m3, one scale per (block, kv head) ---------------------------------------------
+// unit = (run, kv head, K|V): the consecutive tokens of the call that fall into one block.
 template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -113,8 +166,7 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
   if (slot0 < 0) return;
   const int64_t blk = slot0 / bs;
   const int o_min = (int)(slot0 - blk * bs);
-  // Only the first token of a run works: the previous token continues into this slot?
-  if (t0 > 0 && o_min > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;
+  if (t0 > 0 && o_min > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
   int run = 1;
   while (run < bs - o_min && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
 
@@ -133,29 +185,52 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
   const float s_prev = (o_min > 0) ? *sp : 0.0f;
   const float s_cand = (amax == 0) ? 0.0f : (float)((double)bf16_bits_to_float(amax) / 448.0);
   const float s_new = s_prev > s_cand ? s_prev : s_cand;
+  // the block's scale grew: the codes stored below the run are re-expressed in the new scale
+  const bool regrade = o_min > 0 && s_new > s_prev && s_prev > 0.0f;
+  auto regraded = [&](uint32_t c) -> uint8_t {
+    if ((c & 0x7F) == 0x7F) return (uint8_t)c;  // NaN codes stay
+    return fp8_code(fp8_value(c) * (double)s_prev / (double)s_new);
+  };
+  auto encoded = [&](int i, int e) -> uint8_t {
+    if (!(s_new > 0.0f)) return 0;
+    return fp8_code((double)bf16_bits_to_float(src[i * tstride + e]) / (double)s_new);
+  };
 
   uint8_t* tile = cache + tile_offset(blk, kv, h, H, bs, D);
-  if (o_min > 0 && s_new > s_prev && s_prev > 0.0f) {
-    // the block's scale grew: re-express the codes stored below the run in the new scale
-    for (int off = 0; off < o_min; ++off) {
+  if (kv == 0) {
+    if (regrade) {
+      for (int off = 0; off < o_min; ++off) {
+        uint8_t* pc = tile + k_elem(off, lane * E, bs, D);
+        uint8_t c[E];
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const int d = lane * E + e;
-        uint8_t* pc = tile + (kv ? v_elem(off, d, bs, D) : k_elem(off, d, bs, D));
-        const uint32_t c = *pc;
-        if ((c & 0x7F) == 0x7F) continue;  // NaN codes stay
-        *pc = fp8_code(fp8_value(c) * (double)s_prev / (double)s_new);
+        for (int e = 0; e < E; ++e) c[e] = regraded(pc[e]);
+        store_k<E>(pc, c);
       }
     }
-  }
-  for (int i = 0; i < run; ++i) {
+    for (int i = 0; i < run; ++i) {
+      uint8_t c[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const int d = lane * E + e;
-      uint8_t c = 0;
-      if (s_new > 0.0f)
-        c = fp8_code((double)bf16_bits_to_float(src[i * tstride + e]) / (double)s_new);
-      tile[kv ? v_elem(o_min + i, d, bs, D) : k_elem(o_min + i, d, bs, D)] = c;
+      for (int e = 0; e < E; ++e) c[e] = encoded(i, e);
+      store_k<E>(tile + k_elem(o_min + i, lane * E, bs, D), c);
+    }
+  } else {
+    // V: sub-block by sub-block, each channel's 16-token row read (if it holds older codes),
+    // updated and stored once
+    const int first_sb = regrade ? 0 : (o_min >> 4);
+    const int last_sb = (o_min + run - 1) >> 4;
+    for (int sb = first_sb; sb <= last_sb; ++sb) {
+      const int lo = max(o_min - 16 * sb, 0);             // first new position in this row
+      const int hi = min(o_min + run - 16 * sb, 16);      // one past the last new position
+      const int old_n = regrade ? min(lo, 16) : 0;        // older codes to re-express: [0, old_n)
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        uint8_t* row = tile + v_elem(16 * sb, lane * E + e, bs, D);
+        RowImage img;
+        for (int j = 0; j < old_n; ++j) img.put(j, regraded(row[j]));
+        for (int j = max(lo, 0); j < hi; ++j) img.put(j, encoded(16 * sb + j - o_min, e));
+        const int first = old_n > 0 ? 0 : lo;  // older codes, if re-expressed, end where the new begin
+        if (hi > first) store_v_row(row, img, first, hi - first);
+      }
     }
   }
   if (lane == 0) *sp = s_new;
