@@ -33,7 +33,6 @@
 //     caches measures ~6.9 TB/s on this machine against ~6.1 TB/s for ordinary loads.
 //   * K and V each live in one register buffer: the next group's K codes are requested as
 //     soon as QK^T has consumed the current ones, the next V codes as soon as P.V has.
-#include <cstdlib>
 #include <utility>
 
 #include "kvq_internal.h"
@@ -543,49 +542,71 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     pv(vt, pb, cur);
     stamp(4);
   } else {
-    // two full register buffers: the whole next group is requested before the current one is
-    // touched (one wavefront per SIMD; the 512-register file holds both)
+    // Two full register buffers (one wavefront per SIMD; the 512-register file holds both):
+    // a group's codes are requested a whole group ahead of their use.  The steady loop is
+    // unrolled by two so that the buffers and the table-entry registers swap roles without
+    // copies, and every load in it is unconditional (a load under a usually-true condition
+    // would make the compiler's wait counts as strict as if the load were never issued).
     uintx4 kta[4][KJ], vta[DT], ktb[4][KJ], vtb[DT];
     float ska, sva, skb, svb;
     const uint8_t* vbase;
-    {
-      int bk0, bv0;
-      fetch_entries(cur, bk0, bv0);
-      fetch_entries(nxt, blk_k, blk_v);
-      __builtin_amdgcn_sched_barrier(0);
-      load_k(kta, ska, sva, vbase, cur, bk0, bv0);
-      load_v(vta, vbase);
-    }
+    int tk0, tv0, tk1, tv1;  // table entries of the group after the one being loaded
+    Cursor c1 = nxt, c2 = nxt, c3 = nxt;  // groups i+1, i+2, i+3 (clamped to the range's last)
+    if (count > 2) advance(c2);
+    c3 = c2;
+    if (count > 3) advance(c3);
+    fetch_entries(cur, tk0, tv0);
+    fetch_entries(c1, tk1, tv1);
     begin_pair(cur);
-    int i = 0;
-    auto half = [&](uintx4 (&ktx)[4][KJ], uintx4 (&vtx)[DT], float skx, float svx,
-                    uintx4 (&kty)[4][KJ], uintx4 (&vty)[DT], float& sky, float& svy) -> bool {
-      const bool more = i + 1 < count;
-      if (more) {
-        if (i + 2 < count) advance(nn);
-        int nk, nv;
-        fetch_entries(nn, nk, nv);  // entries first: see the ordering rule above
-        load_k(kty, sky, svy, vbase, nxt, blk_k, blk_v);
-        load_v(vty, vbase);
-        blk_k = nk;
-        blk_v = nv;
-      }
-      qk(ktx, S);
-      softmax(S, skx, svx, cur, pb);
-      pv(vtx, pb, cur);
-      if (!more) return false;
-      if (nxt.g == 0) {
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(kta, ska, sva, vbase, cur, tk0, tv0);
+    load_v(vta, vbase);
+    auto leave = [&](const Cursor& next) {  // after a group: does the next one open another pair
+      if (next.g == 0) {
         end_pair(cur, from_start);
-        begin_pair(nxt);
+        begin_pair(next);
         from_start = true;
       }
-      cur = nxt;
-      nxt = nn;
-      ++i;
-      return true;
+      cur = next;
     };
-    while (half(kta, vta, ska, sva, ktb, vtb, skb, svb) &&
-           half(ktb, vtb, skb, svb, kta, vta, ska, sva)) {
+    int i = 0;
+    for (; i + 2 < count; i += 2) {  // groups i, i+1, i+2 exist
+      // buffer a holds group i; tk1/tv1 are the entries of group i+1
+      fetch_entries(c2, tk0, tv0);
+      load_k(ktb, skb, svb, vbase, c1, tk1, tv1);
+      load_v(vtb, vbase);
+      qk(kta, S);
+      softmax(S, ska, sva, cur, pb);
+      pv(vta, pb, cur);
+      leave(c1);
+      // buffer b holds group i+1; tk0/tv0 are the entries of group i+2
+      fetch_entries(c3, tk1, tv1);
+      load_k(kta, ska, sva, vbase, c2, tk0, tv0);
+      load_v(vta, vbase);
+      qk(ktb, S);
+      softmax(S, skb, svb, cur, pb);
+      pv(vtb, pb, cur);
+      leave(c2);
+      c1 = c3;
+      if (i + 4 < count) advance(c3);
+      c2 = c3;
+      if (i + 5 < count) advance(c3);
+    }
+    // one or two groups are left; buffer a holds group i
+    if (i + 1 < count) {
+      load_k(ktb, skb, svb, vbase, c1, tk1, tv1);
+      load_v(vtb, vbase);
+      qk(kta, S);
+      softmax(S, ska, sva, cur, pb);
+      pv(vta, pb, cur);
+      leave(c1);
+      qk(ktb, S);
+      softmax(S, skb, svb, cur, pb);
+      pv(vtb, pb, cur);
+    } else {
+      qk(kta, S);
+      softmax(S, ska, sva, cur, pb);
+      pv(vta, pb, cur);
     }
   }
   end_pair(cur, from_start && cur.g == cur.ng - 1);
@@ -682,15 +703,14 @@ hipError_t launch_stream(const AttnArgs& a0, hipStream_t stream) {
   AttnArgs a = a0;
   a.wave_clock = g_wave_clock;
   if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
-  static const bool deep = getenv("KVQ_DEPTH2") != nullptr;  // experiment switch
+  // one 16-row tile: two wavefronts per SIMD, single register buffers; two tiles: one
+  // wavefront per SIMD, so the loads are double-buffered instead
   if (g_read_ceiling)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  else if (a.row_tiles == 1 && deep)
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 2>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else if (a.row_tiles == 1)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, 2>), dim3(a.num_waves), dim3(64), 0, stream, a);
   const hipError_t e = hipGetLastError();
   if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
   return e;
