@@ -82,9 +82,11 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
 /* Section 7.2.2, "On-the-fly Quantization": quantize num_tokens new K and V rows and store
  * them at their slots (slot = physical_block * block_size + offset; a negative slot skips
  * the token).
- *   k, v          device, bf16 [num_tokens][num_kv_heads][head_dim], read only
+ *   k, v          device, bf16 [num_tokens][num_kv_heads][head_dim], read only, 16-byte aligned
  *   slot_mapping  device, int64 [num_tokens], read only
- *   cache, scales device, layouts above, updated in place
+ *   cache, scales device, layouts above, updated in place; cache 16-byte aligned
+ * Calls with at least 1024 tokens (a prompt) take kernels that handle 16 tokens per
+ * wavefront; the result does not depend on which kernels run.
  * KVQ_INT8_TOKEN_HEAD: per (token, kv head), separately for K and V: scale = fp32 nearest to
  *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
  *   exact x/scale, clamped to [-127, 127].

@@ -97,6 +97,7 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
   if (num_tokens < 0) return KVQ_E_BAD_SHAPE;
   if (num_tokens == 0) return KVQ_OK;
   if (!k || !v || !slot_mapping || !cache || !scales) return KVQ_E_NULLPTR;
+  if ((((uintptr_t)k | (uintptr_t)v | (uintptr_t)cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const hipError_t e = kvq::launch_write(k, v, slot_mapping, num_tokens, cache, scales, *desc,
                                          (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;

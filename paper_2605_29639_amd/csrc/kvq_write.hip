@@ -16,6 +16,7 @@ namespace kvq {
 namespace {
 
 constexpr int kWaves = 4;  // wavefronts per workgroup
+constexpr int kBulkTokens = 1024;  // calls with at least this many tokens take the prefill kernels
 
 __device__ inline float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
@@ -89,28 +90,18 @@ __device__ inline void store_k(uint8_t* p, const uint8_t (&c)[E]) {
 
 // ---- int8, one scale per (token, kv head) -------------------------------------------------
 // unit = (run, kv head, K|V): the consecutive tokens of the call that fall into one 16-token
-// sub-block with consecutive slots; the wavefront of the run's first token does the work.
+// sub-block with consecutive slots.
+
+// One run of `run` tokens starting at token t0, slot0 (any length, any start inside the
+// sub-block): a lane owns D/64 channels of every token.
 template <int D>
-__global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
-    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
-    float* __restrict__ scales, int32_t H, int32_t bs) {
+__device__ inline void int8_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
+                                int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
   constexpr int E = D / 64;  // channels per lane
-  const int lane = threadIdx.x & 63;
-  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (unit >= (int64_t)num_tokens * H * 2) return;
-  const int kv = (int)(unit & 1);
-  const int h = (int)((unit >> 1) % H);
-  const int t0 = (int)((unit >> 1) / H);
-  const int64_t slot0 = slot_mapping[t0];
-  if (slot0 < 0) return;
-  const int64_t blk = slot0 / bs;
+  const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
   const int off0 = (int)(slot0 - blk * bs);
   const int so = off0 & 15;  // position inside the sub-block
-  if (t0 > 0 && so > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
-  int run = 1;
-  while (run < 16 - so && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
-
   uint8_t* tile = cache + tile_offset(blk, kv, h, H, bs, D);
   float* srow = scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0;
   const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * E;
@@ -148,14 +139,13 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
   }
 }
 
-// ---- fp8-e4m3, one scale per (block, kv head) ---------------------------------------------
-// unit = (run, kv head, K|V): the consecutive tokens of the call that fall into one block.
+// The wavefront of a run's first token does the work (one token per sequence in a decode
+// step: every wavefront has a run of its own and they all proceed in parallel).
 template <int D>
-__global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
+__global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
     float* __restrict__ scales, int32_t H, int32_t bs) {
-  constexpr int E = D / 64;
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   if (unit >= (int64_t)num_tokens * H * 2) return;
@@ -164,12 +154,158 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
   const int t0 = (int)((unit >> 1) / H);
   const int64_t slot0 = slot_mapping[t0];
   if (slot0 < 0) return;
-  const int64_t blk = slot0 / bs;
-  const int o_min = (int)(slot0 - blk * bs);
-  if (t0 > 0 && o_min > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
+  const int so = (int)(slot0 & 15);
+  if (t0 > 0 && so > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
   int run = 1;
-  while (run < bs - o_min && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
+  while (run < 16 - so && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
+  int8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+}
 
+// ---- int8, many tokens per call (prefill) --------------------------------------------------
+// A run that fills a whole 16-token sub-block, the common case when a prompt is written at
+// once, is handled with 16-byte loads: a lane owns 8 adjacent channels of 16 / G tokens
+// (G = 512 / D groups of D / 8 lanes).  Which tokens depends on the cache order the codes go
+// into: for K the tokens i * G + g (lane group g, load i), so that each store instruction of
+// the wavefront fills whole quads; for V the tokens g * (16 / G) + i, so that the lane's bytes
+// of one channel are adjacent in that channel's 16-token row.
+//
+// Rounding x / s: the fp32 product x * rcp(s) is within 2.3e-5 of the exact quotient
+// (|quotient| <= 127, rcp within one ulp, one rounding for the product), so unless it lies
+// within 4e-5 of a half-integer its nearest integer is the exact quotient's; the rare
+// elements that do are decided in fp64 like everywhere else.  The scale is one correctly
+// rounded fp32 division, which equals the fp64 quotient rounded once for every bf16 absmax.
+template <int CL>
+__device__ inline uint32_t row_max_u32(uint32_t v) {  // max over the CL lanes that share a row
+  auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  if constexpr (CL == 16)
+    v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
+  return v;
+}
+
+template <int D>
+__device__ inline void int8_subblock(const uint16_t* __restrict__ src, size_t tstride,
+                                     uint8_t* __restrict__ tile, float* __restrict__ srow,
+                                     int kv, int off0, int bs, int lane) {
+  constexpr int CL = D / 8;    // lanes per token row
+  constexpr int G = 64 / CL;   // lane groups = token rows per load instruction
+  constexpr int NI = 16 / G;   // token rows per lane
+  const int c = lane & (CL - 1), g = lane / CL;
+  uint4 raw[NI];
+  int tok[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    tok[i] = kv ? g * NI + i : i * G + g;
+    raw[i] = *(const uint4*)(src + (size_t)tok[i] * tstride + 8 * c);
+  }
+  uint32_t vcode[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // V: per channel, this lane's tokens' bytes
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+    uint32_t amax = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
+      amax = amax > lo ? amax : lo;
+      amax = amax > hi ? amax : hi;
+    }
+    amax = row_max_u32<CL>(amax);
+    const float a = bf16_bits_to_float(amax);
+    const float s = (amax == 0) ? 0.0f : __fdiv_rn(a, 127.0f);
+    const bool fast = s > 1e-30f;  // rcp of a denormal is not usable
+    const float inv = fast ? __builtin_amdgcn_rcpf(s) : 0.0f;
+    uint32_t kcode[2] = {0, 0};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
+                              : __uint_as_float(w[e >> 1] << 16);
+      const float q = x * inv;
+      float r = __builtin_rintf(q);
+      if (__builtin_expect(!fast || fabsf(q - r) > 0.5f - 4e-5f, 0)) {
+        r = (amax == 0) ? 0.0f : (float)(int8_t)int8_code(x, s);
+      }
+      const float stored = r + 128.0f;  // offset-binary, exact
+      if (kv == 0) kcode[e >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(stored, e & 3, kcode[e >> 2]);
+      else vcode[e] = __builtin_amdgcn_cvt_pk_u8_f32(stored, i, vcode[e]);
+    }
+    if (kv == 0)
+      *(uint2*)(tile + k_elem(off0 + tok[i], 8 * c, bs, D)) = make_uint2(kcode[0], kcode[1]);
+    if (c == 0) srow[tok[i]] = s;
+  }
+  if (kv == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint8_t* row = tile + v_elem(off0, 8 * c + e, bs, D) + g * NI;
+      if constexpr (NI == 4) *(uint32_t*)row = vcode[e];
+      else *(uint16_t*)row = (uint16_t)vcode[e];
+    }
+  }
+}
+
+// unit = (window of 16 consecutive tokens of the call, kv head, K|V): the wavefront handles
+// every run that starts inside its window, so no wavefront is launched only to find that its
+// token is not a run's first.
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void write_int8_bulk_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int windows = (num_tokens + 15) >> 4;
+  if (unit >= (int64_t)windows * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int w0 = (int)((unit >> 1) / H) * 16;
+  // lanes 0..15: is token w0 + lane the first of a run
+  bool first = false;
+  {
+    const int t = w0 + lane;
+    if (lane < 16 && t < num_tokens) {
+      const int64_t slot = slot_mapping[t];
+      if (slot >= 0) {
+        const int so = (int)(slot & 15);
+        first = !(t > 0 && so > 0 && slot_mapping[t - 1] == slot - 1);
+      }
+    }
+  }
+  uint32_t starts = (uint32_t)__ballot(first);
+  const size_t tstride = (size_t)H * D;
+  while (starts) {
+    const int t0 = w0 + __builtin_ctz(starts);
+    starts &= starts - 1;
+    const int64_t slot0 = slot_mapping[t0];
+    const int so = (int)(slot0 & 15);
+    // lanes 0..15: does token t0 + lane continue the run
+    const bool cont = lane < 16 - so && t0 + lane < num_tokens && slot_mapping[t0 + lane] == slot0 + lane;
+    const uint32_t m = (uint32_t)__ballot(cont);
+    const int run = __builtin_ctz(~m);  // lane 0 always continues
+    if (run == 16) {
+      const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
+      const int off0 = (int)(slot0 - blk * bs);
+      int8_subblock<D>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
+                       cache + tile_offset(blk, kv, h, H, bs, D),
+                       scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0, kv, off0, bs, lane);
+    } else {
+      int8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+    }
+  }
+}
+
+// ---- fp8-e4m3, one scale per (block, kv head) ---------------------------------------------
+// unit = (run, kv head, K|V): the consecutive tokens of the call that fall into one block.
+
+// One run of `run` tokens starting at token t0, slot0 (any length, any start inside the block,
+// earlier codes re-expressed if the scale grows): a lane owns D/64 channels of every token.
+template <int D>
+__device__ inline void fp8_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                               uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
+                               int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
+  constexpr int E = D / 64;
+  const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
+  const int o_min = (int)(slot0 - blk * bs);
   const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * E;
   const size_t tstride = (size_t)H * D;
   uint32_t amax = 0;
@@ -236,12 +372,170 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
   if (lane == 0) *sp = s_new;
 }
 
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (unit >= (int64_t)num_tokens * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int t0 = (int)((unit >> 1) / H);
+  const int64_t slot0 = slot_mapping[t0];
+  if (slot0 < 0) return;
+  const int o_min = (int)(slot0 & (bs - 1));
+  if (t0 > 0 && o_min > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
+  int run = 1;
+  while (run < bs - o_min && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
+  fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+}
+
+// ---- fp8, many tokens per call (prefill) ---------------------------------------------------
+// A run made of whole 16-token sub-blocks whose block scale does not force a re-encode of
+// earlier codes (always so when a block is written at once) is handled with 16-byte loads, a
+// lane owning 8 channels of 16 / G tokens as in the int8 prefill kernel: one pass for the
+// run's absmax, a second (the rows now come from the cache) for the codes.
+//
+// Rounding x / s to E4M3: with q = x * rcp(s) in fp32 (relative error below 1.8e-7) and
+// t = |q| / 2^(e-3), e = max(floor(log2 |q|), -6), the code's mantissa is the nearest integer
+// to t in [0, 16]; t is within 3e-6 of the exact value, so unless it lies within 1e-5 of a
+// half-integer its nearest integer is the exact one's.  (Just below a power of two the fast
+// exponent may come out one higher than the exact one; t is then 8 and the code the same.)
+// The rare elements near a half-integer are decided in fp64.
+__device__ inline uint32_t fp8_code_fast(float x, float inv, float s, bool usable) {
+  const float q = x * inv;
+  const float a = fminf(fabsf(q), 448.0f);
+  int e = (int)(__float_as_uint(a) >> 23) - 127;
+  e = e < -6 ? -6 : e;
+  const float t = __builtin_ldexpf(a, 3 - e);
+  const float r = __builtin_rintf(t);
+  if (__builtin_expect(!usable || fabsf(t - r) > 0.5f - 1e-5f, 0))
+    return fp8_code((double)x / (double)s);
+  return ((__float_as_uint(q) >> 24) & 0x80u) | (uint32_t)(((e + 7) << 3) + (int)r - 8);
+}
+
+template <int D>
+__device__ inline void fp8_subblocks(const uint16_t* __restrict__ src, size_t tstride,
+                                     uint8_t* __restrict__ tile, float* __restrict__ sp, int kv,
+                                     int o_min, int run, int bs, int lane, bool& done) {
+  constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
+  const int c = lane & (CL - 1), g = lane / CL;
+  int tok[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) tok[i] = kv ? g * NI + i : i * G + g;
+  uint32_t amax = 0;
+  for (int sb = 0; sb < run; sb += 16) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
+        amax = amax > lo ? amax : lo;
+        amax = amax > hi ? amax : hi;
+      }
+    }
+  }
+  amax = wave_max_u32(amax);
+  const float s_prev = (o_min > 0) ? *sp : 0.0f;
+  const float s_cand = (amax == 0) ? 0.0f : __fdiv_rn(bf16_bits_to_float(amax), 448.0f);
+  const float s_new = s_prev > s_cand ? s_prev : s_cand;
+  done = !(o_min > 0 && s_new > s_prev && s_prev > 0.0f);
+  if (!done) return;  // earlier codes must be re-expressed: the general routine does the run
+  const bool usable = s_new > 1e-30f;  // rcp of a denormal is not usable
+  const float inv = usable ? __builtin_amdgcn_rcpf(s_new) : 0.0f;
+  for (int sb = 0; sb < run; sb += 16) {
+    uint32_t vcode[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      uint32_t kcode[2] = {0, 0};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
+                                : __uint_as_float(w[e >> 1] << 16);
+        const uint32_t code = (s_new > 0.0f) ? fp8_code_fast(x, inv, s_new, usable) : 0u;
+        if (kv == 0) kcode[e >> 2] |= code << (8 * (e & 3));
+        else vcode[e] |= code << (8 * i);
+      }
+      if (kv == 0)
+        *(uint2*)(tile + k_elem(o_min + sb + tok[i], 8 * c, bs, D)) = make_uint2(kcode[0], kcode[1]);
+    }
+    if (kv == 1) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint8_t* row = tile + v_elem(o_min + sb, 8 * c + e, bs, D) + g * NI;
+        if constexpr (NI == 4) *(uint32_t*)row = vcode[e];
+        else *(uint16_t*)row = (uint16_t)vcode[e];
+      }
+    }
+  }
+  if (lane == 0) *sp = s_new;
+}
+
+// unit = (window of 16 consecutive tokens of the call, kv head, K|V), as for int8
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int windows = (num_tokens + 15) >> 4;
+  if (unit >= (int64_t)windows * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int w0 = (int)((unit >> 1) / H) * 16;
+  bool first = false;
+  {
+    const int t = w0 + lane;
+    if (lane < 16 && t < num_tokens) {
+      const int64_t slot = slot_mapping[t];
+      if (slot >= 0)
+        first = !(t > 0 && (slot & (bs - 1)) > 0 && slot_mapping[t - 1] == slot - 1);
+    }
+  }
+  uint32_t starts = (uint32_t)__ballot(first);
+  const size_t tstride = (size_t)H * D;
+  while (starts) {
+    const int t0 = w0 + __builtin_ctz(starts);
+    starts &= starts - 1;
+    const int64_t slot0 = slot_mapping[t0];
+    const int o_min = (int)(slot0 & (bs - 1));
+    int run = 0;
+    for (int base = 0; base < bs - o_min; base += 64) {  // block sizes reach 128
+      const int j = base + lane;
+      const bool cont = j < bs - o_min && t0 + j < num_tokens && slot_mapping[t0 + j] == slot0 + j;
+      const unsigned long long m = __ballot(cont);
+      const int n = m == ~0ull ? 64 : __builtin_ctzll(~m);
+      run += n;
+      if (n < 64) break;
+    }
+    bool done = false;
+    if (((o_min | run) & 15) == 0) {
+      const int64_t blk = slot0 >> __builtin_ctz(bs);
+      fp8_subblocks<D>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
+                       cache + tile_offset(blk, kv, h, H, bs, D),
+                       scales + ((size_t)blk * 2 + kv) * H + h, kv, o_min, run, bs, lane, done);
+    }
+    if (!done) fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mapping,
                         int32_t num_tokens, void* cache, float* scales,
                         const kvq_cache_desc_t& desc, hipStream_t stream) {
-  const int64_t units = (int64_t)num_tokens * desc.num_kv_heads * 2;
+  // many tokens (a prompt): a wavefront per window of 16 tokens; few (a decode step): a
+  // wavefront per token, so that runs are handled in parallel rather than one after another
+  const bool bulk = num_tokens >= kBulkTokens;
+  const int64_t units =
+      (int64_t)(bulk ? (num_tokens + 15) / 16 : num_tokens) * desc.num_kv_heads * 2;
   const unsigned grid = (unsigned)((units + kWaves - 1) / kWaves);
   const dim3 block(kWaves * 64);
   const uint16_t* kk = (const uint16_t*)k;
@@ -250,7 +544,13 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
 #define KVQ_LAUNCH_WRITE(KERNEL, DD)                                                          \
   hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
                      num_tokens, c, scales, desc.num_kv_heads, desc.block_size)
-  if (desc.mode == KVQ_INT8_TOKEN_HEAD) {
+  if (bulk && desc.mode == KVQ_INT8_TOKEN_HEAD) {
+    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 128);
+    else KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 64);
+  } else if (bulk) {
+    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_fp8_bulk_kernel, 128);
+    else KVQ_LAUNCH_WRITE(write_fp8_bulk_kernel, 64);
+  } else if (desc.mode == KVQ_INT8_TOKEN_HEAD) {
     if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_kernel, 128);
     else KVQ_LAUNCH_WRITE(write_int8_kernel, 64);
   } else {

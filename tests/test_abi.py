@@ -64,6 +64,10 @@ def test_write_argument_checks():
     assert L.kv_quant_write(FAKE, FAKE, FAKE, 4, FAKE, FAKE, None, None) == kvq.E_NULLPTR
     assert L.kv_quant_write(FAKE, FAKE, FAKE, -1, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
     assert L.kv_quant_write(None, None, None, 0, None, None, C.byref(ok), None) == kvq.OK
+    odd = C.c_void_p(0x1008)                               # k, v and cache: 16-byte aligned
+    assert L.kv_quant_write(odd, FAKE, FAKE, 4, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
+    assert L.kv_quant_write(FAKE, odd, FAKE, 4, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
+    assert L.kv_quant_write(FAKE, FAKE, FAKE, 4, odd, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
     for i in range(5):
         args = [FAKE, FAKE, FAKE, 4, FAKE, FAKE]
         args[i if i < 3 else i + 1] = None

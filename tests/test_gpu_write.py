@@ -52,6 +52,50 @@ def test_ragged_shapes_bulk_write(mode, shape):
     assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
 
 
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1)])
+def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
+    """Thousands of tokens in one call (the prefill kernels): ragged sequences back to back, so
+    that runs start at any token index; one sequence continued from the middle of a block;
+    skipped tokens; rows full of rounding ties, tiny and huge rows."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    lens = [700, 33, 1, 1234, 16, 515, 47]
+    wl = W.custom("prefill", mode, lens, 1, H, H, D, bs, seed=31 + bs + D + mode)
+    desc = gpu_desc(wl)
+    cache, scales = kvq.alloc_cache(desc)
+    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, bs, H, D)
+    # sequence 3's first 21 tokens were written by an earlier call
+    k, v = wl.kv_rows(3, 0, 21)
+    s = wl.slots(3, 0, 21)
+    oracle.kv_quant_write(k, v, s, oc, osc, mode)
+    kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v), torch.from_numpy(s).cuda(),
+                       cache, scales, desc)
+    ks, vs, ss = [], [], []
+    for b, L in enumerate(lens):
+        lo = 21 if b == 3 else 0
+        k, v = wl.kv_rows(b, lo, L)
+        kf, vf = W.bf16_bits_to_f32(k), W.bf16_bits_to_f32(v)
+        if b == 0:
+            qmax = 127.0 if mode == 0 else 448.0
+            vf[64:128] = np.round(vf[64:128] * 16) / 2   # half-integers ...
+            vf[64:128, :, 0] = qmax                      # ... at scale exactly 1: ties
+            kf[128:160] *= np.float32(2.0 ** -120)       # scales below the normal fp32 range
+            kf[160:192] *= np.float32(2.0 ** 110)
+            kf[200:216] = 0
+        s = wl.slots(b, lo, L)
+        if b == 5:
+            s[-3:] = -1                                  # skipped tokens at a run's end
+        ks.append(W.to_bf16_bits(kf)), vs.append(W.to_bf16_bits(vf)), ss.append(s)
+    k, v, s = np.concatenate(ks), np.concatenate(vs), np.concatenate(ss)
+    assert len(s) >= 2048
+    oracle.kv_quant_write(k, v, s, oc, osc, mode)
+    kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v), torch.from_numpy(s).cuda(),
+                       cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
+
+
 @pytest.mark.parametrize("bs,D", [(16, 128), (64, 64)])
 def test_fp8_token_by_token_append_with_rescale(bs, D):
     """Decode-style appends: each call adds one token per sequence; magnitudes vary so that the
