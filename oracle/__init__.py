@@ -9,6 +9,8 @@ Arrays use the oracle's canonical layout:
   scales float32 [num_blocks, 2, num_kv_heads, block_size]   mode 0 (int8 per token-head)
          float32 [num_blocks, 2, num_kv_heads]               mode 1 (fp8-e4m3 per block-head)
   k, v, q uint16 bf16 bit patterns [tokens, heads, head_dim]
+Mode 2 is the unquantized baseline: cache uint16 (bf16 bit patterns), same shape; scales is an
+empty float32 array.
 """
 import ctypes as C
 
@@ -18,6 +20,7 @@ from . import build as _build
 
 MODE_INT8 = 0
 MODE_FP8 = 1
+MODE_BF16 = 2
 
 _lib = None
 
@@ -112,22 +115,33 @@ def scale(absmax, qmax):
 
 def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
     """Zero-filled canonical cache and scales."""
-    cache = np.zeros((num_blocks, 2, num_kv_heads, block_size, head_dim), dtype=np.uint8)
-    if mode == MODE_INT8:
+    cache = np.zeros((num_blocks, 2, num_kv_heads, block_size, head_dim),
+                     dtype=np.uint16 if mode == MODE_BF16 else np.uint8)
+    if mode == MODE_BF16:
+        scales = np.zeros((0,), dtype=np.float32)
+    elif mode == MODE_INT8:
         scales = np.zeros((num_blocks, 2, num_kv_heads, block_size), dtype=np.float32)
     else:
         scales = np.zeros((num_blocks, 2, num_kv_heads), dtype=np.float32)
     return cache, scales
 
 
+def _chk_cache(cache, scales, mode):
+    _chk(cache, np.uint16 if mode == MODE_BF16 else np.uint8, "cache")
+    _chk(scales, np.float32, "scales")
+    nblk, two, H, bs, D = cache.shape
+    assert two == 2
+    assert scales.shape == {MODE_INT8: (nblk, 2, H, bs), MODE_FP8: (nblk, 2, H),
+                            MODE_BF16: (0,)}[mode]
+
+
 def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
     """In-place write of bf16 rows k, v [T, H_kv, D] at slot_mapping [T] (int64)."""
     _chk(k, np.uint16, "k"), _chk(v, np.uint16, "v")
     _chk(slot_mapping, np.int64, "slot_mapping")
-    _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    _chk_cache(cache, scales, mode)
     nblk, two, H, bs, D = cache.shape
-    assert two == 2 and k.shape == v.shape == (slot_mapping.shape[0], H, D)
-    assert scales.shape == ((nblk, 2, H, bs) if mode == MODE_INT8 else (nblk, 2, H))
+    assert k.shape == v.shape == (slot_mapping.shape[0], H, D)
     live = slot_mapping[slot_mapping >= 0]
     assert live.size == 0 or int(live.max()) < nblk * bs
     rc = lib().oracle_kv_quant_write(_ptr(k), _ptr(v), _ptr(slot_mapping), k.shape[0],
@@ -139,6 +153,8 @@ def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
 def dequant(cache, scales, mode):
     """Dequantized fp64 value of every logical element, same shape as cache."""
     nblk, _, H, bs, D = cache.shape
+    if mode == MODE_BF16:
+        return bf16_to_f64(cache)
     if mode == MODE_INT8:
         return cache.view(np.int8).astype(np.float64) * scales.astype(np.float64)[..., None]
     table = fp8_decode(np.arange(256, dtype=np.uint8))
@@ -147,7 +163,7 @@ def dequant(cache, scales, mode):
 
 def gather_dequant(cache, scales, mode, block_table_row, n, kv, h):
     """Dense fp64 [n, D] of K (kv=0) or V (kv=1) of one sequence and kv head."""
-    _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    _chk_cache(cache, scales, mode)
     row = np.ascontiguousarray(block_table_row, dtype=np.int32)
     nblk, _, H, bs, D = cache.shape
     assert (n + bs - 1) // bs <= row.shape[0]
@@ -160,7 +176,7 @@ def gather_dequant(cache, scales, mode, block_table_row, n, kv, h):
 
 def paged_decode_attn(q, cache, scales, mode, block_tables, seq_lens, q_len, sm_scale):
     """out float64 [batch*q_len, H_q, D]."""
-    _chk(q, np.uint16, "q"), _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    _chk(q, np.uint16, "q"), _chk_cache(cache, scales, mode)
     _chk(block_tables, np.int32, "block_tables"), _chk(seq_lens, np.int32, "seq_lens")
     nblk, _, H, bs, D = cache.shape
     batch = seq_lens.shape[0]
@@ -183,7 +199,7 @@ def paged_decode_attn(q, cache, scales, mode, block_tables, seq_lens, q_len, sm_
 def attn_weights(q, cache, scales, mode, block_table_row, seq_len, q_len, j, hq, q_token_index,
                  sm_scale):
     """Softmax weights of one (sequence, query token j, q head hq): float64 [n]."""
-    _chk(q, np.uint16, "q"), _chk(cache, np.uint8, "cache"), _chk(scales, np.float32, "scales")
+    _chk(q, np.uint16, "q"), _chk_cache(cache, scales, mode)
     row = np.ascontiguousarray(block_table_row, dtype=np.int32)
     nblk, _, H, bs, D = cache.shape
     n = seq_len - q_len + j + 1

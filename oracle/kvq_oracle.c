@@ -17,8 +17,10 @@
  *
  * Layout used by the oracle (the "canonical logical layout"):
  *   cache : u8  [num_blocks][2 (0=K,1=V)][num_kv_heads][block_size][head_dim]
+ *           (mode 2: u16 bf16 bit patterns, same shape)
  *   scales: f32 [num_blocks][2][num_kv_heads][block_size]      (mode 0, int8)
  *           f32 [num_blocks][2][num_kv_heads]                  (mode 1, fp8)
+ *           unused                                             (mode 2)
  *   k, v, q : bf16 bit patterns (uint16), [tokens][heads][head_dim]
  *   out     : f64 [batch*q_len][num_q_heads][head_dim]
  *
@@ -34,6 +36,9 @@
 
 #define ORACLE_MODE_INT8 0
 #define ORACLE_MODE_FP8 1
+/* The unquantized cache the paper's Section 8.5 measures its quantized one against ("BF16
+ * KV cache" baseline): the rows are stored as they are. */
+#define ORACLE_MODE_BF16 2
 
 /* ---- O1: a bf16 bit pattern is the top half of an fp32; widening is exact ---- */
 double oracle_bf16_to_f64(uint16_t bits) {
@@ -144,6 +149,20 @@ int oracle_kv_quant_write(const uint16_t* k, const uint16_t* v, const int64_t* s
     }
     return 0;
   }
+  if (mode == ORACLE_MODE_BF16) {
+    uint16_t* cache16 = (uint16_t*)cache;
+    for (int32_t t = 0; t < num_tokens; ++t) {
+      int64_t slot = slot_mapping[t];
+      if (slot < 0) continue;
+      int64_t blk = slot / bs;
+      int off = (int)(slot % bs);
+      for (int kv = 0; kv < 2; ++kv)
+        for (int h = 0; h < H; ++h)
+          memcpy(cache16 + tile_index(blk, kv, h, H, bs, D) + (size_t)off * D,
+                 (kv ? v : k) + ((size_t)t * H + h) * D, sizeof(uint16_t) * (size_t)D);
+    }
+    return 0;
+  }
   if (mode != ORACLE_MODE_FP8) return -1;
 
   /* mode 1: visit each touched block once, in order of first appearance. */
@@ -214,6 +233,9 @@ double oracle_dequant_at(const uint8_t* cache, const float* scales, int32_t mode
                          int kv, int h, int off, int d, int32_t block_size,
                          int32_t num_kv_heads, int32_t head_dim) {
   const int H = num_kv_heads, D = head_dim, bs = block_size;
+  if (mode == ORACLE_MODE_BF16)
+    return oracle_bf16_to_f64(
+        ((const uint16_t*)cache)[tile_index(blk, kv, h, H, bs, D) + (size_t)off * D + d]);
   uint8_t c = cache[tile_index(blk, kv, h, H, bs, D) + (size_t)off * D + d];
   if (mode == ORACLE_MODE_INT8) {
     double s = (double)scales[(((size_t)blk * 2 + kv) * H + h) * bs + off];

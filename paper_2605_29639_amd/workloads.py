@@ -16,6 +16,7 @@ import numpy as np
 
 MODE_INT8 = 0  # int8 codes, one fp32 scale per (token, kv head)
 MODE_FP8 = 1   # fp8-e4m3 codes, one fp32 scale per (block, kv head)
+MODE_BF16 = 2  # the unquantized baseline: bf16 rows stored as they are, no scales
 
 BASE_SEED = 26052963900
 
@@ -112,6 +113,8 @@ class Workload:
         H, D, bs = self.num_kv_heads, self.head_dim, self.block_size
         if self.mode == MODE_INT8:
             per_token_head = 2.0 * (D + 4)
+        elif self.mode == MODE_BF16:
+            per_token_head = 4.0 * D
         else:
             per_token_head = 2.0 * D + 8.0 / bs
         kv = self.unique_tokens() * H * per_token_head

@@ -47,6 +47,39 @@ def test_tiny_config_equals_dense_brute_force(mode):
     assert rel < (0.005 if mode == W.MODE_INT8 else 0.07)
 
 
+def test_unquantized_mode_is_attention_over_the_original_rows():
+    """Mode 2 stores the bf16 rows as they are, so the checker's output must be the dense
+    attention over the workload's own K and V, gathered here without the checker: this pins
+    its slot indexing, table walk and attention loops with no quantization in between."""
+    wl = W.custom("plain", W.MODE_BF16, [37, 100, 5], 2, 4, 2, 64, 16, seed=12)
+    cache, scales = oracle_fill(wl)
+    assert cache.dtype == np.uint16 and scales.size == 0
+    out = run(wl, cache, scales)
+    G = wl.group
+    for b in range(wl.batch):
+        L = int(wl.seq_lens[b])
+        k, v = wl.kv_rows(b, 0, L)
+        for j in range(wl.q_len):
+            n = L - wl.q_len + j + 1
+            q = oracle.bf16_to_f64(wl.q[b * wl.q_len + j])
+            for h in range(wl.num_kv_heads):
+                want, _ = brute.dense_attention(q[h * G:(h + 1) * G],
+                                                oracle.bf16_to_f64(k[:n, h]),
+                                                oracle.bf16_to_f64(v[:n, h]), wl.sm_scale)
+                assert np.allclose(out[b * wl.q_len + j, h * G:(h + 1) * G], want, rtol=0, atol=1e-13)
+    # the stored bits are the rows' bits, at the slots the table names
+    k, v = wl.kv_rows(1, 0, 100)
+    for p in (0, 15, 16, 99):
+        blk, off = wl.block_tables[1][p // 16], p % 16
+        assert np.array_equal(cache[blk, 0, :, off], k[p]) and np.array_equal(cache[blk, 1, :, off], v[p])
+    # and quantized attention stays near it (one K channel of the 128 is 20x larger than the
+    # rest, which costs int8 per token-head a few percent)
+    wq = W.custom("plain", W.MODE_INT8, [37, 100, 5], 2, 4, 2, 64, 16, seed=12)
+    assert np.array_equal(wq.q, wl.q)
+    cq, sq = oracle_fill(wq)
+    assert np.abs(run(wq, cq, sq) - out).max() < 0.10 * np.abs(out).max()
+
+
 def test_weights_are_a_probability_vector():
     wl = W.tiny()
     cache, scales = oracle_fill(wl)
