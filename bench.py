@@ -43,12 +43,15 @@ class HipEvents:
         return ms.value
 
 
+MODE_NAMES = {0: "int8", 1: "fp8", 2: "bf16"}
+
+
 def measured_traffic(wl):
     """HBM bytes per launch of the streaming kernel for this workload, from the committed
     rocprofv3 FETCH_SIZE / WRITE_SIZE summary (profiles/traffic.json), or None."""
     try:
         table = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
-        key = "%s/%s" % (wl.name, "int8" if wl.mode == 0 else "fp8")
+        key = "%s/%s" % (wl.name, MODE_NAMES[wl.mode])
         return table[key]["hbm_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         return None
@@ -56,7 +59,8 @@ def measured_traffic(wl):
 
 def make_workload(name, mode):
     from paper_2605_29639_amd import workloads as W
-    kw = {} if mode is None else {"mode": {"int8": W.MODE_INT8, "fp8": W.MODE_FP8}[mode]}
+    kw = {} if mode is None else {"mode": {"int8": W.MODE_INT8, "fp8": W.MODE_FP8,
+                                           "bf16": W.MODE_BF16}[mode]}
     if name == "llama8b":
         return W.llama8b(**kw)
     if name == "fp8_append":
@@ -76,11 +80,13 @@ def main():
     ap.add_argument("--prewarm-s", type=float, default=0.5,
                     help="seconds of untimed load before the warmup steps")
     ap.add_argument("--workload", default="llama8b")
-    ap.add_argument("--mode", default=None, choices=["int8", "fp8"],
-                    help="override the workload's quantization mode")
+    ap.add_argument("--mode", default=None, choices=["int8", "fp8", "bf16"],
+                    help="override the workload's cache mode (bf16 = the unquantized baseline)")
     ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
     ap.add_argument("--chunk", type=int, default=-1, help="split-K granule in tokens (-1 or 0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16-baseline", action="store_true",
+                    help="skip timing the same workload over an unquantized (bf16) cache")
     ap.add_argument("--alias-blocks", type=int, default=0,
                     help="diagnostic: fold every block-table entry modulo this many blocks so that "
                          "all reads hit the caches (shows the kernel's pure issue time); the "
@@ -228,9 +234,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8 codes, f16 MFMA operands, f32 accumulate",
+        "dtype": ("bf16 rows, bf16 MFMA operands, f32 accumulate" if wl.mode == 2 else
+                  "u8 codes, f16 MFMA operands, f32 accumulate"),
         "data": "synthetic" if not args.alias_blocks else "INVALID: aliased block tables (diagnostic)",
-        "config": {"workload": wl.name, "mode": "int8_token_head" if wl.mode == 0 else "fp8e4m3_block_head",
+        "config": {"workload": wl.name, "mode": {0: "int8_token_head", 1: "fp8e4m3_block_head", 2: "bf16_unquantized"}[wl.mode],
                    "batch": B, "q_len": wl.q_len, "num_q_heads": Hq, "num_kv_heads": wl.num_kv_heads,
                    "head_dim": D, "block_size": wl.block_size, "sum_seq_lens": int(wl.seq_lens.sum()),
                    "max_seq_len": max_len, "chunk_tokens": chunk or "auto (even split over 2048 wavefronts)",
@@ -278,12 +285,69 @@ def main():
     te1.record()
     torch.cuda.synchronize()
     bulk_s = te0.elapsed_time(te1) / 10 * 1e-3
-    per_row = 2 * D + D + (4 if wl.mode == 0 else 4.0 / wl.block_size)
+    per_row = 2 * D + {0: D + 4, 1: D + 4.0 / wl.block_size, 2: 2 * D}[wl.mode]
     bulk_bytes = n_tok * wl.num_kv_heads * 2 * per_row
     result["prefill_write"] = {"tokens": n_tok, "sequences": n_seq, "us": bulk_s * 1e6,
                                "bytes": bulk_bytes, "GB/s": bulk_bytes / bulk_s / 1e9,
                                "tokens_per_s": n_tok / bulk_s}
     del k_bulk, v_bulk, s_bulk
+
+    # The same step over an unquantized cache (the paper's Section 8.5 baseline): same shapes,
+    # lengths, tables and K/V values, the rows stored as bf16.  Timed like the step and like
+    # the streaming kernel above; the ratio is the kernel-level form of the paper's claim that
+    # the quantized cache relieves decode of half its memory traffic.
+    step(1)  # (the second layer cache: the prefill measurement above rewrote part of the first)
+    torch.cuda.synchronize()
+    out_main = out.cpu().numpy()  # the measured path's output, for the parity figure below
+    if wl.mode != 2 and not args.no_bf16_baseline:
+        del caches, cache0, scales0, cache, scales
+        torch.cuda.empty_cache()
+        wl2 = make_workload(args.workload, "bf16")
+        alg2 = wl2.algorithmic_bytes()
+        layers2 = args.layers or max(2, int(np.ceil(4 * 256e6 / alg2["kv"])))
+        caches2 = []
+        for _ in range(layers2):
+            c2, s2, desc2 = gpu_fill(wl2)
+            caches2.append((c2, s2))
+        ws2 = kvq.alloc_workspace(desc2, B, wl.q_len, Hq, max_len, chunk)
+
+        def step2(i, write=True):
+            c2, s2 = caches2[i % layers2]
+            if write:
+                kvq.kv_quant_write(k_new, v_new, slots_new, c2, s2, desc2, stream=stream)
+            kvq.paged_decode_attn(q, c2, s2, desc2, bt, sl, wl.q_len, max_len, wl.sm_scale, out,
+                                  ws2, chunk_tokens=chunk, stream=stream)
+        for i in range(args.warmup + 20):
+            step2(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step2(i)
+        torch.cuda.synchronize()
+        step2_s = (time.perf_counter() - t0) / args.steps
+        L.kvq_profile_skip_reduce(1)
+        for i in range(args.warmup):
+            step2(i, write=False)
+        torch.cuda.synchronize()
+        assert ev.hip.hipEventRecord(e0, hip_stream) == 0
+        for i in range(args.steps):
+            step2(i, write=False)
+        assert ev.hip.hipEventRecord(e1, hip_stream) == 0
+        torch.cuda.synchronize()
+        L.kvq_profile_skip_reduce(0)
+        kern2_s = ev.elapsed_ms(e0, e1) * 1e-3 / args.steps
+        result["bf16_baseline"] = {
+            "us_per_layer": step2_s * 1e6, "kernel_us_mean": kern2_s * 1e6,
+            "algorithmic_bytes": alg2["total"], "GB/s": alg2["total"] / step2_s / 1e9,
+            "kernel_GB/s": alg2["total"] / kern2_s / 1e9,
+            "step_time_ratio_quantized_to_bf16": step_s / step2_s,
+            "kernel_time_ratio_quantized_to_bf16": kern_s / kern2_s,
+            "bytes_ratio_quantized_to_bf16": alg["total"] / alg2["total"],
+            # how far quantization moves the output on this synthetic data (1 % of the K
+            # channels are 20x outliers): max |quantized - bf16| / max |bf16|
+            "output_deviation_quantized_vs_bf16": attn_err(out_main, out.cpu().numpy().astype(np.float64))}
+        del caches2, c2, s2, ws2
+        torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
         import oracle
@@ -314,7 +378,7 @@ def main():
         cpu_s = float(np.median(times))
         frac = tok / float(wl.seq_lens.sum())
         sample_bytes = alg["total"] * frac
-        got = out.cpu().numpy()[:n_seq * wl.q_len]
+        got = out_main[:n_seq * wl.q_len]
         result["cpu_baseline"] = {
             "value": sample_bytes / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
             "kind": "oracle",

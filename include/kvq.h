@@ -35,8 +35,12 @@ extern "C" {
 
 typedef enum {
   KVQ_INT8_TOKEN_HEAD = 0,    /* int8 codes in [-127,127], one fp32 scale per (token, kv head) */
-  KVQ_FP8E4M3_BLOCK_HEAD = 1  /* OCP E4M3 (finite-only, max 448) codes, one fp32 scale per
+  KVQ_FP8E4M3_BLOCK_HEAD = 1, /* OCP E4M3 (finite-only, max 448) codes, one fp32 scale per
                                  (cache block, kv head) */
+  KVQ_BF16_PLAIN = 2          /* no quantization: the bf16 rows as they are, no scales.  The
+                                 baseline the paper's Section 8.5 measures its quantized
+                                 cache against ("BF16 KV cache"); same entry points, twice
+                                 the bytes */
 } kvq_mode_t;
 
 enum {
@@ -64,6 +68,12 @@ enum {
  * offset-binary form (stored byte = code XOR 0x80 = code + 128); e4m3 codes are stored as is.
  * kvq_cache_to_canonical / kvq_cache_from_canonical convert to and from the plain
  * [num_blocks][2][num_kv_heads][block_size][head_dim] order.
+ * KVQ_BF16_PLAIN: 2-byte elements, tile = (...) * block_size * head_dim * 2 bytes and, in
+ * elements inside a tile,
+ *     K:  (off/4) * 4*head_dim + (d/8) * 32 + (off%4) * 8 + d%8
+ *     V:  (off/16) * 16*head_dim + ((off%16)/8) * 8*head_dim + d * 8 + off%8
+ * (the same idea with 8-element pieces); there is no scales buffer (its size is 0 and the
+ * `scales` arguments are ignored and may be NULL).
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
  *         f32 [num_blocks][2][num_kv_heads]               for KVQ_FP8E4M3_BLOCK_HEAD
  * Supported: head_dim 64 or 128; block_size a power of two in [16, 256]. */
@@ -90,6 +100,7 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
  * KVQ_INT8_TOKEN_HEAD: per (token, kv head), separately for K and V: scale = fp32 nearest to
  *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
  *   exact x/scale, clamped to [-127, 127].
+ * KVQ_BF16_PLAIN: the rows are copied to their slots unchanged.
  * KVQ_FP8E4M3_BLOCK_HEAD: the tokens of this call that fall into one block must be
  *   consecutive in token order with consecutive increasing slots (append order).  For each
  *   such run, per kv head, separately for K and V: s_prev = the stored block scale if the
@@ -141,7 +152,7 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
 
 /* Conversions between the physical cache above and the canonical
  * [num_blocks][2][num_kv_heads][block_size][head_dim] array of plain codes (int8 two's
- * complement / e4m3 bytes); both device, kvq_cache_bytes() long, must not overlap.  Used by
+ * complement / e4m3 bytes / bf16 bit patterns); both device, kvq_cache_bytes() long, must not overlap.  Used by
  * tests and tools; not on the hot path. */
 int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,
                            void* stream);

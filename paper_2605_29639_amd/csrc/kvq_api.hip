@@ -8,7 +8,8 @@ namespace {
 
 bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   if (!d) { *err = KVQ_E_NULLPTR; return false; }
-  if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD) {
+  if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD &&
+      d->mode != KVQ_BF16_PLAIN) {
     *err = KVQ_E_BAD_MODE;
     return false;
   }
@@ -55,7 +56,9 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   if (chunk_tokens == 0) {
     // even split over as many wavefronts as an MI355X keeps resident at this kernel's
     // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
-    const int64_t resident = plan->row_tiles == 1 ? kAutoWaves : kAutoWaves / 2;
+    // (an unquantized cache needs twice the registers per group: one wavefront per SIMD)
+    const int64_t resident =
+        plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN ? kAutoWaves : kAutoWaves / 2;
     plan->range_groups = 0;
     plan->num_waves = (int32_t)(flat_max < resident ? flat_max : resident);
   } else {
@@ -78,12 +81,13 @@ extern "C" {
 size_t kvq_cache_bytes(const kvq_cache_desc_t* desc) {
   int err;
   if (!desc_ok(desc, &err)) return 0;
-  return (size_t)desc->num_blocks * 2 * desc->num_kv_heads * desc->block_size * desc->head_dim;
+  return (size_t)desc->num_blocks * 2 * desc->num_kv_heads * desc->block_size * desc->head_dim *
+         kvq::elem_bytes(desc->mode);
 }
 
 size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
   int err;
-  if (!desc_ok(desc, &err)) return 0;
+  if (!desc_ok(desc, &err) || desc->mode == KVQ_BF16_PLAIN) return 0;
   const size_t per_block = (size_t)2 * desc->num_kv_heads *
                            (desc->mode == KVQ_INT8_TOKEN_HEAD ? desc->block_size : 1);
   return (size_t)desc->num_blocks * per_block * sizeof(float);
@@ -96,7 +100,8 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
   if (!desc_ok(desc, &err)) return err;
   if (num_tokens < 0) return KVQ_E_BAD_SHAPE;
   if (num_tokens == 0) return KVQ_OK;
-  if (!k || !v || !slot_mapping || !cache || !scales) return KVQ_E_NULLPTR;
+  if (!k || !v || !slot_mapping || !cache) return KVQ_E_NULLPTR;
+  if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
   if ((((uintptr_t)k | (uintptr_t)v | (uintptr_t)cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const hipError_t e = kvq::launch_write(k, v, slot_mapping, num_tokens, cache, scales, *desc,
                                          (hipStream_t)stream);
@@ -128,7 +133,8 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
     return KVQ_E_BAD_SHAPE;
   if (batch == 0) return KVQ_OK;
   if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
-  if (!q || !cache || !scales || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
+  if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
+  if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
   const size_t need = (plan.acc_floats + plan.ml_floats) * sizeof(float);
   if (need > 0) {
     if (!workspace) return KVQ_E_NULLPTR;

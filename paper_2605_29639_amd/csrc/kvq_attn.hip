@@ -46,6 +46,7 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef short short2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr float kPOffset = 10.0f;   // probabilities are scaled by 2^10 (cancels in acc / l)
 constexpr float kMinVScale = 7.888609052210118e-31f;  // 2^-100
@@ -148,9 +149,14 @@ __device__ inline int range_of(int f, int requested, int flat_groups, int num_wa
 // an XOR of the loaded words (one dword per wavefront is stored so that the loads stay).
 template <int MODE, int D, int NT, bool CEIL, int DEPTH>
 __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
+  constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
+  constexpr int EB = PLAIN ? 2 : 1;                // bytes per cache element
   constexpr int DT = D / 16;
-  constexpr int KJ = D / 64;
-  constexpr int KS = D / 32;  // MFMA steps over the channels
+  constexpr int KJ = D * EB / 64;  // 16-byte K pieces per lane and quad
+  constexpr int VW = DT * EB;      // 16-byte V pieces per lane
+  constexpr int KS = D / 32;       // MFMA steps over the channels
+  // matrix-instruction operand of 8 values: f16 (from codes) or the cache's own bf16
+  using Operand = std::conditional_t<PLAIN, bf16x8, half8>;
   const int lane = threadIdx.x;
   const int m16 = lane & 15, g4 = lane >> 4;
   const int w = blockIdx.x;
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads, NRG = p.num_row_groups;
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
-  const uint32_t tile_bytes = (uint32_t)bs * D;
+  const uint32_t tile_bytes = (uint32_t)bs * D * EB;
   const int sbk = m16 >> 2;  // sub-block this lane reads K from
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;  // bytes per cache block
   const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3);  // inside a 4-token quad
@@ -244,25 +250,35 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
     const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
     const uint8_t* kbase =
-        cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * D + k_lane);
-    vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * D);
+        cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * (D * EB) + k_lane);
+    vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * (D * EB));
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int j = 0; j < KJ; ++j) kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * 4 * D + 256 * j));
-    const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? h * bs + m16 + off_v : h;
-    const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
-    sk = __builtin_nontemporal_load(sp);
-    sv = __builtin_nontemporal_load(sp + s_kv);
+      for (int j = 0; j < KJ; ++j)
+        kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * D * EB) + 256 * j));
+    if constexpr (PLAIN) {
+      sk = 1.0f;
+      sv = 1.0f;
+    } else {
+      const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? h * bs + m16 + off_v : h;
+      const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
+      sk = __builtin_nontemporal_load(sp);
+      sv = __builtin_nontemporal_load(sp + s_kv);
+    }
   };
-  auto load_v = [&](uintx4 (&vt)[DT], const uint8_t* vbase) {
+  // (unquantized: piece 2 tt + half is channel tile tt, tokens 8 half .. 8 half + 7)
+  auto load_v = [&](uintx4 (&vt)[VW], const uint8_t* vbase) {
 #pragma unroll
-    for (int tt = 0; tt < DT; ++tt) vt[tt] = __builtin_nontemporal_load((const uintx4*)(vbase + 256 * tt));
+    for (int x = 0; x < VW; ++x) {
+      const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
+      vt[x] = __builtin_nontemporal_load((const uintx4*)(vbase + at));
+    }
   };
 
   // ---- per-pair state: q as the B operand of QK^T, each row's causal length, the running
   // maximum / sum / accumulator ----
-  half8 qb[NT][KS];
+  Operand qb[NT][KS];
   int nrow[NT];
   floatx4 acc[NT][DT];
   float m_run[NT], l_run[NT];
@@ -281,14 +297,19 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
           p.q + (((size_t)c.b * p.q_len + j) * p.num_q_heads + (size_t)h * p.group + gi) * D;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const int d0 = 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+        // the 8 channels this lane contributes to step s: the ones its K pieces hold
+        const int d0 = PLAIN ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
         const uintx4 raw = *(const uintx4*)(qrow + d0);
+        if constexpr (PLAIN) {
+          qb[nt][s] = __builtin_bit_cast(bf16x8, live ? raw : uintx4{0u, 0u, 0u, 0u});
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
-          const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
-          qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
-          qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+          for (int e = 0; e < 4; ++e) {
+            const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
+            const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
+            qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
+            qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+          }
         }
       }
       m_run[nt] = -INFINITY;
@@ -347,12 +368,19 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
       for (int j = 0; j < KJ; ++j) {
         const uintx4 raw = kt[u][j];
-        const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
-        const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
+        if constexpr (PLAIN) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, qb[nt][2 * j], S[nt][u], 0, 0, 0);
-          S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, qb[nt][2 * j + 1], S[nt][u], 0, 0, 0);
+          for (int nt = 0; nt < NT; ++nt)
+            S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[nt][j], S[nt][u], 0, 0, 0);
+        } else {
+          const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
+          const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, qb[nt][2 * j], S[nt][u], 0, 0, 0);
+            S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, qb[nt][2 * j + 1], S[nt][u], 0, 0, 0);
+          }
         }
       }
   };
@@ -363,7 +391,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   // operands is kept as separate multiply / add so that the row broadcast rides on the
   // instruction itself (v_mul_f32_dpp, v_add_f32_dpp) instead of costing moves.
   auto softmax_impl = [&](auto TAILC, floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
-                          half8 (&pb)[NT][2]) {
+                          Operand (&pb)[NT][2 * EB]) {
 #pragma clang fp contract(off)
     constexpr bool TAIL = decltype(TAILC)::value;
     if constexpr (CEIL) {
@@ -373,8 +401,8 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     const int pos0 = c.g << 6, L = c.L;
     // this lane's scales: logit factor, log2 of the V scale and its inverse
     float skp = sk * p.scale_log2;
-    float lsv = __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
-    float rsv = __builtin_amdgcn_exp2f(-lsv);
+    float lsv = PLAIN ? 0.0f : __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
+    float rsv = PLAIN ? 1.0f : __builtin_amdgcn_exp2f(-lsv);
     if (MODE == KVQ_INT8_TOKEN_HEAD && TAIL && pos0 + 16 * g4 + m16 >= L) {
       skp = 0.0f;  // a slot that was never written: its scales are not data
       lsv = 0.0f;
@@ -392,6 +420,8 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
         if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
           ze = S[nt][u][i] * row_bcast<tix>(skp);
           ze = ze + row_bcast<tix>(lsv);
+        } else if constexpr (PLAIN) {
+          ze = S[nt][u][i] * skp;
         } else {
           ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
         }
@@ -411,6 +441,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       m_run[nt] = m_new;
       const float msub = m_safe - kPOffset;
       float lsum = 0.0f;
+      [[maybe_unused]] uint32_t hi_bits[16], lo_bits[16];
       static_for<16>([&](auto I) {
         constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
         const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
@@ -420,8 +451,28 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
         } else {
           lsum = lsum + pr;
         }
-        pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+        if constexpr (PLAIN) {
+          // bf16 keeps 8 bits of a probability: it goes in as two terms, the value cut to
+          // bf16 and the (exactly representable) rest cut to bf16, 16 bits in all
+          hi_bits[tix] = __float_as_uint(pr) & 0xFFFF0000u;
+          lo_bits[tix] = __float_as_uint(pr - __uint_as_float(hi_bits[tix]));
+        } else {
+          pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+        }
       });
+      if constexpr (PLAIN) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          uintx4 ph, pl;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {  // the upper halves of two tokens' words, packed
+            ph[e] = __builtin_amdgcn_perm(hi_bits[8 * hf + 2 * e + 1], hi_bits[8 * hf + 2 * e], 0x07060302u);
+            pl[e] = __builtin_amdgcn_perm(lo_bits[8 * hf + 2 * e + 1], lo_bits[8 * hf + 2 * e], 0x07060302u);
+          }
+          pb[nt][hf] = __builtin_bit_cast(bf16x8, ph);
+          pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
+        }
+      }
       if constexpr (MODE == KVQ_FP8E4M3_BLOCK_HEAD) lsum = lsum * rsv;  // one scale per lane
       l_run[nt] = l_run[nt] * alpha[nt] + lsum;
     }
@@ -433,7 +484,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     }
   };
   auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
-                     half8 (&pb)[NT][2]) {
+                     Operand (&pb)[NT][2 * EB]) {
     if ((c.g << 6) + 64 > c.L - p.q_len + 1)
       softmax_impl(std::true_type{}, S, sk, sv, c, pb);
     else
@@ -444,12 +495,35 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   // In a group that reaches past the sequence's last position the V bytes of the missing
   // tokens are whatever the pool holds; their probabilities are exactly 0, but an e4m3 NaN
   // code times 0 would still poison the sum, so those bytes are cleared first.
-  auto pv_impl = [&](auto CLEARC, const uintx4 (&vt)[DT], const half8 (&pb)[NT][2],
+  auto pv_impl = [&](auto CLEARC, const uintx4 (&vt)[VW], const Operand (&pb)[NT][2 * EB],
                      const Cursor& c) {
     constexpr bool CLEAR = decltype(CLEARC)::value;
     if constexpr (CEIL) {
 #pragma unroll
-      for (int tt = 0; tt < DT; ++tt) ceil_x ^= vt[tt][0] ^ vt[tt][1] ^ vt[tt][2] ^ vt[tt][3];
+      for (int tt = 0; tt < VW; ++tt) ceil_x ^= vt[tt][0] ^ vt[tt][1] ^ vt[tt][2] ^ vt[tt][3];
+      return;
+    }
+    if constexpr (PLAIN) {
+      // a piece holds 8 tokens x 2 bytes: tokens 8 hf + 2 e and + 1 in word e
+      const int live = c.L - ((c.g << 6) + 16 * g4);  // tokens of this lane's sub-block below L
+#pragma unroll
+      for (int x = 0; x < VW; ++x) {
+        const int hf = x & 1, tt = x >> 1;
+        uintx4 raw = vt[x];
+        if constexpr (CLEAR) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = live - (8 * hf + 2 * e);
+            raw[e] &= n >= 2 ? ~0u : n == 1 ? 0xFFFFu : 0u;
+          }
+        }
+        const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          acc[nt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[nt][hf], acc[nt][tt], 0, 0, 0);
+          acc[nt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[nt][2 + hf], acc[nt][tt], 0, 0, 0);
+        }
+      }
       return;
     }
     uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
@@ -477,8 +551,8 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       }
     }
   };
-  auto pv = [&](const uintx4 (&vt)[DT], const half8 (&pb)[NT][2], const Cursor& c) {
-    if (MODE == KVQ_FP8E4M3_BLOCK_HEAD && (c.g << 6) + 64 > c.L)
+  auto pv = [&](const uintx4 (&vt)[VW], const Operand (&pb)[NT][2 * EB], const Cursor& c) {
+    if ((MODE == KVQ_FP8E4M3_BLOCK_HEAD || PLAIN) && (c.g << 6) + 64 > c.L)
       pv_impl(std::true_type{}, vt, pb, c);
     else
       pv_impl(std::false_type{}, vt, pb, c);
@@ -490,14 +564,14 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   // waiting for an entry never waits for code loads issued behind it. ----
   int blk_k, blk_v;
   floatx4 S[NT][4];
-  half8 pb[NT][2];
+  Operand pb[NT][2 * EB];
   const int count = f1 - f0;
   Cursor nxt = cur;
   if (count > 1) advance(nxt);
   Cursor nn = nxt;
   bool from_start = cur.g == 0;  // did this wave see the current pair from its first group
   if constexpr (DEPTH == 1) {
-    uintx4 kt[4][KJ], vt[DT];
+    uintx4 kt[4][KJ], vt[VW];
     float sk, sv;
     const uint8_t* vbase;
     {
@@ -547,7 +621,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     // unrolled by two so that the buffers and the table-entry registers swap roles without
     // copies, and every load in it is unconditional (a load under a usually-true condition
     // would make the compiler's wait counts as strict as if the load were never issued).
-    uintx4 kta[4][KJ], vta[DT], ktb[4][KJ], vtb[DT];
+    uintx4 kta[4][KJ], vta[VW], ktb[4][KJ], vtb[VW];
     float ska, sva, skb, svb;
     const uint8_t* vbase;
     int tk0, tv0, tk1, tv1;  // table entries of the group after the one being loaded
@@ -709,8 +783,11 @@ hipError_t launch_stream(const AttnArgs& a0, hipStream_t stream) {
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else if (a.row_tiles == 1)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  else
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, 2>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  else {
+    // an unquantized cache has twice the bytes per group: no room for a second buffer
+    constexpr int kDepth = MODE == KVQ_BF16_PLAIN ? 1 : 2;
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, kDepth>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  }
   const hipError_t e = hipGetLastError();
   if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
   return e;
@@ -732,9 +809,12 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   if (a.mode == KVQ_INT8_TOKEN_HEAD)
     e = a.head_dim == 128 ? launch_stream<KVQ_INT8_TOKEN_HEAD, 128>(a, stream)
                           : launch_stream<KVQ_INT8_TOKEN_HEAD, 64>(a, stream);
-  else
+  else if (a.mode == KVQ_FP8E4M3_BLOCK_HEAD)
     e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 128>(a, stream)
                           : launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 64>(a, stream);
+  else
+    e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
+                          : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);
   if (e != hipSuccess || g_read_ceiling || g_skip_reduce) return e;
   const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
   if (a.head_dim == 128)

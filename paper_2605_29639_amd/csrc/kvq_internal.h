@@ -29,6 +29,17 @@ __host__ __device__ inline int v_elem(int off, int d, int /*block_size*/, int he
   return (off >> 4) * (16 * head_dim) + d * 16 + (off & 15);
 }
 
+// The same two orders for the 2-byte elements of an unquantized cache, in elements: a lane's
+// 16-byte piece is 8 elements, so K slices are 8 channels wide and a V row of 16 tokens is
+// kept as two half-rows of 8 (all channels' first halves, then all second halves).
+__host__ __device__ inline int k_elem16(int off, int d, int head_dim) {
+  return (off >> 2) * (4 * head_dim) + (d >> 3) * 32 + (off & 3) * 8 + (d & 7);
+}
+__host__ __device__ inline int v_elem16(int off, int d, int head_dim) {
+  return (off >> 4) * (16 * head_dim) + ((off >> 3) & 1) * (8 * head_dim) + d * 8 + (off & 7);
+}
+__host__ __device__ inline int elem_bytes(int mode) { return mode == KVQ_BF16_PLAIN ? 2 : 1; }
+
 // int8 codes are kept in the cache in offset-binary form (stored byte = code XOR 0x80, i.e.
 // code + 128), which is the form the byte -> f16 conversion in the attention kernel consumes
 // directly; e4m3 codes are stored as they are.

@@ -26,6 +26,22 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
   }
 }
 
+__global__ __launch_bounds__(256) void repack16_kernel(const uint16_t* __restrict__ src,
+                                                       uint16_t* __restrict__ dst, size_t total,
+                                                       int H, int bs, int D, bool to_canonical) {
+  const size_t tile_elems = (size_t)bs * D;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const size_t tile = i / tile_elems;
+    const int within = (int)(i - tile * tile_elems);
+    const int off = within / D, d = within - off * D;
+    const int kv = (int)((tile / H) & 1);
+    const size_t phys = tile * tile_elems + (kv ? v_elem16(off, d, D) : k_elem16(off, d, D));
+    if (to_canonical) dst[i] = src[phys];
+    else dst[phys] = src[i];
+  }
+}
+
 }  // namespace
 
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
@@ -35,6 +51,12 @@ hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& des
   if (total == 0) return hipSuccess;
   size_t blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
+  if (desc.mode == KVQ_BF16_PLAIN) {
+    hipLaunchKernelGGL(repack16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (const uint16_t*)src, (uint16_t*)dst, total, desc.num_kv_heads,
+                       desc.block_size, desc.head_dim, to_canonical);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                      (const uint8_t*)src, (uint8_t*)dst, total, desc.num_kv_heads,
                      desc.block_size, desc.head_dim, desc.mode, to_canonical);

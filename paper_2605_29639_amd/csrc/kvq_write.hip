@@ -526,6 +526,33 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
   }
 }
 
+// ---- unquantized cache: the rows are copied to their slots ---------------------------------
+// unit = (token, kv head, K|V); a lane moves D/64 adjacent channels.
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void write_plain_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint16_t* __restrict__ cache,
+    int32_t H, int32_t bs) {
+  constexpr int E = D / 64;
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (unit >= (int64_t)num_tokens * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int t = (int)((unit >> 1) / H);
+  const int64_t slot = slot_mapping[t];
+  if (slot < 0) return;
+  const int64_t blk = slot >> __builtin_ctz(bs);
+  const int off = (int)(slot & (bs - 1));
+  const uint16_t* src = (kv ? v : k) + ((size_t)t * H + h) * D + lane * E;
+  uint16_t* tile = cache + tile_offset(blk, kv, h, H, bs, D);  // in elements
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int d = lane * E + e;
+    tile[kv ? v_elem16(off, d, D) : k_elem16(off, d, D)] = src[e];
+  }
+}
+
 }  // namespace
 
 hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mapping,
@@ -544,7 +571,15 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
 #define KVQ_LAUNCH_WRITE(KERNEL, DD)                                                          \
   hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
                      num_tokens, c, scales, desc.num_kv_heads, desc.block_size)
-  if (bulk && desc.mode == KVQ_INT8_TOKEN_HEAD) {
+  if (desc.mode == KVQ_BF16_PLAIN) {
+    const unsigned g = (unsigned)(((int64_t)num_tokens * desc.num_kv_heads * 2 + kWaves - 1) / kWaves);
+    if (desc.head_dim == 128)
+      hipLaunchKernelGGL((write_plain_kernel<128>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, (uint16_t*)cache, desc.num_kv_heads, desc.block_size);
+    else
+      hipLaunchKernelGGL((write_plain_kernel<64>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, (uint16_t*)cache, desc.num_kv_heads, desc.block_size);
+  } else if (bulk && desc.mode == KVQ_INT8_TOKEN_HEAD) {
     if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 128);
     else KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 64);
   } else if (bulk) {

@@ -9,6 +9,7 @@ import os
 
 MODE_INT8 = 0   # KVQ_INT8_TOKEN_HEAD
 MODE_FP8 = 1    # KVQ_FP8E4M3_BLOCK_HEAD
+MODE_BF16 = 2   # KVQ_BF16_PLAIN (unquantized baseline)
 
 OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, -5
 
@@ -33,6 +34,8 @@ class CacheDesc(C.Structure):
     def scales_shape(self):
         if self.mode == MODE_INT8:
             return (self.num_blocks, 2, self.num_kv_heads, self.block_size)
+        if self.mode == MODE_BF16:
+            return (0,)
         return (self.num_blocks, 2, self.num_kv_heads)
 
 
@@ -95,6 +98,8 @@ def _stream(stream):
 
 def _dev(t, dtype, name):
     import torch
+    if t is not None and t.numel() == 0 and t.dtype == dtype:
+        return C.c_void_p(None)  # an empty tensor has no storage to point at
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise TypeError("%s must be a contiguous device tensor of %s" % (name, dtype))
     return C.c_void_p(t.data_ptr())
@@ -156,20 +161,23 @@ def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max
 
 
 def cache_to_canonical(cache, desc, stream=None):
-    """Canonical [num_blocks, 2, H_kv, block_size, head_dim] uint8 copy of a physical cache."""
+    """Canonical [num_blocks, 2, H_kv, block_size, head_dim] copy of a physical cache: uint8
+    codes, or int16 bf16 bit patterns for an unquantized cache."""
     import torch
     out = torch.empty_like(cache)
     rc = lib().kvq_cache_to_canonical(_dev(cache, torch.uint8, "cache"), C.c_void_p(out.data_ptr()),
                                       C.byref(desc), _stream(stream))
     if rc != OK:
         raise KvqError(rc, "kvq_cache_to_canonical")
+    if desc.mode == MODE_BF16:
+        out = out.view(torch.int16)
     return out.view(desc.cache_shape())
 
 
 def cache_from_canonical(canonical, desc, stream=None):
     """Physical-layout cache (flat uint8) holding the given canonical array."""
     import torch
-    canonical = canonical.contiguous().view(-1)
+    canonical = canonical.contiguous().view(-1).view(torch.uint8)
     out = torch.empty_like(canonical)
     rc = lib().kvq_cache_from_canonical(_dev(canonical, torch.uint8, "canonical"),
                                         C.c_void_p(out.data_ptr()), C.byref(desc), _stream(stream))

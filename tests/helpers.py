@@ -97,6 +97,8 @@ def upload_oracle_cache(wl, cache_np, scales_np):
     import torch
     from paper_2605_29639_amd import kvq
     desc = gpu_desc(wl)
+    if cache_np.dtype == np.uint16:  # unquantized cache: bf16 bit patterns
+        cache_np = cache_np.view(np.int16)
     cache = kvq.cache_from_canonical(torch.from_numpy(cache_np).cuda(), desc)
     scales = torch.from_numpy(scales_np).cuda()
     torch.cuda.synchronize()

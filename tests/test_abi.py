@@ -40,6 +40,8 @@ def test_sizes():
     assert L.kvq_cache_bytes(C.byref(d())) == 8 * 2 * 2 * 16 * 64
     assert L.kvq_scales_bytes(C.byref(d())) == 8 * 2 * 2 * 16 * 4
     assert L.kvq_scales_bytes(C.byref(d(mode=1))) == 8 * 2 * 2 * 4
+    assert L.kvq_cache_bytes(C.byref(d(mode=2))) == 8 * 2 * 2 * 16 * 64 * 2   # unquantized: bf16
+    assert L.kvq_scales_bytes(C.byref(d(mode=2))) == 0
     assert L.kvq_cache_bytes(C.byref(d(D=96))) == 0
     assert L.kvq_cache_bytes(None) == 0
 
@@ -48,7 +50,7 @@ FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below fails validati
 
 
 @pytest.mark.parametrize("desc,code", [
-    (d(mode=2), kvq.E_BAD_MODE), (d(mode=-1), kvq.E_BAD_MODE),
+    (d(mode=3), kvq.E_BAD_MODE), (d(mode=-1), kvq.E_BAD_MODE),
     (d(bs=8), kvq.E_BAD_SHAPE), (d(bs=48), kvq.E_BAD_SHAPE), (d(bs=512), kvq.E_BAD_SHAPE),
     (d(D=96), kvq.E_BAD_SHAPE), (d(D=256), kvq.E_BAD_SHAPE), (d(H=0), kvq.E_BAD_SHAPE),
     (d(nblk=-1), kvq.E_BAD_SHAPE),

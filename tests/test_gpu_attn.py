@@ -34,7 +34,10 @@ def check(wl, chunks=(0,), tol=TOL):
     return errs
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16]
+
+
+@pytest.mark.parametrize("mode", MODES)
 def test_tiny_config(mode):
     check(W.tiny(mode), chunks=(0, 64))
 
@@ -57,7 +60,7 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_shapes_and_splits(mode, case):
     name, lens, q_len, Hq, Hkv, D, bs = case
@@ -66,7 +69,7 @@ def test_shapes_and_splits(mode, case):
     check(wl, chunks=(0, 64, 256))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", MODES)
 def test_gpu_written_cache_gives_the_same_attention(mode):
     """End to end through both entry points: the library's own cache (bit-identical to the
     checker's, see test_gpu_write) and the uploaded checker's cache give the same output."""
@@ -81,7 +84,7 @@ def test_gpu_written_cache_gives_the_same_attention(mode):
     assert attn_err(a, want) <= TOL
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", MODES)
 def test_stale_bytes_after_the_last_position_are_never_used(mode):
     """Unwritten slots hold NaN codes / NaN or huge scales; block-table entries past the last
     block are -1.  The output must not change and must stay finite."""
@@ -95,7 +98,10 @@ def test_stale_bytes_after_the_last_position_are_never_used(mode):
         live[s // 16, s % 16] = True
     dirty_c, dirty_s = oc.copy(), osc.copy()
     for blk, off in np.argwhere(~live):
-        dirty_c[blk, :, :, off, :] = 0x7F if mode == W.MODE_FP8 else 0x80
+        if mode == W.MODE_BF16:   # NaN and infinity bit patterns
+            dirty_c[blk, :, :, off, :] = 0x7FC0 if (blk + off) % 2 else 0xFF80
+        else:
+            dirty_c[blk, :, :, off, :] = 0x7F if mode == W.MODE_FP8 else 0x80
         if mode == W.MODE_INT8:
             dirty_s[blk, :, :, off] = np.nan if (blk + off) % 2 else 3e38
     if mode == W.MODE_FP8:
@@ -116,7 +122,7 @@ def test_run_to_run_determinism():
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", MODES)
 def test_degenerate_inputs(mode):
     """All-zero V rows carrying the largest weight, zero q, huge and tiny V magnitudes."""
     wl = W.custom("degenerate", mode, [80, 80, 80, 80], 1, 4, 2, 64, 16, seed=21, outliers=False)

@@ -40,11 +40,14 @@ def compare_on_sample(wl, chunks, seqs=None):
     canon = kvq.cache_to_canonical(cache, desc)
     idx = torch.from_numpy(blocks.astype(np.int64)).cuda()
     got_c = canon[idx].cpu().numpy()
-    got_s = scales[idx].cpu().numpy()
+    if wl.mode == W.MODE_BF16:   # unquantized: bf16 bit patterns, no scales
+        got_c = got_c.view(np.uint16)
     del canon
     bad = np.argwhere(got_c != oc[blocks])
     assert bad.size == 0, "codes differ, first at (sampled block, kv, h, off, d) %s" % bad[0]
-    assert np.array_equal(got_s.view(np.uint32), osc[blocks].view(np.uint32))
+    if wl.mode != W.MODE_BF16:
+        got_s = scales[idx].cpu().numpy()
+        assert np.array_equal(got_s.view(np.uint32), osc[blocks].view(np.uint32))
 
     # --- attention over everything on the GPU, over the sample on the CPU ---
     rows = np.concatenate([np.arange(b * wl.q_len, (b + 1) * wl.q_len) for b in seqs])
@@ -83,6 +86,15 @@ def test_long_context_wide_gqa_full_size():
     assert wl.batch == 32 and wl.group == 16 and wl.chunk_tokens == 2048
     assert 16384 <= wl.seq_lens.min() and wl.seq_lens.max() <= 65536
     compare_on_sample(wl, chunks=(2048, 0), seqs=sample_sequences(wl, extra=1))
+
+
+def test_unquantized_baseline_full_size():
+    """The bf16 twin bench.py times beside the quantized path: configuration 2's shapes over an
+    unquantized cache, and configuration 5's (two row tiles)."""
+    wl = W.llama8b(mode=W.MODE_BF16)
+    compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=4))
+    wl = W.verify_prefix(mode=W.MODE_BF16)
+    compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=0))
 
 
 @pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])

@@ -12,7 +12,10 @@ from helpers import bits_to_bf16_tensor, gpu_desc, gpu_fill, oracle_fill
 
 def fetch(cache, scales, desc):
     from paper_2605_29639_amd import kvq
-    return kvq.cache_to_canonical(cache, desc).cpu().numpy(), scales.cpu().numpy()
+    canon = kvq.cache_to_canonical(cache, desc).cpu().numpy()
+    if canon.dtype == np.int16:  # unquantized cache: bf16 bit patterns
+        canon = canon.view(np.uint16)
+    return canon, scales.cpu().numpy()
 
 
 def assert_pool_equal(wl, got, want):
@@ -26,7 +29,7 @@ def assert_pool_equal(wl, got, want):
         sb[0], gs[tuple(sb[0])], ws[tuple(sb[0])])
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
 def test_tiny_config(mode):
     wl = W.tiny(mode)
     cache, scales, desc = gpu_fill(wl)
@@ -43,7 +46,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_ragged_shapes_bulk_write(mode, shape):
     lens, H, D, bs = shape
@@ -124,7 +127,7 @@ def test_fp8_token_by_token_append_with_rescale(bs, D):
     assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
 def test_chunked_prefill_then_appends(mode):
     """A sequence written in uneven pieces (block-aligned or not) and then appended to."""
     import torch
