@@ -686,7 +686,9 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   end_pair(cur, from_start && cur.g == cur.ng - 1);
   stamp(5);
   stamp(7);
-  if constexpr (CEIL) p.ws_ml[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
+  // (one dword per lane into the accumulator area, which holds at least 16 * D floats per
+  // wavefront, so that the loads cannot be optimised away)
+  if constexpr (CEIL) p.ws_acc[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
 
 // ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query token,
