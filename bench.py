@@ -296,6 +296,32 @@ def main():
     # lengths, tables and K/V values, the rows stored as bf16.  Timed like the step and like
     # the streaming kernel above; the ratio is the kernel-level form of the paper's claim that
     # the quantized cache relieves decode of half its memory traffic.
+    # Block moves between the pool and a packed staging area (the tiered cache's load and
+    # evict steps): about 64 MB of blocks of the second layer cache, to and from device memory
+    # and pinned host memory.  GB/s counts the bytes once (they are read once and written once).
+    cache1, scales1 = caches[1 % layers]
+    n_blk = int(min(desc.num_blocks, max(1, (64 << 20) // kvq.packed_sizes(desc, 1)[0])))
+    ids = torch.from_numpy(np.random.default_rng(1).permutation(desc.num_blocks)[:n_blk]
+                           .astype(np.int32)).cuda()
+    cb, sf = kvq.packed_sizes(desc, n_blk)
+    moves = {"blocks": n_blk, "bytes": cb + 4 * sf}
+    for where, kw in (("device", dict(device="cuda")), ("pinned_host", dict(pin_memory=True))):
+        pc = torch.empty(cb, dtype=torch.uint8, **kw)
+        ps = torch.empty(sf, dtype=torch.float32, **kw)
+        for name, fn in (("export", lambda: kvq.blocks_export(cache1, scales1, desc, ids, pc, ps, stream=stream)),
+                         ("import", lambda: kvq.blocks_import(pc, ps, desc, ids, cache1, scales1, stream=stream))):
+            fn()
+            torch.cuda.synchronize()
+            te0.record()
+            for _ in range(5):
+                fn()
+            te1.record()
+            torch.cuda.synchronize()
+            us = te0.elapsed_time(te1) / 5 * 1e3
+            moves["%s_%s" % (name, where)] = {"us": us, "GB/s": (cb + 4 * sf) / us / 1e3}
+        del pc, ps
+    result["block_moves"] = moves
+
     step(1)  # (the second layer cache: the prefill measurement above rewrote part of the first)
     torch.cuda.synchronize()
     out_main = out.cpu().numpy()  # the measured path's output, for the parity figure below

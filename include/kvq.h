@@ -159,6 +159,27 @@ int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_d
 int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,
                              void* stream);
 
+/* Block transfers between the pool and a packed staging area: the GPU end of the tiered
+ * cache's LoadToGPU step (Section 3.3, Algorithm 1: blocks absent from GPU memory are loaded
+ * from local CPU memory before the batch runs) and of its counterpart, the eviction of blocks
+ * to CPU memory.  A block is one contiguous piece of `cache` (2 * num_kv_heads * block_size
+ * * head_dim elements, in the physical order above) and one of `scales`, so the packed form
+ * is simply those pieces one after another:
+ *   kvq_blocks_export: packed block i  <-  pool block block_ids[i]
+ *   kvq_blocks_import: pool block block_ids[i]  <-  packed block i
+ *   block_ids      device, int32 [num], each in [0, num_blocks); for import, all different
+ *   packed_cache   num * kvq_cache_bytes(desc) / num_blocks bytes, 16-byte aligned
+ *   packed_scales  num * kvq_scales_bytes(desc) / num_blocks bytes (ignored for KVQ_BF16_PLAIN)
+ * The packed buffers may be device memory or pinned host memory that the GPU can address
+ * (hipHostMalloc): the kernels then read or write it over the host link directly.
+ * num == 0 succeeds without launching. */
+int kvq_blocks_export(const void* cache, const float* scales, const kvq_cache_desc_t* desc,
+                      const int32_t* block_ids, int32_t num, void* packed_cache,
+                      float* packed_scales, void* stream);
+int kvq_blocks_import(const void* packed_cache, const float* packed_scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_ids, int32_t num,
+                      void* cache, float* scales, void* stream);
+
 /* Measurement hook, not part of the path: while `before` and `after` (hipEvent_t handles
  * created by the caller) are set, every paged_decode_attn call records `before` on its stream
  * immediately ahead of its split kernel (the kernel that streams the K/V codes) and `after`

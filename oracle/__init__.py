@@ -211,5 +211,28 @@ def attn_weights(q, cache, scales, mode, block_table_row, seq_len, q_len, j, hq,
     return w
 
 
+def blocks_export(cache, scales, mode, block_ids):
+    """Packed copy of the named blocks (the tiered cache's eviction to CPU memory, Section 3.3):
+    packed block i is pool block block_ids[i].  Returns (packed cache, packed scales)."""
+    _chk_cache(cache, scales, mode)
+    ids = np.asarray(block_ids, dtype=np.int64)
+    assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
+    packed_scales = scales[ids].copy() if mode != MODE_BF16 else scales.copy()
+    return cache[ids].copy(), packed_scales
+
+
+def blocks_import(packed_cache, packed_scales, mode, block_ids, cache, scales):
+    """The reverse (LoadToGPU of Algorithm 1): pool block block_ids[i] becomes packed block i,
+    in place; every other block keeps its contents.  The ids must differ."""
+    _chk_cache(cache, scales, mode)
+    ids = np.asarray(block_ids, dtype=np.int64)
+    assert len(set(ids.tolist())) == ids.size
+    assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
+    for i, blk in enumerate(ids):
+        cache[blk] = packed_cache[i]
+        if mode != MODE_BF16:
+            scales[blk] = packed_scales[i]
+
+
 def num_threads():
     return int(lib().oracle_num_threads())

@@ -195,6 +195,39 @@ int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache
              : KVQ_E_HIP;
 }
 
+static int block_copy(const void* pool_cache, const float* pool_scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_ids, int32_t num,
+                      void* packed_cache, float* packed_scales, bool to_packed, void* stream) {
+  int err;
+  if (!desc_ok(desc, &err)) return err;
+  // one workgroup per 4 KiB piece of a block; 32-bit byte offsets inside a block
+  const int64_t block_bytes = (int64_t)2 * desc->num_kv_heads * desc->block_size *
+                              desc->head_dim * kvq::elem_bytes(desc->mode);
+  if (num < 0 || block_bytes > 0x7FFFFFFF || (int64_t)num * ((block_bytes + 4095) / 4096) > 0x7FFFFFFF)
+    return KVQ_E_BAD_SHAPE;
+  if (num == 0) return KVQ_OK;
+  if (!pool_cache || !block_ids || !packed_cache) return KVQ_E_NULLPTR;
+  if (desc->mode != KVQ_BF16_PLAIN && (!pool_scales || !packed_scales)) return KVQ_E_NULLPTR;
+  if ((((uintptr_t)pool_cache | (uintptr_t)packed_cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
+  const hipError_t e = kvq::launch_block_copy(pool_cache, pool_scales, *desc, block_ids, num,
+                                              packed_cache, packed_scales, to_packed,
+                                              (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+int kvq_blocks_export(const void* cache, const float* scales, const kvq_cache_desc_t* desc,
+                      const int32_t* block_ids, int32_t num, void* packed_cache,
+                      float* packed_scales, void* stream) {
+  return block_copy(cache, scales, desc, block_ids, num, packed_cache, packed_scales, true, stream);
+}
+
+int kvq_blocks_import(const void* packed_cache, const float* packed_scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_ids, int32_t num,
+                      void* cache, float* scales, void* stream) {
+  return block_copy(cache, scales, desc, block_ids, num, (void*)packed_cache,
+                    (float*)packed_scales, false, stream);
+}
+
 void kvq_profile_split_events(void* before, void* after) {
   kvq::set_profile_events((hipEvent_t)before, (hipEvent_t)after);
 }

@@ -82,6 +82,10 @@ void set_profile_events(hipEvent_t before, hipEvent_t after);
 void set_read_ceiling(bool on);
 void set_skip_reduce(bool on);
 void set_wave_clock(unsigned long long* buf);
+hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
+                             const kvq_cache_desc_t& desc, const int32_t* block_ids, int32_t num,
+                             void* packed_cache, float* packed_scales, bool to_packed,
+                             hipStream_t stream);
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream);
 

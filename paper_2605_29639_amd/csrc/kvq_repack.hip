@@ -7,6 +7,8 @@
 namespace kvq {
 namespace {
 
+typedef uint32_t uintx4v __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ src,
                                                      uint8_t* __restrict__ dst, size_t total,
                                                      int H, int bs, int D, int mode,
@@ -42,7 +44,50 @@ __global__ __launch_bounds__(256) void repack16_kernel(const uint16_t* __restric
   }
 }
 
+// Whole blocks between the pool and a packed staging area.  A workgroup moves one 4 KiB piece
+// of one block's codes (16 bytes per lane); the workgroup of a block's first piece also moves
+// the block's scales.  Non-temporal on both sides: every byte is touched once.
+__global__ __launch_bounds__(256) void block_copy_kernel(
+    uint8_t* __restrict__ pool_cache, float* __restrict__ pool_scales,
+    uint8_t* __restrict__ packed_cache, float* __restrict__ packed_scales,
+    const int32_t* __restrict__ block_ids, uint32_t block_bytes, uint32_t scale_floats,
+    uint32_t pieces, bool to_packed) {
+  const uint32_t i = blockIdx.x / pieces, piece = blockIdx.x - i * pieces;
+  const size_t blk = (size_t)block_ids[i];
+  const uint32_t at = piece * 4096u + threadIdx.x * 16u;
+  if (at < block_bytes) {
+    uintx4v* in_pool = (uintx4v*)(pool_cache + blk * block_bytes + at);
+    uintx4v* in_packed = (uintx4v*)(packed_cache + (size_t)i * block_bytes + at);
+    if (to_packed) __builtin_nontemporal_store(__builtin_nontemporal_load(in_pool), in_packed);
+    else __builtin_nontemporal_store(__builtin_nontemporal_load(in_packed), in_pool);
+  }
+  if (piece == 0) {
+    for (uint32_t k = threadIdx.x; k < scale_floats; k += 256) {
+      float* in_pool = pool_scales + blk * scale_floats + k;
+      float* in_packed = packed_scales + (size_t)i * scale_floats + k;
+      if (to_packed) *in_packed = *in_pool;
+      else *in_pool = *in_packed;
+    }
+  }
+}
+
 }  // namespace
+
+hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
+                             const kvq_cache_desc_t& desc, const int32_t* block_ids, int32_t num,
+                             void* packed_cache, float* packed_scales, bool to_packed,
+                             hipStream_t stream) {
+  const uint32_t block_bytes = 2u * desc.num_kv_heads * desc.block_size * desc.head_dim *
+                               elem_bytes(desc.mode);
+  const uint32_t scale_floats =
+      desc.mode == KVQ_BF16_PLAIN ? 0u
+      : 2u * desc.num_kv_heads * (desc.mode == KVQ_INT8_TOKEN_HEAD ? desc.block_size : 1);
+  const uint32_t pieces = (block_bytes + 4095u) / 4096u;
+  hipLaunchKernelGGL(block_copy_kernel, dim3((unsigned)num * pieces), dim3(256), 0, stream,
+                     (uint8_t*)pool_cache, (float*)pool_scales, (uint8_t*)packed_cache,
+                     packed_scales, block_ids, block_bytes, scale_floats, pieces, to_packed);
+  return hipGetLastError();
+}
 
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream) {

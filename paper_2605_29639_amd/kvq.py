@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_workspace_bytes",
            "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
+           "kvq_blocks_export", "kvq_blocks_import",
            "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
            "kvq_profile_wave_clock",
            "kvq_strerror")
@@ -72,6 +73,10 @@ def lib():
         L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
         L.kvq_cache_from_canonical.restype = C.c_int
         L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
+        L.kvq_blocks_export.restype = C.c_int
+        L.kvq_blocks_export.argtypes = [P, P, D, P, I32, P, P, P]
+        L.kvq_blocks_import.restype = C.c_int
+        L.kvq_blocks_import.argtypes = [P, P, D, P, I32, P, P, P]
         L.kvq_profile_split_events.restype = None
         L.kvq_profile_split_events.argtypes = [P, P]
         L.kvq_profile_skip_reduce.restype = None
@@ -158,6 +163,44 @@ def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != OK:
         raise KvqError(rc, "paged_decode_attn")
+
+
+def _any(t, dtype, name):
+    """Device tensor, or pinned host tensor the GPU can address."""
+    import torch
+    if t is not None and t.numel() == 0 and t.dtype == dtype:
+        return C.c_void_p(None)
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype or not t.is_contiguous() or \
+            not (t.is_cuda or t.is_pinned()):
+        raise TypeError("%s must be a contiguous device or pinned host tensor of %s" % (name, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def packed_sizes(desc, num):
+    """(cache bytes, scale floats) of `num` packed blocks."""
+    nb = max(desc.num_blocks, 1)
+    return (num * (lib().kvq_cache_bytes(desc) // nb), num * (lib().kvq_scales_bytes(desc) // nb // 4))
+
+
+def blocks_export(cache, scales, desc, block_ids, packed_cache, packed_scales, stream=None):
+    import torch
+    rc = lib().kvq_blocks_export(_dev(cache, torch.uint8, "cache"), _dev(scales, torch.float32, "scales"),
+                                 C.byref(desc), _dev(block_ids, torch.int32, "block_ids"),
+                                 block_ids.numel(), _any(packed_cache, torch.uint8, "packed_cache"),
+                                 _any(packed_scales, torch.float32, "packed_scales"), _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "kvq_blocks_export")
+
+
+def blocks_import(packed_cache, packed_scales, desc, block_ids, cache, scales, stream=None):
+    import torch
+    rc = lib().kvq_blocks_import(_any(packed_cache, torch.uint8, "packed_cache"),
+                                 _any(packed_scales, torch.float32, "packed_scales"), C.byref(desc),
+                                 _dev(block_ids, torch.int32, "block_ids"), block_ids.numel(),
+                                 _dev(cache, torch.uint8, "cache"), _dev(scales, torch.float32, "scales"),
+                                 _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "kvq_blocks_import")
 
 
 def cache_to_canonical(cache, desc, stream=None):

@@ -121,3 +121,20 @@ def test_repack_argument_checks():
     assert L.kvq_cache_to_canonical(None, FAKE, C.byref(d()), None) == kvq.E_NULLPTR
     assert L.kvq_cache_from_canonical(FAKE, FAKE, C.byref(d(D=1)), None) == kvq.E_BAD_SHAPE
     assert L.kvq_cache_to_canonical(None, None, C.byref(d(nblk=0)), None) == kvq.OK
+
+
+def test_block_move_argument_checks():
+    L = kvq.lib()
+    ok = d()
+    for f in (L.kvq_blocks_export, L.kvq_blocks_import):
+        assert f(FAKE, FAKE, None, FAKE, 2, FAKE, FAKE, None) == kvq.E_NULLPTR
+        assert f(FAKE, FAKE, C.byref(d(mode=7)), FAKE, 2, FAKE, FAKE, None) == kvq.E_BAD_MODE
+        assert f(FAKE, FAKE, C.byref(ok), FAKE, -1, FAKE, FAKE, None) == kvq.E_BAD_SHAPE
+        assert f(None, None, C.byref(ok), None, 0, None, None, None) == kvq.OK
+        for i in (0, 1, 3, 5, 6):
+            args = [FAKE, FAKE, C.byref(ok), FAKE, 2, FAKE, FAKE, None]
+            args[i] = None
+            assert f(*args) == kvq.E_NULLPTR
+        odd = C.c_void_p(0x1004)
+        assert f(odd, FAKE, C.byref(ok), FAKE, 2, FAKE, FAKE, None) == kvq.E_BAD_SHAPE
+        assert f(FAKE, FAKE, C.byref(ok), FAKE, 2, odd, FAKE, None) == kvq.E_BAD_SHAPE

@@ -416,3 +416,39 @@ def test_footprint_is_half_of_bf16():
         cache, scales = oracle.alloc_cache(mode, 10, bs, 8, D)
         ratio = (cache.nbytes + scales.nbytes) / (10 * 2 * 8 * bs * D * 2)
         assert 0.5 <= ratio <= 0.52
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
+    """The tiered cache's block moves are index copies: checked element by element against
+    explicit loops, as a round trip, and for leaving every other block alone."""
+    rng = np.random.default_rng(17 + mode)
+    nblk, bs, H, D = 9, 16, 2, 64
+    cache, scales = oracle.alloc_cache(mode, nblk, bs, H, D)
+    cache[:] = rng.integers(0, 1 << (8 * cache.itemsize), size=cache.shape, dtype=np.uint32).astype(cache.dtype)
+    scales[...] = rng.random(scales.shape, dtype=np.float32)
+    ids = np.array([7, 0, 3], dtype=np.int32)
+    pc, ps = oracle.blocks_export(cache, scales, mode, ids)
+    assert pc.shape == (3,) + cache.shape[1:]
+    for i, blk in enumerate(ids):
+        for kv in range(2):
+            for h in range(H):
+                assert np.array_equal(pc[i, kv, h], cache[blk, kv, h])
+                if mode != W.MODE_BF16:
+                    assert np.array_equal(ps[i, kv, h], scales[blk, kv, h])
+    # import into another pool at other ids: those blocks change, the rest do not
+    pool, pscales = oracle.alloc_cache(mode, nblk, bs, H, D)
+    pool[:] = 0x5A
+    pscales[...] = 9.0
+    before, before_s = pool.copy(), pscales.copy()
+    dst = np.array([1, 8, 4], dtype=np.int32)
+    oracle.blocks_import(pc, ps, mode, dst, pool, pscales)
+    for i, blk in enumerate(dst):
+        assert np.array_equal(pool[blk], cache[ids[i]])
+    others = [b for b in range(nblk) if b not in dst]
+    assert np.array_equal(pool[others], before[others])
+    if mode != W.MODE_BF16:
+        assert np.array_equal(pscales[dst], scales[ids]) and np.array_equal(pscales[others], before_s[others])
+    # round trip
+    back, back_s = oracle.blocks_export(pool, pscales, mode, dst)
+    assert np.array_equal(back, pc) and np.array_equal(back_s, ps)
