@@ -10,7 +10,8 @@ Arrays use the oracle's canonical layout:
          float32 [num_blocks, 2, num_kv_heads]               mode 1 (fp8-e4m3 per block-head)
   k, v, q uint16 bf16 bit patterns [tokens, heads, head_dim]
 Mode 2 is the unquantized baseline: cache uint16 (bf16 bit patterns), same shape; scales is an
-empty float32 array.
+empty float32 array.  Mode 3 is fp8-e4m3 with static per-tensor scales: scales is float32 [2]
+(K, V), set by the caller and only read.
 """
 import ctypes as C
 
@@ -21,6 +22,7 @@ from . import build as _build
 MODE_INT8 = 0
 MODE_FP8 = 1
 MODE_BF16 = 2
+MODE_FP8_TENSOR = 3
 
 _lib = None
 
@@ -119,6 +121,8 @@ def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
                      dtype=np.uint16 if mode == MODE_BF16 else np.uint8)
     if mode == MODE_BF16:
         scales = np.zeros((0,), dtype=np.float32)
+    elif mode == MODE_FP8_TENSOR:
+        scales = np.zeros((2,), dtype=np.float32)
     elif mode == MODE_INT8:
         scales = np.zeros((num_blocks, 2, num_kv_heads, block_size), dtype=np.float32)
     else:
@@ -132,7 +136,7 @@ def _chk_cache(cache, scales, mode):
     nblk, two, H, bs, D = cache.shape
     assert two == 2
     assert scales.shape == {MODE_INT8: (nblk, 2, H, bs), MODE_FP8: (nblk, 2, H),
-                            MODE_BF16: (0,)}[mode]
+                            MODE_BF16: (0,), MODE_FP8_TENSOR: (2,)}[mode]
 
 
 def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
@@ -158,6 +162,8 @@ def dequant(cache, scales, mode):
     if mode == MODE_INT8:
         return cache.view(np.int8).astype(np.float64) * scales.astype(np.float64)[..., None]
     table = fp8_decode(np.arange(256, dtype=np.uint8))
+    if mode == MODE_FP8_TENSOR:
+        return table[cache] * scales.astype(np.float64)[None, :, None, None, None]
     return table[cache] * scales.astype(np.float64)[..., None, None]
 
 
@@ -217,7 +223,8 @@ def blocks_export(cache, scales, mode, block_ids):
     _chk_cache(cache, scales, mode)
     ids = np.asarray(block_ids, dtype=np.int64)
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
-    packed_scales = scales[ids].copy() if mode != MODE_BF16 else scales.copy()
+    per_block = mode in (MODE_INT8, MODE_FP8)  # else the scales are not part of a block
+    packed_scales = scales[ids].copy() if per_block else scales.copy()
     return cache[ids].copy(), packed_scales
 
 
@@ -230,7 +237,7 @@ def blocks_import(packed_cache, packed_scales, mode, block_ids, cache, scales):
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
     for i, blk in enumerate(ids):
         cache[blk] = packed_cache[i]
-        if mode != MODE_BF16:
+        if mode in (MODE_INT8, MODE_FP8):
             scales[blk] = packed_scales[i]
 
 

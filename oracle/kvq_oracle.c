@@ -21,6 +21,7 @@
  *   scales: f32 [num_blocks][2][num_kv_heads][block_size]      (mode 0, int8)
  *           f32 [num_blocks][2][num_kv_heads]                  (mode 1, fp8)
  *           unused                                             (mode 2)
+ *           f32 [2] (K, V), an input                           (mode 3)
  *   k, v, q : bf16 bit patterns (uint16), [tokens][heads][head_dim]
  *   out     : f64 [batch*q_len][num_q_heads][head_dim]
  *
@@ -39,6 +40,10 @@
 /* The unquantized cache the paper's Section 8.5 measures its quantized one against ("BF16
  * KV cache" baseline): the rows are stored as they are. */
 #define ORACLE_MODE_BF16 2
+/* "Per-tensor" scaling (Section 7.2.2) in its static form: one fp32 scale for all of a layer's
+ * K and one for all of its V, fixed beforehand by the caller (scales[0], scales[1]); the write
+ * only encodes, values beyond 448 scales saturate. */
+#define ORACLE_MODE_FP8_TENSOR 3
 
 /* ---- O1: a bf16 bit pattern is the top half of an fp32; widening is exact ---- */
 double oracle_bf16_to_f64(uint16_t bits) {
@@ -163,6 +168,24 @@ int oracle_kv_quant_write(const uint16_t* k, const uint16_t* v, const int64_t* s
     }
     return 0;
   }
+  if (mode == ORACLE_MODE_FP8_TENSOR) {
+    for (int32_t t = 0; t < num_tokens; ++t) {
+      int64_t slot = slot_mapping[t];
+      if (slot < 0) continue;
+      int64_t blk = slot / bs;
+      int off = (int)(slot % bs);
+      for (int kv = 0; kv < 2; ++kv) {
+        const float s = scales[kv];
+        for (int h = 0; h < H; ++h) {
+          const uint16_t* row = (kv ? v : k) + ((size_t)t * H + h) * D;
+          uint8_t* dst = cache + tile_index(blk, kv, h, H, bs, D) + (size_t)off * D;
+          for (int d = 0; d < D; ++d)
+            dst[d] = (s > 0.0f) ? oracle_fp8_encode(oracle_bf16_to_f64(row[d]) / (double)s) : 0x00;
+        }
+      }
+    }
+    return 0;
+  }
   if (mode != ORACLE_MODE_FP8) return -1;
 
   /* mode 1: visit each touched block once, in order of first appearance. */
@@ -241,6 +264,7 @@ double oracle_dequant_at(const uint8_t* cache, const float* scales, int32_t mode
     double s = (double)scales[(((size_t)blk * 2 + kv) * H + h) * bs + off];
     return (double)(int8_t)c * s;
   }
+  if (mode == ORACLE_MODE_FP8_TENSOR) return oracle_fp8_decode(c) * (double)scales[kv];
   return oracle_fp8_decode(c) * (double)scales[((size_t)blk * 2 + kv) * H + h];
 }
 

@@ -2,6 +2,7 @@
 import numpy as np
 
 import oracle
+from paper_2605_29639_amd import workloads as W
 
 
 def oracle_fill(wl, sequences=None):
@@ -11,6 +12,8 @@ def oracle_fill(wl, sequences=None):
     those sequences are written (the rest of the pool stays zero)."""
     cache, scales = oracle.alloc_cache(wl.mode, wl.num_blocks, wl.block_size, wl.num_kv_heads,
                                        wl.head_dim)
+    if wl.mode == W.MODE_FP8_TENSOR:
+        scales[:] = W.STATIC_SCALES
     seqs = range(wl.batch) if sequences is None else sequences
     for b in seqs:
         start, stop = wl.write_range(b)

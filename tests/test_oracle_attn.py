@@ -26,7 +26,7 @@ def run(wl, cache, scales):
                                     wl.q_len, wl.sm_scale)
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR])
 def test_tiny_config_equals_dense_brute_force(mode):
     wl = W.tiny(mode)
     cache, scales = oracle_fill(wl)

@@ -452,3 +452,62 @@ def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
     # round trip
     back, back_s = oracle.blocks_export(pool, pscales, mode, dst)
     assert np.array_equal(back, pc) and np.array_equal(back_s, ps)
+
+
+def test_static_per_tensor_fp8_codes():
+    """Mode 3: the write only encodes x / s with the caller's two scales.  Pinned by (a) every
+    finite code times a power-of-two scale coming back as itself, (b) torch's e4m3 cast of the
+    exactly representable quotient for a power-of-two scale, (c) exact rational rounding and
+    saturation for a scale that is not a power of two; the scales are never modified and the
+    K scale is not used for V."""
+    bs, D = 16, 64
+    # (a) 254 finite codes = 4 tokens of 64 channels (NaN codes 0x7F / 0xFF left out)
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = oracle.fp8_decode(codes)
+    x = np.zeros((bs, 1, D))
+    x.reshape(-1)[:codes.size] = vals * 2.0 ** -3
+    xb = f32_bits_of(x.astype(np.float32))
+    assert np.array_equal(W.bf16_bits_to_f32(xb).astype(np.float64), x)   # bf16-exact inputs
+    cache, scales = oracle.alloc_cache(3, 2, bs, 1, D)
+    scales[:] = (2.0 ** -3, 2.0 ** 5)
+    oracle.kv_quant_write(xb, xb, np.arange(bs, dtype=np.int64), cache, scales, 3)
+    assert scales.tolist() == [2.0 ** -3, 2.0 ** 5]
+    got = cache[0, 0, 0].reshape(-1)[:codes.size]
+    assert np.array_equal(got & 0x7F, codes & 0x7F)
+    assert np.array_equal((got >> 7)[vals != 0], (codes >> 7)[vals != 0])
+    # V used its own scale: the same inputs over 2^5 are 256 times smaller
+    want_v = oracle.fp8_encode(x.reshape(-1)[:codes.size] / 2.0 ** 5)
+    assert np.array_equal(cache[0, 1, 0].reshape(-1)[:codes.size], want_v)
+    # (b) random bf16 rows, power-of-two scale: x / s is exact in fp32, torch casts it
+    rng = np.random.default_rng(40)
+    x = W.bf16_bits_to_f32(f32_bits_of(rng.standard_normal((bs, 1, D), dtype=np.float32) * 3))
+    s = np.float32(2.0 ** -6)
+    scales[:] = (s, s)
+    oracle.kv_quant_write(f32_bits_of(x), f32_bits_of(x), np.arange(bs, 2 * bs, dtype=np.int64),
+                          cache, scales, 3)
+    y = torch.from_numpy(np.clip(x / s, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(cache[1, 0, 0], y[:, 0])
+    # (c) a scale that is no power of two; some values saturate
+    s = np.float32(0.0123)
+    scales[:] = (s, s)
+    oracle.kv_quant_write(f32_bits_of(x), f32_bits_of(x), np.arange(bs, dtype=np.int64), cache,
+                          scales, 3)
+    mags = [Fraction(float(v)) for v in oracle.fp8_decode(np.arange(0x7F, dtype=np.uint8))]
+    saturated = 0
+    for t in range(bs):
+        for d in range(0, D, 3):
+            yq = Fraction(float(x[t, 0, d])) / Fraction(float(s))
+            saturated += abs(yq) > 448
+            a = min(abs(yq), Fraction(448))
+            want = min((abs(mg - a), c & 1, c) for c, mg in enumerate(mags))[2]
+            want |= 0x80 if np.signbit(x[t, 0, d]) else 0
+            assert cache[0, 1, 0, t, d] == want
+    assert saturated > 0
+    # dequantized values are code * tensor scale
+    dq = oracle.dequant(cache, scales, 3)
+    assert dq[0, 1, 0, 3, 6] == oracle.fp8_decode(cache[0, 1, 0, 3, 6]) * float(s)
+    # a zero scale gives zero codes
+    scales[:] = (0.0, s)
+    oracle.kv_quant_write(f32_bits_of(x), f32_bits_of(x), np.arange(bs, dtype=np.int64), cache,
+                          scales, 3)
+    assert not cache[0, 0].any() and cache[0, 1].any()
