@@ -37,10 +37,13 @@ typedef enum {
   KVQ_INT8_TOKEN_HEAD = 0,    /* int8 codes in [-127,127], one fp32 scale per (token, kv head) */
   KVQ_FP8E4M3_BLOCK_HEAD = 1, /* OCP E4M3 (finite-only, max 448) codes, one fp32 scale per
                                  (cache block, kv head) */
-  KVQ_BF16_PLAIN = 2          /* no quantization: the bf16 rows as they are, no scales.  The
+  KVQ_BF16_PLAIN = 2,         /* no quantization: the bf16 rows as they are, no scales.  The
                                  baseline the paper's Section 8.5 measures its quantized
                                  cache against ("BF16 KV cache"); same entry points, twice
                                  the bytes */
+  KVQ_FP8E4M3_TENSOR = 3      /* E4M3 codes with static per-tensor scales: one fp32 scale for
+                                 all of the layer's K, one for all of its V, chosen by the
+                                 caller beforehand and only read by the library */
 } kvq_mode_t;
 
 enum {
@@ -74,6 +77,7 @@ enum {
  *     V:  (off/16) * 16*head_dim + ((off%16)/8) * 8*head_dim + d * 8 + off%8
  * (the same idea with 8-element pieces); there is no scales buffer (its size is 0 and the
  * `scales` arguments are ignored and may be NULL).
+ * KVQ_FP8E4M3_TENSOR: the cache is the e4m3 one; scales is f32 [2] = {K scale, V scale}.
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
  *         f32 [num_blocks][2][num_kv_heads]               for KVQ_FP8E4M3_BLOCK_HEAD
  * Supported: head_dim 64 or 128; block_size a power of two in [16, 256]. */
@@ -101,6 +105,8 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
  *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
  *   exact x/scale, clamped to [-127, 127].
  * KVQ_BF16_PLAIN: the rows are copied to their slots unchanged.
+ * KVQ_FP8E4M3_TENSOR: code = encode(x / scales[kv]) (0x00 when the scale is 0), saturating at
+ *   +-448; the scales are not modified.
  * KVQ_FP8E4M3_BLOCK_HEAD: the tokens of this call that fall into one block must be
  *   consecutive in token order with consecutive increasing slots (append order).  For each
  *   such run, per kv head, separately for K and V: s_prev = the stored block scale if the
@@ -169,7 +175,8 @@ int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache
  *   kvq_blocks_import: pool block block_ids[i]  <-  packed block i
  *   block_ids      device, int32 [num], each in [0, num_blocks); for import, all different
  *   packed_cache   num * kvq_cache_bytes(desc) / num_blocks bytes, 16-byte aligned
- *   packed_scales  num * kvq_scales_bytes(desc) / num_blocks bytes (ignored for KVQ_BF16_PLAIN)
+ *   packed_scales  num * kvq_scales_bytes(desc) / num_blocks bytes (ignored for KVQ_BF16_PLAIN
+ *                  and KVQ_FP8E4M3_TENSOR, whose scales are not part of a block)
  * The packed buffers may be device memory or pinned host memory that the GPU can address
  * (hipHostMalloc): the kernels then read or write it over the host link directly.
  * num == 0 succeeds without launching. */

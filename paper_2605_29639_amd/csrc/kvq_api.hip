@@ -9,7 +9,7 @@ namespace {
 bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   if (!d) { *err = KVQ_E_NULLPTR; return false; }
   if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD &&
-      d->mode != KVQ_BF16_PLAIN) {
+      d->mode != KVQ_BF16_PLAIN && d->mode != KVQ_FP8E4M3_TENSOR) {
     *err = KVQ_E_BAD_MODE;
     return false;
   }
@@ -88,6 +88,7 @@ size_t kvq_cache_bytes(const kvq_cache_desc_t* desc) {
 size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
   int err;
   if (!desc_ok(desc, &err) || desc->mode == KVQ_BF16_PLAIN) return 0;
+  if (desc->mode == KVQ_FP8E4M3_TENSOR) return 2 * sizeof(float);
   const size_t per_block = (size_t)2 * desc->num_kv_heads *
                            (desc->mode == KVQ_INT8_TOKEN_HEAD ? desc->block_size : 1);
   return (size_t)desc->num_blocks * per_block * sizeof(float);
@@ -207,7 +208,9 @@ static int block_copy(const void* pool_cache, const float* pool_scales,
     return KVQ_E_BAD_SHAPE;
   if (num == 0) return KVQ_OK;
   if (!pool_cache || !block_ids || !packed_cache) return KVQ_E_NULLPTR;
-  if (desc->mode != KVQ_BF16_PLAIN && (!pool_scales || !packed_scales)) return KVQ_E_NULLPTR;
+  const bool block_scales =
+      desc->mode == KVQ_INT8_TOKEN_HEAD || desc->mode == KVQ_FP8E4M3_BLOCK_HEAD;
+  if (block_scales && (!pool_scales || !packed_scales)) return KVQ_E_NULLPTR;
   if ((((uintptr_t)pool_cache | (uintptr_t)packed_cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const hipError_t e = kvq::launch_block_copy(pool_cache, pool_scales, *desc, block_ids, num,
                                               packed_cache, packed_scales, to_packed,

@@ -150,6 +150,8 @@ __device__ inline int range_of(int f, int requested, int flat_groups, int num_wa
 template <int MODE, int D, int NT, bool CEIL, int DEPTH>
 __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
+  // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
+  constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
   constexpr int EB = PLAIN ? 2 : 1;                // bytes per cache element
   constexpr int DT = D / 16;
   constexpr int KJ = D * EB / 64;  // 16-byte K pieces per lane and quad
@@ -231,8 +233,12 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;  // bytes per cache block
   const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3);  // inside a 4-token quad
   const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16;  // inside a 16-token sub-block
-  const uint32_t s_block_stride = (MODE == KVQ_INT8_TOKEN_HEAD) ? 2u * H * bs : 2u * H;
-  const uint32_t s_kv = (MODE == KVQ_INT8_TOKEN_HEAD) ? (uint32_t)H * bs : (uint32_t)H;
+  const uint32_t s_block_stride = (MODE == KVQ_INT8_TOKEN_HEAD)  ? 2u * H * bs
+                                  : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
+                                                                 : 2u * H;
+  const uint32_t s_kv = (MODE == KVQ_INT8_TOKEN_HEAD)  ? (uint32_t)H * bs
+                        : (MODE == KVQ_FP8E4M3_TENSOR) ? 1u
+                                                       : (uint32_t)H;
 
   // block-table entries of the sub-blocks this lane reads K and V from
   auto fetch_entries = [&](const Cursor& c, int& blk_k, int& blk_v) {
@@ -261,7 +267,9 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       sk = 1.0f;
       sv = 1.0f;
     } else {
-      const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD) ? h * bs + m16 + off_v : h;
+      const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD)  ? h * bs + m16 + off_v
+                              : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
+                                                             : h;
       const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
       sk = __builtin_nontemporal_load(sp);
       sv = __builtin_nontemporal_load(sp + s_kv);
@@ -473,7 +481,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
           pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
         }
       }
-      if constexpr (MODE == KVQ_FP8E4M3_BLOCK_HEAD) lsum = lsum * rsv;  // one scale per lane
+      if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
       l_run[nt] = l_run[nt] * alpha[nt] + lsum;
     }
     if (__any(rescale)) {
@@ -552,7 +560,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     }
   };
   auto pv = [&](const uintx4 (&vt)[VW], const Operand (&pb)[NT][2 * EB], const Cursor& c) {
-    if ((MODE == KVQ_FP8E4M3_BLOCK_HEAD || PLAIN) && (c.g << 6) + 64 > c.L)
+    if ((FP8 || PLAIN) && (c.g << 6) + 64 > c.L)
       pv_impl(std::true_type{}, vt, pb, c);
     else
       pv_impl(std::false_type{}, vt, pb, c);
@@ -814,6 +822,9 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   else if (a.mode == KVQ_FP8E4M3_BLOCK_HEAD)
     e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 128>(a, stream)
                           : launch_stream<KVQ_FP8E4M3_BLOCK_HEAD, 64>(a, stream);
+  else if (a.mode == KVQ_FP8E4M3_TENSOR)
+    e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_TENSOR, 128>(a, stream)
+                          : launch_stream<KVQ_FP8E4M3_TENSOR, 64>(a, stream);
   else
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);

@@ -80,8 +80,9 @@ hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
   const uint32_t block_bytes = 2u * desc.num_kv_heads * desc.block_size * desc.head_dim *
                                elem_bytes(desc.mode);
   const uint32_t scale_floats =
-      desc.mode == KVQ_BF16_PLAIN ? 0u
-      : 2u * desc.num_kv_heads * (desc.mode == KVQ_INT8_TOKEN_HEAD ? desc.block_size : 1);
+      desc.mode == KVQ_INT8_TOKEN_HEAD      ? 2u * desc.num_kv_heads * desc.block_size
+      : desc.mode == KVQ_FP8E4M3_BLOCK_HEAD ? 2u * desc.num_kv_heads
+                                            : 0u;  // no per-block scales
   const uint32_t pieces = (block_bytes + 4095u) / 4096u;
   hipLaunchKernelGGL(block_copy_kernel, dim3((unsigned)num * pieces), dim3(256), 0, stream,
                      (uint8_t*)pool_cache, (float*)pool_scales, (uint8_t*)packed_cache,

@@ -302,23 +302,28 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_bulk_kernel(
 template <int D>
 __device__ inline void fp8_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
-                               int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
+                               int bs, int kv, int h, int t0, int64_t slot0, int run, int lane,
+                               bool tensor_scale) {
   constexpr int E = D / 64;
   const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
   const int o_min = (int)(slot0 - blk * bs);
   const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * E;
   const size_t tstride = (size_t)H * D;
+  // tensor_scale: the scale is the caller's (one per layer for K, one for V) and only read;
+  // otherwise it is the block's, grown to cover this run
   uint32_t amax = 0;
-  for (int i = 0; i < run; ++i) {
+  if (!tensor_scale) {
+    for (int i = 0; i < run; ++i) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const uint32_t a = src[i * tstride + e] & 0x7FFF;
-      amax = a > amax ? a : amax;
+      for (int e = 0; e < E; ++e) {
+        const uint32_t a = src[i * tstride + e] & 0x7FFF;
+        amax = a > amax ? a : amax;
+      }
     }
+    amax = wave_max_u32(amax);
   }
-  amax = wave_max_u32(amax);
-  float* sp = scales + ((size_t)blk * 2 + kv) * H + h;
-  const float s_prev = (o_min > 0) ? *sp : 0.0f;
+  float* sp = tensor_scale ? scales + kv : scales + ((size_t)blk * 2 + kv) * H + h;
+  const float s_prev = (tensor_scale || o_min > 0) ? *sp : 0.0f;
   const float s_cand = (amax == 0) ? 0.0f : (float)((double)bf16_bits_to_float(amax) / 448.0);
   const float s_new = s_prev > s_cand ? s_prev : s_cand;
   // the block's scale grew: the codes stored below the run are re-expressed in the new scale
@@ -369,14 +374,14 @@ __device__ inline void fp8_run(const uint16_t* __restrict__ k, const uint16_t* _
       }
     }
   }
-  if (lane == 0) *sp = s_new;
+  if (lane == 0 && !tensor_scale) *sp = s_new;
 }
 
 template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
-    float* __restrict__ scales, int32_t H, int32_t bs) {
+    float* __restrict__ scales, int32_t H, int32_t bs, int32_t tensor_scale) {
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   if (unit >= (int64_t)num_tokens * H * 2) return;
@@ -389,7 +394,7 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
   if (t0 > 0 && o_min > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
   int run = 1;
   while (run < bs - o_min && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
-  fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+  fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane, tensor_scale != 0);
 }
 
 // ---- fp8, many tokens per call (prefill) ---------------------------------------------------
@@ -419,28 +424,31 @@ __device__ inline uint32_t fp8_code_fast(float x, float inv, float s, bool usabl
 template <int D>
 __device__ inline void fp8_subblocks(const uint16_t* __restrict__ src, size_t tstride,
                                      uint8_t* __restrict__ tile, float* __restrict__ sp, int kv,
-                                     int o_min, int run, int bs, int lane, bool& done) {
+                                     int o_min, int run, int bs, int lane, bool tensor_scale,
+                                     bool& done) {
   constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
   const int c = lane & (CL - 1), g = lane / CL;
   int tok[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) tok[i] = kv ? g * NI + i : i * G + g;
   uint32_t amax = 0;
-  for (int sb = 0; sb < run; sb += 16) {
+  if (!tensor_scale) {
+    for (int sb = 0; sb < run; sb += 16) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      for (int i = 0; i < NI; ++i) {
+        const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
-        amax = amax > lo ? amax : lo;
-        amax = amax > hi ? amax : hi;
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
+          amax = amax > lo ? amax : lo;
+          amax = amax > hi ? amax : hi;
+        }
       }
     }
+    amax = wave_max_u32(amax);
   }
-  amax = wave_max_u32(amax);
-  const float s_prev = (o_min > 0) ? *sp : 0.0f;
+  const float s_prev = (tensor_scale || o_min > 0) ? *sp : 0.0f;
   const float s_cand = (amax == 0) ? 0.0f : __fdiv_rn(bf16_bits_to_float(amax), 448.0f);
   const float s_new = s_prev > s_cand ? s_prev : s_cand;
   done = !(o_min > 0 && s_new > s_prev && s_prev > 0.0f);
@@ -474,7 +482,7 @@ __device__ inline void fp8_subblocks(const uint16_t* __restrict__ src, size_t ts
       }
     }
   }
-  if (lane == 0) *sp = s_new;
+  if (lane == 0 && !tensor_scale) *sp = s_new;
 }
 
 // unit = (window of 16 consecutive tokens of the call, kv head, K|V), as for int8
@@ -482,7 +490,7 @@ template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
-    float* __restrict__ scales, int32_t H, int32_t bs) {
+    float* __restrict__ scales, int32_t H, int32_t bs, int32_t tensor_scale) {
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int windows = (num_tokens + 15) >> 4;
@@ -520,9 +528,11 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
       const int64_t blk = slot0 >> __builtin_ctz(bs);
       fp8_subblocks<D>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
                        cache + tile_offset(blk, kv, h, H, bs, D),
-                       scales + ((size_t)blk * 2 + kv) * H + h, kv, o_min, run, bs, lane, done);
+                       tensor_scale ? scales + kv : scales + ((size_t)blk * 2 + kv) * H + h, kv,
+                       o_min, run, bs, lane, tensor_scale != 0, done);
     }
-    if (!done) fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+    if (!done)
+      fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane, tensor_scale != 0);
   }
 }
 
@@ -571,6 +581,10 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
 #define KVQ_LAUNCH_WRITE(KERNEL, DD)                                                          \
   hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
                      num_tokens, c, scales, desc.num_kv_heads, desc.block_size)
+#define KVQ_LAUNCH_WRITE_FP8(KERNEL, DD)                                                      \
+  hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
+                     num_tokens, c, scales, desc.num_kv_heads, desc.block_size,               \
+                     (int32_t)(desc.mode == KVQ_FP8E4M3_TENSOR))
   if (desc.mode == KVQ_BF16_PLAIN) {
     const unsigned g = (unsigned)(((int64_t)num_tokens * desc.num_kv_heads * 2 + kWaves - 1) / kWaves);
     if (desc.head_dim == 128)
@@ -583,16 +597,17 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
     if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 128);
     else KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 64);
   } else if (bulk) {
-    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_fp8_bulk_kernel, 128);
-    else KVQ_LAUNCH_WRITE(write_fp8_bulk_kernel, 64);
+    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE_FP8(write_fp8_bulk_kernel, 128);
+    else KVQ_LAUNCH_WRITE_FP8(write_fp8_bulk_kernel, 64);
   } else if (desc.mode == KVQ_INT8_TOKEN_HEAD) {
     if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_kernel, 128);
     else KVQ_LAUNCH_WRITE(write_int8_kernel, 64);
   } else {
-    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_fp8_kernel, 128);
-    else KVQ_LAUNCH_WRITE(write_fp8_kernel, 64);
+    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE_FP8(write_fp8_kernel, 128);
+    else KVQ_LAUNCH_WRITE_FP8(write_fp8_kernel, 64);
   }
 #undef KVQ_LAUNCH_WRITE
+#undef KVQ_LAUNCH_WRITE_FP8
   return hipGetLastError();
 }
 

@@ -10,6 +10,7 @@ import os
 MODE_INT8 = 0   # KVQ_INT8_TOKEN_HEAD
 MODE_FP8 = 1    # KVQ_FP8E4M3_BLOCK_HEAD
 MODE_BF16 = 2   # KVQ_BF16_PLAIN (unquantized baseline)
+MODE_FP8_TENSOR = 3  # KVQ_FP8E4M3_TENSOR (static per-tensor scales)
 
 OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, -5
 
@@ -37,6 +38,8 @@ class CacheDesc(C.Structure):
             return (self.num_blocks, 2, self.num_kv_heads, self.block_size)
         if self.mode == MODE_BF16:
             return (0,)
+        if self.mode == MODE_FP8_TENSOR:
+            return (2,)
         return (self.num_blocks, 2, self.num_kv_heads)
 
 
@@ -179,7 +182,9 @@ def _any(t, dtype, name):
 def packed_sizes(desc, num):
     """(cache bytes, scale floats) of `num` packed blocks."""
     nb = max(desc.num_blocks, 1)
-    return (num * (lib().kvq_cache_bytes(desc) // nb), num * (lib().kvq_scales_bytes(desc) // nb // 4))
+    per_block_scales = desc.mode in (MODE_INT8, MODE_FP8)
+    return (num * (lib().kvq_cache_bytes(desc) // nb),
+            num * (lib().kvq_scales_bytes(desc) // nb // 4) if per_block_scales else 0)
 
 
 def blocks_export(cache, scales, desc, block_ids, packed_cache, packed_scales, stream=None):

@@ -52,6 +52,8 @@ def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=No
     desc = gpu_desc(wl)
     if cache is None:
         cache, scales = kvq.alloc_cache(desc)
+        if wl.mode == W.MODE_FP8_TENSOR:
+            scales.copy_(torch.tensor(W.STATIC_SCALES, dtype=torch.float32))
     seqs = range(wl.batch) if sequences is None else sequences
     for b in seqs:
         start, stop = wl.write_range(b)

@@ -42,6 +42,8 @@ def test_sizes():
     assert L.kvq_scales_bytes(C.byref(d(mode=1))) == 8 * 2 * 2 * 4
     assert L.kvq_cache_bytes(C.byref(d(mode=2))) == 8 * 2 * 2 * 16 * 64 * 2   # unquantized: bf16
     assert L.kvq_scales_bytes(C.byref(d(mode=2))) == 0
+    assert L.kvq_cache_bytes(C.byref(d(mode=3))) == 8 * 2 * 2 * 16 * 64       # static fp8 scales:
+    assert L.kvq_scales_bytes(C.byref(d(mode=3))) == 8                        # one for K, one for V
     assert L.kvq_cache_bytes(C.byref(d(D=96))) == 0
     assert L.kvq_cache_bytes(None) == 0
 
@@ -50,7 +52,7 @@ FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below fails validati
 
 
 @pytest.mark.parametrize("desc,code", [
-    (d(mode=3), kvq.E_BAD_MODE), (d(mode=-1), kvq.E_BAD_MODE),
+    (d(mode=99), kvq.E_BAD_MODE), (d(mode=-1), kvq.E_BAD_MODE),
     (d(bs=8), kvq.E_BAD_SHAPE), (d(bs=48), kvq.E_BAD_SHAPE), (d(bs=512), kvq.E_BAD_SHAPE),
     (d(D=96), kvq.E_BAD_SHAPE), (d(D=256), kvq.E_BAD_SHAPE), (d(H=0), kvq.E_BAD_SHAPE),
     (d(nblk=-1), kvq.E_BAD_SHAPE),
@@ -87,7 +89,7 @@ def test_attn_argument_checks():
     L = kvq.lib()
     ok = d()
     assert attn(L, None) == kvq.E_NULLPTR
-    assert attn(L, d(mode=3)) == kvq.E_BAD_MODE
+    assert attn(L, d(mode=99)) == kvq.E_BAD_MODE
     assert attn(L, ok, Hq=3) == kvq.E_BAD_SHAPE            # 3 % 2 != 0
     assert attn(L, ok, q_len=0) == kvq.E_BAD_SHAPE
     assert attn(L, ok, q_len=17) == kvq.E_BAD_SHAPE

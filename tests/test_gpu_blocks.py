@@ -17,7 +17,7 @@ def canon(t, desc):
 
 
 @pytest.mark.parametrize("host", [False, True], ids=["device", "pinned_host"])
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR])
 @pytest.mark.parametrize("bs,D,H", [(16, 128, 8), (64, 64, 3)])
 def test_export_then_import_elsewhere(mode, host, bs, D, H):
     import torch
@@ -38,7 +38,7 @@ def test_export_then_import_elsewhere(mode, host, bs, D, H):
     want_c, want_s = oracle.blocks_export(oc, osc, mode, ids)
     pdesc = kvq.make_desc(mode, n, bs, H, D)          # the packed area is a pool of n blocks
     assert np.array_equal(canon(pc.cuda(), pdesc), want_c)
-    if mode != W.MODE_BF16:
+    if mode in (W.MODE_INT8, W.MODE_FP8):
         assert np.array_equal(ps.cpu().numpy().view(np.uint32).reshape(want_s.shape),
                               want_s.view(np.uint32))
     # import into a second pool at other places

@@ -10,6 +10,9 @@ from paper_2605_29639_amd import workloads as W
 from helpers import bits_to_bf16_tensor, gpu_desc, gpu_fill, oracle_fill
 
 
+ALL_MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR]
+
+
 def fetch(cache, scales, desc):
     from paper_2605_29639_amd import kvq
     canon = kvq.cache_to_canonical(cache, desc).cpu().numpy()
@@ -29,7 +32,7 @@ def assert_pool_equal(wl, got, want):
         sb[0], gs[tuple(sb[0])], ws[tuple(sb[0])])
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", ALL_MODES)
 def test_tiny_config(mode):
     wl = W.tiny(mode)
     cache, scales, desc = gpu_fill(wl)
@@ -46,7 +49,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", ALL_MODES)
 @pytest.mark.parametrize("shape", SHAPES)
 def test_ragged_shapes_bulk_write(mode, shape):
     lens, H, D, bs = shape
@@ -55,7 +58,7 @@ def test_ragged_shapes_bulk_write(mode, shape):
     assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR])
 @pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1)])
 def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     """Thousands of tokens in one call (the prefill kernels): ragged sequences back to back, so
@@ -68,6 +71,9 @@ def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     desc = gpu_desc(wl)
     cache, scales = kvq.alloc_cache(desc)
     oc, osc = oracle.alloc_cache(mode, wl.num_blocks, bs, H, D)
+    if mode == W.MODE_FP8_TENSOR:
+        osc[:] = W.STATIC_SCALES
+        scales.copy_(torch.from_numpy(osc))
     # sequence 3's first 21 tokens were written by an earlier call
     k, v = wl.kv_rows(3, 0, 21)
     s = wl.slots(3, 0, 21)
@@ -127,7 +133,7 @@ def test_fp8_token_by_token_append_with_rescale(bs, D):
     assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", ALL_MODES)
 def test_chunked_prefill_then_appends(mode):
     """A sequence written in uneven pieces (block-aligned or not) and then appended to."""
     import torch
@@ -136,6 +142,9 @@ def test_chunked_prefill_then_appends(mode):
     desc = gpu_desc(wl)
     cache, scales = kvq.alloc_cache(desc)
     oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 128)
+    if mode == W.MODE_FP8_TENSOR:
+        osc[:] = W.STATIC_SCALES
+        scales.copy_(torch.from_numpy(osc))
     for lo, hi in ((0, 16), (16, 37), (37, 38), (38, 96), (96, 149), (149, 150)):
         k, v = wl.kv_rows(0, lo, hi)
         s = wl.slots(0, lo, hi)
