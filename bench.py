@@ -103,7 +103,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_29639_amd import kvq
-    from helpers import bits_to_bf16_tensor, gpu_fill, attn_err
+    from paper_2605_29639_amd.fill import bits_to_bf16_tensor, gpu_fill, attn_err
     kvq.lib()  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream

@@ -33,46 +33,7 @@ def oracle_fill(wl, sequences=None):
 
 # --------------------------------------------------------------------------- GPU side
 
-def bits_to_bf16_tensor(bits, device="cuda"):
-    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 device tensor (no value change)."""
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
-
-
-def gpu_desc(wl):
-    from paper_2605_29639_amd import kvq
-    return kvq.make_desc(wl.mode, wl.num_blocks, wl.block_size, wl.num_kv_heads, wl.head_dim)
-
-
-def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=None):
-    """The library writes the workload into a (zeroed unless given) device pool with the same
-    call sequence as oracle_fill.  Returns (cache, scales, desc)."""
-    import torch
-    from paper_2605_29639_amd import kvq
-    desc = gpu_desc(wl)
-    if cache is None:
-        cache, scales = kvq.alloc_cache(desc)
-        if wl.mode == W.MODE_FP8_TENSOR:
-            scales.copy_(torch.tensor(W.STATIC_SCALES, dtype=torch.float32))
-    seqs = range(wl.batch) if sequences is None else sequences
-    for b in seqs:
-        start, stop = wl.write_range(b)
-        if stop > start:
-            k, v = wl.kv_rows(b, start, stop)
-            kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
-                               torch.from_numpy(wl.slots(b, start, stop)).cuda(), cache, scales,
-                               desc)
-    if wl.append_tokens:
-        ks, vs, ss = [], [], []
-        for b in seqs:
-            p0, p1 = wl.prefill_len(b), int(wl.seq_lens[b])
-            k, v = wl.kv_rows(b, p0, p1)
-            ks.append(k), vs.append(v), ss.append(wl.slots(b, p0, p1))
-        kvq.kv_quant_write(bits_to_bf16_tensor(np.concatenate(ks)),
-                           bits_to_bf16_tensor(np.concatenate(vs)),
-                           torch.from_numpy(np.concatenate(ss)).cuda(), cache, scales, desc)
-    torch.cuda.synchronize()
-    return cache, scales, desc
+from paper_2605_29639_amd.fill import attn_err, bits_to_bf16_tensor, gpu_desc, gpu_fill  # noqa: E402,F401
 
 
 def gpu_attention(wl, cache, scales, desc, chunk_tokens=None, seq_lens=None, q=None, q_len=None):
@@ -109,7 +70,3 @@ def upload_oracle_cache(wl, cache_np, scales_np):
     torch.cuda.synchronize()
     return cache, scales, desc
 
-
-def attn_err(got, want):
-    """max |got - want| / max |want| over the whole output tensor."""
-    return float(np.abs(got.astype(np.float64) - want).max() / np.abs(want).max())
