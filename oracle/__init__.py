@@ -11,7 +11,9 @@ Arrays use the oracle's canonical layout:
   k, v, q uint16 bf16 bit patterns [tokens, heads, head_dim]
 Mode 2 is the unquantized baseline: cache uint16 (bf16 bit patterns), same shape; scales is an
 empty float32 array.  Mode 3 is fp8-e4m3 with static per-tensor scales: scales is float32 [2]
-(K, V), set by the caller and only read.
+(K, V), set by the caller and only read.  Mode 4 is int4 per token-head: cache rows are
+head_dim / 2 bytes (channel 2j in the low nibble of byte j, channel 2j+1 in the high one,
+4-bit two's complement), scales as mode 0.
 """
 import ctypes as C
 
@@ -23,6 +25,7 @@ MODE_INT8 = 0
 MODE_FP8 = 1
 MODE_BF16 = 2
 MODE_FP8_TENSOR = 3
+MODE_INT4 = 4
 
 _lib = None
 
@@ -40,6 +43,8 @@ def lib():
         L.oracle_fp8_encode.argtypes = [C.c_double]
         L.oracle_int8_encode.restype = C.c_int8
         L.oracle_int8_encode.argtypes = [C.c_double, C.c_float]
+        L.oracle_int4_encode.restype = C.c_int8
+        L.oracle_int4_encode.argtypes = [C.c_double, C.c_float]
         L.oracle_scale.restype = C.c_float
         L.oracle_scale.argtypes = [C.c_double, C.c_double]
         L.oracle_kv_quant_write.restype = C.c_int
@@ -111,19 +116,43 @@ def int8_encode(x, s):
     return out
 
 
+def int4_encode(x, s):
+    """RNE(x / s) clamped to [-7, 7]; x float64 array, s one fp32 scale."""
+    x = np.asarray(x, dtype=np.float64)
+    L = lib()
+    out = np.empty(x.shape, dtype=np.int8)
+    flat, o = x.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.oracle_int4_encode(float(flat[i]), float(np.float32(s)))
+    return out
+
+
+def unpack_int4(cache):
+    """int8 codes [..., 2 * n] of an int4 cache [..., n] (low nibble first)."""
+    lo = (cache & 15).astype(np.int8)
+    hi = (cache >> 4).astype(np.int8)
+    both = np.stack([lo, hi], axis=-1).reshape(cache.shape[:-1] + (2 * cache.shape[-1],))
+    return ((both ^ 8) - 8).astype(np.int8)
+
+
+def head_dim_of(cache, mode):
+    return cache.shape[-1] * (2 if mode == MODE_INT4 else 1)
+
+
 def scale(absmax, qmax):
     return np.float32(lib().oracle_scale(float(absmax), float(qmax)))
 
 
 def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
     """Zero-filled canonical cache and scales."""
-    cache = np.zeros((num_blocks, 2, num_kv_heads, block_size, head_dim),
+    cache = np.zeros((num_blocks, 2, num_kv_heads, block_size,
+                      head_dim // 2 if mode == MODE_INT4 else head_dim),
                      dtype=np.uint16 if mode == MODE_BF16 else np.uint8)
     if mode == MODE_BF16:
         scales = np.zeros((0,), dtype=np.float32)
     elif mode == MODE_FP8_TENSOR:
         scales = np.zeros((2,), dtype=np.float32)
-    elif mode == MODE_INT8:
+    elif mode in (MODE_INT8, MODE_INT4):
         scales = np.zeros((num_blocks, 2, num_kv_heads, block_size), dtype=np.float32)
     else:
         scales = np.zeros((num_blocks, 2, num_kv_heads), dtype=np.float32)
@@ -136,7 +165,8 @@ def _chk_cache(cache, scales, mode):
     nblk, two, H, bs, D = cache.shape
     assert two == 2
     assert scales.shape == {MODE_INT8: (nblk, 2, H, bs), MODE_FP8: (nblk, 2, H),
-                            MODE_BF16: (0,), MODE_FP8_TENSOR: (2,)}[mode]
+                            MODE_BF16: (0,), MODE_FP8_TENSOR: (2,),
+                            MODE_INT4: (nblk, 2, H, bs)}[mode]
 
 
 def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
@@ -144,7 +174,8 @@ def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
     _chk(k, np.uint16, "k"), _chk(v, np.uint16, "v")
     _chk(slot_mapping, np.int64, "slot_mapping")
     _chk_cache(cache, scales, mode)
-    nblk, two, H, bs, D = cache.shape
+    nblk, two, H, bs, _ = cache.shape
+    D = head_dim_of(cache, mode)
     assert k.shape == v.shape == (slot_mapping.shape[0], H, D)
     live = slot_mapping[slot_mapping >= 0]
     assert live.size == 0 or int(live.max()) < nblk * bs
@@ -159,6 +190,8 @@ def dequant(cache, scales, mode):
     nblk, _, H, bs, D = cache.shape
     if mode == MODE_BF16:
         return bf16_to_f64(cache)
+    if mode == MODE_INT4:
+        return unpack_int4(cache).astype(np.float64) * scales.astype(np.float64)[..., None]
     if mode == MODE_INT8:
         return cache.view(np.int8).astype(np.float64) * scales.astype(np.float64)[..., None]
     table = fp8_decode(np.arange(256, dtype=np.uint8))
@@ -171,7 +204,8 @@ def gather_dequant(cache, scales, mode, block_table_row, n, kv, h):
     """Dense fp64 [n, D] of K (kv=0) or V (kv=1) of one sequence and kv head."""
     _chk_cache(cache, scales, mode)
     row = np.ascontiguousarray(block_table_row, dtype=np.int32)
-    nblk, _, H, bs, D = cache.shape
+    nblk, _, H, bs, _ = cache.shape
+    D = head_dim_of(cache, mode)
     assert (n + bs - 1) // bs <= row.shape[0]
     assert n == 0 or (row[:(n + bs - 1) // bs].min() >= 0 and row[:(n + bs - 1) // bs].max() < nblk)
     dense = np.empty((n, D), dtype=np.float64)
@@ -184,7 +218,8 @@ def paged_decode_attn(q, cache, scales, mode, block_tables, seq_lens, q_len, sm_
     """out float64 [batch*q_len, H_q, D]."""
     _chk(q, np.uint16, "q"), _chk_cache(cache, scales, mode)
     _chk(block_tables, np.int32, "block_tables"), _chk(seq_lens, np.int32, "seq_lens")
-    nblk, _, H, bs, D = cache.shape
+    nblk, _, H, bs, _ = cache.shape
+    D = head_dim_of(cache, mode)
     batch = seq_lens.shape[0]
     assert q.shape[0] == batch * q_len and q.shape[2] == D
     Hq = q.shape[1]
@@ -207,7 +242,8 @@ def attn_weights(q, cache, scales, mode, block_table_row, seq_len, q_len, j, hq,
     """Softmax weights of one (sequence, query token j, q head hq): float64 [n]."""
     _chk(q, np.uint16, "q"), _chk_cache(cache, scales, mode)
     row = np.ascontiguousarray(block_table_row, dtype=np.int32)
-    nblk, _, H, bs, D = cache.shape
+    nblk, _, H, bs, _ = cache.shape
+    D = head_dim_of(cache, mode)
     n = seq_len - q_len + j + 1
     w = np.empty(n, dtype=np.float64)
     got = lib().oracle_attn_weights(_ptr(q), _ptr(cache), _ptr(scales), mode, bs, H, D, _ptr(row),
@@ -223,7 +259,7 @@ def blocks_export(cache, scales, mode, block_ids):
     _chk_cache(cache, scales, mode)
     ids = np.asarray(block_ids, dtype=np.int64)
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
-    per_block = mode in (MODE_INT8, MODE_FP8)  # else the scales are not part of a block
+    per_block = mode in (MODE_INT8, MODE_FP8, MODE_INT4)  # else the scales are not part of a block
     packed_scales = scales[ids].copy() if per_block else scales.copy()
     return cache[ids].copy(), packed_scales
 
@@ -237,7 +273,7 @@ def blocks_import(packed_cache, packed_scales, mode, block_ids, cache, scales):
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
     for i, blk in enumerate(ids):
         cache[blk] = packed_cache[i]
-        if mode in (MODE_INT8, MODE_FP8):
+        if mode in (MODE_INT8, MODE_FP8, MODE_INT4):
             scales[blk] = packed_scales[i]
 
 

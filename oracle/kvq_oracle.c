@@ -22,6 +22,8 @@
  *           f32 [num_blocks][2][num_kv_heads]                  (mode 1, fp8)
  *           unused                                             (mode 2)
  *           f32 [2] (K, V), an input                           (mode 3)
+ *           as mode 0                                          (mode 4; cache rows are
+ *           head_dim / 2 bytes)
  *   k, v, q : bf16 bit patterns (uint16), [tokens][heads][head_dim]
  *   out     : f64 [batch*q_len][num_q_heads][head_dim]
  *
@@ -44,6 +46,11 @@
  * K and one for all of its V, fixed beforehand by the caller (scales[0], scales[1]); the write
  * only encodes, values beyond 448 scales saturate. */
 #define ORACLE_MODE_FP8_TENSOR 3
+/* INT4, the third format Section 7.2.2 names: codes in [-7, 7], one fp32 scale per (token,
+ * kv head) as for int8 (scale = fp32 nearest to absmax / 7), two codes per byte: byte j of a
+ * row holds channel 2j in its low nibble and channel 2j+1 in its high nibble, each a 4-bit
+ * two's complement number.  The cache's last dimension is head_dim / 2 bytes. */
+#define ORACLE_MODE_INT4 4
 
 /* ---- O1: a bf16 bit pattern is the top half of an fp32; widening is exact ---- */
 double oracle_bf16_to_f64(uint16_t bits) {
@@ -107,6 +114,17 @@ int8_t oracle_int8_encode(double x, float s) {
   return (int8_t)r;
 }
 
+/* int4: the same rule with 7 in place of 127 (the quotient of a bf16 by an fp32 value is a
+ * half-integer exactly or at least 2^-25 away from one, whatever the divisor's size) */
+int8_t oracle_int4_encode(double x, float s) {
+  double r;
+  if (s == 0.0f) return 0;
+  r = rint(x / (double)s);
+  if (r > 7.0) r = 7.0;
+  if (r < -7.0) r = -7.0;
+  return (int8_t)r;
+}
+
 /* scale = fp32 nearest to absmax / qmax */
 float oracle_scale(double absmax, double qmax) { return (float)(absmax / qmax); }
 
@@ -165,6 +183,34 @@ int oracle_kv_quant_write(const uint16_t* k, const uint16_t* v, const int64_t* s
         for (int h = 0; h < H; ++h)
           memcpy(cache16 + tile_index(blk, kv, h, H, bs, D) + (size_t)off * D,
                  (kv ? v : k) + ((size_t)t * H + h) * D, sizeof(uint16_t) * (size_t)D);
+    }
+    return 0;
+  }
+  if (mode == ORACLE_MODE_INT4) {
+    const int Db = D / 2; /* bytes per row */
+    for (int32_t t = 0; t < num_tokens; ++t) {
+      int64_t slot = slot_mapping[t];
+      if (slot < 0) continue;
+      int64_t blk = slot / bs;
+      int off = (int)(slot % bs);
+      for (int kv = 0; kv < 2; ++kv) {
+        for (int h = 0; h < H; ++h) {
+          const uint16_t* row = (kv ? v : k) + ((size_t)t * H + h) * D;
+          double m = 0.0;
+          for (int d = 0; d < D; ++d) {
+            double a = fabs(oracle_bf16_to_f64(row[d]));
+            if (a > m) m = a;
+          }
+          float s = (m == 0.0) ? 0.0f : oracle_scale(m, 7.0);
+          scales[(((size_t)blk * 2 + kv) * H + h) * bs + off] = s;
+          uint8_t* dst = cache + tile_index(blk, kv, h, H, bs, Db) + (size_t)off * Db;
+          for (int j = 0; j < Db; ++j) {
+            int lo = oracle_int4_encode(oracle_bf16_to_f64(row[2 * j]), s);
+            int hi = oracle_int4_encode(oracle_bf16_to_f64(row[2 * j + 1]), s);
+            dst[j] = (uint8_t)((lo & 15) | ((hi & 15) << 4));
+          }
+        }
+      }
     }
     return 0;
   }
@@ -256,6 +302,12 @@ double oracle_dequant_at(const uint8_t* cache, const float* scales, int32_t mode
                          int kv, int h, int off, int d, int32_t block_size,
                          int32_t num_kv_heads, int32_t head_dim) {
   const int H = num_kv_heads, D = head_dim, bs = block_size;
+  if (mode == ORACLE_MODE_INT4) {
+    uint8_t byte = cache[tile_index(blk, kv, h, H, bs, D / 2) + (size_t)off * (D / 2) + d / 2];
+    int nib = (d & 1) ? (byte >> 4) : (byte & 15);
+    int code = (nib ^ 8) - 8; /* 4-bit two's complement */
+    return (double)code * (double)scales[(((size_t)blk * 2 + kv) * H + h) * bs + off];
+  }
   if (mode == ORACLE_MODE_BF16)
     return oracle_bf16_to_f64(
         ((const uint16_t*)cache)[tile_index(blk, kv, h, H, bs, D) + (size_t)off * D + d]);

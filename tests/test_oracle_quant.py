@@ -418,7 +418,7 @@ def test_footprint_is_half_of_bf16():
         assert 0.5 <= ratio <= 0.52
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4])
 def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
     """The tiered cache's block moves are index copies: checked element by element against
     explicit loops, as a round trip, and for leaving every other block alone."""
@@ -427,6 +427,7 @@ def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
     cache, scales = oracle.alloc_cache(mode, nblk, bs, H, D)
     cache[:] = rng.integers(0, 1 << (8 * cache.itemsize), size=cache.shape, dtype=np.uint32).astype(cache.dtype)
     scales[...] = rng.random(scales.shape, dtype=np.float32)
+    per_block_scales = mode in (W.MODE_INT8, W.MODE_FP8, W.MODE_INT4)
     ids = np.array([7, 0, 3], dtype=np.int32)
     pc, ps = oracle.blocks_export(cache, scales, mode, ids)
     assert pc.shape == (3,) + cache.shape[1:]
@@ -434,7 +435,7 @@ def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
         for kv in range(2):
             for h in range(H):
                 assert np.array_equal(pc[i, kv, h], cache[blk, kv, h])
-                if mode != W.MODE_BF16:
+                if per_block_scales:
                     assert np.array_equal(ps[i, kv, h], scales[blk, kv, h])
     # import into another pool at other ids: those blocks change, the rest do not
     pool, pscales = oracle.alloc_cache(mode, nblk, bs, H, D)
@@ -447,11 +448,13 @@ def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
         assert np.array_equal(pool[blk], cache[ids[i]])
     others = [b for b in range(nblk) if b not in dst]
     assert np.array_equal(pool[others], before[others])
-    if mode != W.MODE_BF16:
+    if per_block_scales:
         assert np.array_equal(pscales[dst], scales[ids]) and np.array_equal(pscales[others], before_s[others])
+    else:
+        assert np.array_equal(pscales, before_s)
     # round trip
     back, back_s = oracle.blocks_export(pool, pscales, mode, dst)
-    assert np.array_equal(back, pc) and np.array_equal(back_s, ps)
+    assert np.array_equal(back, pc) and (not per_block_scales or np.array_equal(back_s, ps))
 
 
 def test_static_per_tensor_fp8_codes():
@@ -511,3 +514,75 @@ def test_static_per_tensor_fp8_codes():
     oracle.kv_quant_write(f32_bits_of(x), f32_bits_of(x), np.arange(bs, dtype=np.int64), cache,
                           scales, 3)
     assert not cache[0, 0].any() and cache[0, 1].any()
+
+
+# ---------------------------------------------------------------------------- int4
+
+def write_rows_int4(k_rows):
+    """Write T rows (values exact in bf16) for 1 head into a fresh int4 pool; returns
+    (codes int8 [T, D], scales [T], raw cache)."""
+    k_rows = np.asarray(k_rows, dtype=np.float32)
+    T, D = k_rows.shape
+    kb = f32_bits_of(k_rows).reshape(T, 1, D)
+    bs = 16
+    nblk = (T + bs - 1) // bs
+    cache, scales = oracle.alloc_cache(oracle.MODE_INT4, nblk, bs, 1, D)
+    oracle.kv_quant_write(kb, kb.copy(), np.arange(T, dtype=np.int64), cache, scales, oracle.MODE_INT4)
+    raw = cache[:, 0, 0].reshape(nblk * bs, D // 2)[:T]
+    # unpacked here by hand, not with the checker's own helper
+    codes = np.empty((T, D), dtype=np.int8)
+    codes[:, 0::2] = ((raw & 15).astype(np.int16) ^ 8) - 8
+    codes[:, 1::2] = ((raw >> 4).astype(np.int16) ^ 8) - 8
+    return codes, scales[:, 0, 0].reshape(nblk * bs)[:T], cache, scales
+
+
+def test_int4_hand_computed_ties_and_nibble_order(golden_dir):
+    rows = read_table(os.path.join(golden_dir, "int4_ties.txt"))
+    xs = [float(r[0]) for r in rows]
+    want = [int(r[1]) for r in rows]
+    D = 64
+    row = np.zeros(D, dtype=np.float32)
+    row[:len(xs)] = xs
+    for x in xs:
+        bf16_exact(x)
+    codes, sc, cache, _ = write_rows_int4(row[None, :])
+    assert sc[0] == np.float32(1.0)
+    assert codes[0, :len(xs)].tolist() == want
+    assert not codes[0, len(xs):].any()
+    # byte 0 holds channel 0 (7 -> 0x7) low and channel 1 (-7 -> 0x9) high; byte 1: 6, 6
+    assert cache[0, 0, 0, 0, 0] == 0x97 and cache[0, 0, 0, 0, 1] == 0x66
+    assert cache.shape[-1] == D // 2
+
+
+def test_int4_codes_equal_exact_rational_rounding_and_never_minus_eight():
+    rng = np.random.default_rng(71)
+    T, D = 600, 128
+    x = rng.standard_normal((T, D), dtype=np.float32)
+    x[:, 5] *= 3.0
+    xv = W.bf16_bits_to_f32(f32_bits_of(x))
+    codes, sc, cache, scales = write_rows_int4(xv)
+    for t in range(T):
+        m = Fraction(float(np.abs(xv[t]).max()))
+        assert sc[t] == nearest_f32(m / 7), t
+        s = Fraction(float(sc[t]))
+        want = [max(-7, min(7, rne_fraction(Fraction(float(v)) / s))) for v in xv[t]]
+        assert codes[t].tolist() == want, t
+    assert codes.min() == -7 and codes.max() == 7
+    assert np.all(np.abs(codes.astype(np.int32)).max(axis=1) == 7)
+    # round trip: |x - code * s| <= s / 2, and the checker's own unpack / dequant agree
+    s64 = sc.astype(np.float64)[:, None]
+    assert np.all(np.abs(xv.astype(np.float64) - codes * s64) <= s64 / 2 * (1 + 1e-12))
+    assert np.array_equal(oracle.unpack_int4(cache)[:, 0, 0].reshape(-1, D)[:T], codes)
+    dq = oracle.dequant(cache, scales, oracle.MODE_INT4)
+    assert np.array_equal(dq[:, 0, 0].reshape(-1, D)[:T], codes * s64)
+
+
+def test_int4_scale_is_correctly_rounded_and_zero_rows():
+    hi = np.arange(0x0080, 0x7F80, 41, dtype=np.uint32)
+    for v in (hi << np.uint32(16)).view(np.float32):
+        assert oracle.scale(float(v), 7.0) == nearest_f32(Fraction(float(v)) / 7)
+    row = np.zeros((2, 64), dtype=np.float32)
+    row[1, 3] = -2.0
+    codes, sc, cache, _ = write_rows_int4(row)
+    assert sc[0] == 0 and not cache[0, 0, 0, 0].any()
+    assert sc[1] == np.float32(2.0 / 7) and codes[1, 3] == -7 and np.count_nonzero(codes[1]) == 1
