@@ -43,7 +43,7 @@ class HipEvents:
         return ms.value
 
 
-MODE_NAMES = {0: "int8", 1: "fp8", 2: "bf16", 3: "fp8_tensor"}
+MODE_NAMES = {0: "int8", 1: "fp8", 2: "bf16", 3: "fp8_tensor", 4: "int4"}
 
 
 def measured_traffic(wl):
@@ -61,7 +61,8 @@ def make_workload(name, mode):
     from paper_2605_29639_amd import workloads as W
     kw = {} if mode is None else {"mode": {"int8": W.MODE_INT8, "fp8": W.MODE_FP8,
                                            "bf16": W.MODE_BF16,
-                                           "fp8_tensor": W.MODE_FP8_TENSOR}[mode]}
+                                           "fp8_tensor": W.MODE_FP8_TENSOR,
+                                           "int4": W.MODE_INT4}[mode]}
     if name == "llama8b":
         return W.llama8b(**kw)
     if name == "fp8_append":
@@ -81,7 +82,7 @@ def main():
     ap.add_argument("--prewarm-s", type=float, default=0.5,
                     help="seconds of untimed load before the warmup steps")
     ap.add_argument("--workload", default="llama8b")
-    ap.add_argument("--mode", default=None, choices=["int8", "fp8", "bf16", "fp8_tensor"],
+    ap.add_argument("--mode", default=None, choices=["int8", "fp8", "bf16", "fp8_tensor", "int4"],
                     help="override the workload's cache mode (bf16 = the unquantized baseline)")
     ap.add_argument("--layers", type=int, default=0, help="layer caches cycled (0 = auto)")
     ap.add_argument("--chunk", type=int, default=-1, help="split-K granule in tokens (-1 or 0 = automatic)")
@@ -236,10 +237,11 @@ def main():
         "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("bf16 rows, bf16 MFMA operands, f32 accumulate" if wl.mode == 2 else
+                  "u4 codes, f16 MFMA operands, f32 accumulate" if wl.mode == 4 else
                   "u8 codes, f16 MFMA operands, f32 accumulate"),
         "data": "synthetic" if not args.alias_blocks else "INVALID: aliased block tables (diagnostic)",
         "config": {"workload": wl.name, "mode": {0: "int8_token_head", 1: "fp8e4m3_block_head", 2: "bf16_unquantized",
-                            3: "fp8e4m3_static_tensor_scales"}[wl.mode],
+                            3: "fp8e4m3_static_tensor_scales", 4: "int4_token_head"}[wl.mode],
                    "batch": B, "q_len": wl.q_len, "num_q_heads": Hq, "num_kv_heads": wl.num_kv_heads,
                    "head_dim": D, "block_size": wl.block_size, "sum_seq_lens": int(wl.seq_lens.sum()),
                    "max_seq_len": max_len, "chunk_tokens": chunk or "auto (even split over 2048 wavefronts)",
@@ -287,7 +289,7 @@ def main():
     te1.record()
     torch.cuda.synchronize()
     bulk_s = te0.elapsed_time(te1) / 10 * 1e-3
-    per_row = 2 * D + {0: D + 4, 1: D + 4.0 / wl.block_size, 2: 2 * D, 3: D}[wl.mode]
+    per_row = 2 * D + {0: D + 4, 1: D + 4.0 / wl.block_size, 2: 2 * D, 3: D, 4: D / 2 + 4}[wl.mode]
     bulk_bytes = n_tok * wl.num_kv_heads * 2 * per_row
     result["prefill_write"] = {"tokens": n_tok, "sequences": n_seq, "us": bulk_s * 1e6,
                                "bytes": bulk_bytes, "GB/s": bulk_bytes / bulk_s / 1e9,

@@ -41,9 +41,11 @@ typedef enum {
                                  baseline the paper's Section 8.5 measures its quantized
                                  cache against ("BF16 KV cache"); same entry points, twice
                                  the bytes */
-  KVQ_FP8E4M3_TENSOR = 3      /* E4M3 codes with static per-tensor scales: one fp32 scale for
+  KVQ_FP8E4M3_TENSOR = 3,     /* E4M3 codes with static per-tensor scales: one fp32 scale for
                                  all of the layer's K, one for all of its V, chosen by the
                                  caller beforehand and only read by the library */
+  KVQ_INT4_TOKEN_HEAD = 4     /* int4 codes in [-7,7], two per byte, one fp32 scale per
+                                 (token, kv head); head_dim 128 only */
 } kvq_mode_t;
 
 enum {
@@ -78,6 +80,15 @@ enum {
  * (the same idea with 8-element pieces); there is no scales buffer (its size is 0 and the
  * `scales` arguments are ignored and may be NULL).
  * KVQ_FP8E4M3_TENSOR: the cache is the e4m3 one; scales is f32 [2] = {K scale, V scale}.
+ * KVQ_INT4_TOKEN_HEAD (head_dim 128): a tile is block_size * 64 bytes; a code is stored as the
+ * nibble code + 8.  Eight codes that feed one lane of a matrix instruction share a 32-bit word,
+ * element e of the eight in nibble e/2 (e even) or e/2 + 4 (e odd), so that one AND-OR
+ * isolates two neighbouring elements as an f16 pair.  Word holding logical element (off, d):
+ *     K:  (off/4) * 256 + ((d%32)/8) * 64 + (off%4) * 16 + (d/32) * 4,   e = d % 8
+ *     V:  (off/16) * 1024 + (d/32) * 256 + (d%16) * 16 + ((d/16)%2) * 8 + ((off%16)/8) * 4,
+ *         e = off % 8
+ * scales as for KVQ_INT8_TOKEN_HEAD.  The canonical form packs channel 2j (low nibble) and
+ * 2j+1 (high nibble) of a token in byte j, 4-bit two's complement, rows of head_dim/2 bytes.
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
  *         f32 [num_blocks][2][num_kv_heads]               for KVQ_FP8E4M3_BLOCK_HEAD
  * Supported: head_dim 64 or 128; block_size a power of two in [16, 256]. */
@@ -104,6 +115,7 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
  * KVQ_INT8_TOKEN_HEAD: per (token, kv head), separately for K and V: scale = fp32 nearest to
  *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
  *   exact x/scale, clamped to [-127, 127].
+ * KVQ_INT4_TOKEN_HEAD: as KVQ_INT8_TOKEN_HEAD with 7 in place of 127.
  * KVQ_BF16_PLAIN: the rows are copied to their slots unchanged.
  * KVQ_FP8E4M3_TENSOR: code = encode(x / scales[kv]) (0x00 when the scale is 0), saturating at
  *   +-448; the scales are not modified.

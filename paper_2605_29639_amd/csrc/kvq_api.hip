@@ -9,14 +9,16 @@ namespace {
 bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   if (!d) { *err = KVQ_E_NULLPTR; return false; }
   if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD &&
-      d->mode != KVQ_BF16_PLAIN && d->mode != KVQ_FP8E4M3_TENSOR) {
+      d->mode != KVQ_BF16_PLAIN && d->mode != KVQ_FP8E4M3_TENSOR &&
+      d->mode != KVQ_INT4_TOKEN_HEAD) {
     *err = KVQ_E_BAD_MODE;
     return false;
   }
   const int bs = d->block_size;
   const bool bs_ok = bs >= 16 && bs <= 256 && (bs & (bs - 1)) == 0;
   if (d->num_blocks < 0 || !bs_ok || d->num_kv_heads <= 0 ||
-      (d->head_dim != 64 && d->head_dim != 128)) {
+      (d->head_dim != 64 && d->head_dim != 128) ||
+      (d->mode == KVQ_INT4_TOKEN_HEAD && d->head_dim != 128)) {
     *err = KVQ_E_BAD_SHAPE;
     return false;
   }
@@ -81,8 +83,8 @@ extern "C" {
 size_t kvq_cache_bytes(const kvq_cache_desc_t* desc) {
   int err;
   if (!desc_ok(desc, &err)) return 0;
-  return (size_t)desc->num_blocks * 2 * desc->num_kv_heads * desc->block_size * desc->head_dim *
-         kvq::elem_bytes(desc->mode);
+  return (size_t)desc->num_blocks * 2 * desc->num_kv_heads * desc->block_size *
+         kvq::row_bytes(desc->mode, desc->head_dim);
 }
 
 size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
@@ -90,7 +92,7 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
   if (!desc_ok(desc, &err) || desc->mode == KVQ_BF16_PLAIN) return 0;
   if (desc->mode == KVQ_FP8E4M3_TENSOR) return 2 * sizeof(float);
   const size_t per_block = (size_t)2 * desc->num_kv_heads *
-                           (desc->mode == KVQ_INT8_TOKEN_HEAD ? desc->block_size : 1);
+                           (desc->mode == KVQ_FP8E4M3_BLOCK_HEAD ? 1 : desc->block_size);
   return (size_t)desc->num_blocks * per_block * sizeof(float);
 }
 
@@ -203,13 +205,14 @@ static int block_copy(const void* pool_cache, const float* pool_scales,
   if (!desc_ok(desc, &err)) return err;
   // one workgroup per 4 KiB piece of a block; 32-bit byte offsets inside a block
   const int64_t block_bytes = (int64_t)2 * desc->num_kv_heads * desc->block_size *
-                              desc->head_dim * kvq::elem_bytes(desc->mode);
+                              kvq::row_bytes(desc->mode, desc->head_dim);
   if (num < 0 || block_bytes > 0x7FFFFFFF || (int64_t)num * ((block_bytes + 4095) / 4096) > 0x7FFFFFFF)
     return KVQ_E_BAD_SHAPE;
   if (num == 0) return KVQ_OK;
   if (!pool_cache || !block_ids || !packed_cache) return KVQ_E_NULLPTR;
-  const bool block_scales =
-      desc->mode == KVQ_INT8_TOKEN_HEAD || desc->mode == KVQ_FP8E4M3_BLOCK_HEAD;
+  const bool block_scales = desc->mode == KVQ_INT8_TOKEN_HEAD ||
+                            desc->mode == KVQ_FP8E4M3_BLOCK_HEAD ||
+                            desc->mode == KVQ_INT4_TOKEN_HEAD;
   if (block_scales && (!pool_scales || !packed_scales)) return KVQ_E_NULLPTR;
   if ((((uintptr_t)pool_cache | (uintptr_t)packed_cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const hipError_t e = kvq::launch_block_copy(pool_cache, pool_scales, *desc, block_ids, num,

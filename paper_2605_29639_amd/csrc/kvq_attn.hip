@@ -93,6 +93,25 @@ __device__ inline void cvt4(uint32_t x, half2v& lo, half2v& hi) {
   }
 }
 
+// Eight stored int4 nibbles (code + 8) of one word -> eight f16 codes; element 2i comes from
+// nibble i, element 2i + 1 from nibble i + 4.  An AND-OR drops two nibbles, 16 bits apart,
+// into the mantissas of a pair of f16 1024.0: nibbles at bits 0-3 give 1024 + n, nibbles at
+// bits 4-7 give 1024 + 16 n; one packed add or fused multiply-add turns either into n - 8.
+__device__ inline half8 cvt_int4(uint32_t x) {
+  const half2v k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+  const half2v k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+  const half2v k72 = {(_Float16)72.0f, (_Float16)72.0f};
+  const uint32_t y = x >> 8;
+  const half2v a = __builtin_bit_cast(half2v, (x & 0x000F000Fu) | 0x64006400u) - k1032;
+  const half2v b = __builtin_bit_cast(half2v, (x & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+  const half2v c = __builtin_bit_cast(half2v, (y & 0x000F000Fu) | 0x64006400u) - k1032;
+  const half2v d = __builtin_bit_cast(half2v, (y & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+  half8 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+  return r;
+}
+
 template <int MODE>
 __device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
   half2v a, b, c, d;
@@ -152,10 +171,14 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
   // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
+  constexpr bool INT4 = MODE == KVQ_INT4_TOKEN_HEAD;  // two codes per byte (head_dim 128)
+  // one fp32 scale per token and head, K and V
+  constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD || INT4;
   constexpr int EB = PLAIN ? 2 : 1;                // bytes per cache element
+  constexpr int RB = INT4 ? D / 2 : D * EB;        // bytes per token row in a tile
   constexpr int DT = D / 16;
-  constexpr int KJ = D * EB / 64;  // 16-byte K pieces per lane and quad
-  constexpr int VW = DT * EB;      // 16-byte V pieces per lane
+  constexpr int KJ = RB / 64;      // 16-byte K pieces per lane and quad
+  constexpr int VW = RB / 16;      // 16-byte V pieces per lane
   constexpr int KS = D / 32;       // MFMA steps over the channels
   // matrix-instruction operand of 8 values: f16 (from codes) or the cache's own bf16
   using Operand = std::conditional_t<PLAIN, bf16x8, half8>;
@@ -228,15 +251,15 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads, NRG = p.num_row_groups;
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
-  const uint32_t tile_bytes = (uint32_t)bs * D * EB;
+  const uint32_t tile_bytes = (uint32_t)bs * RB;
   const int sbk = m16 >> 2;  // sub-block this lane reads K from
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;  // bytes per cache block
   const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3);  // inside a 4-token quad
   const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16;  // inside a 16-token sub-block
-  const uint32_t s_block_stride = (MODE == KVQ_INT8_TOKEN_HEAD)  ? 2u * H * bs
+  const uint32_t s_block_stride = TOKEN_SCALE                    ? 2u * H * bs
                                   : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
                                                                  : 2u * H;
-  const uint32_t s_kv = (MODE == KVQ_INT8_TOKEN_HEAD)  ? (uint32_t)H * bs
+  const uint32_t s_kv = TOKEN_SCALE                    ? (uint32_t)H * bs
                         : (MODE == KVQ_FP8E4M3_TENSOR) ? 1u
                                                        : (uint32_t)H;
 
@@ -256,18 +279,18 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
     const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
     const uint8_t* kbase =
-        cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * (D * EB) + k_lane);
-    vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * (D * EB));
+        cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * RB + k_lane);
+    vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * RB);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int j = 0; j < KJ; ++j)
-        kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * D * EB) + 256 * j));
+        kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
     if constexpr (PLAIN) {
       sk = 1.0f;
       sv = 1.0f;
     } else {
-      const uint32_t s_lane = (MODE == KVQ_INT8_TOKEN_HEAD)  ? h * bs + m16 + off_v
+      const uint32_t s_lane = TOKEN_SCALE                    ? h * bs + m16 + off_v
                               : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
                                                              : h;
       const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
@@ -306,7 +329,8 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         // the 8 channels this lane contributes to step s: the ones its K pieces hold
-        const int d0 = PLAIN ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+        const int d0 =
+            PLAIN || INT4 ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
         const uintx4 raw = *(const uintx4*)(qrow + d0);
         if constexpr (PLAIN) {
           qb[nt][s] = __builtin_bit_cast(bf16x8, live ? raw : uintx4{0u, 0u, 0u, 0u});
@@ -381,6 +405,14 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
             S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[nt][j], S[nt][u], 0, 0, 0);
+        } else if constexpr (INT4) {  // word s of the piece: the 8 channels of step 4 j + s
+#pragma unroll
+          for (int st = 0; st < 4; ++st) {
+            const half8 a = cvt_int4(raw[st]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qb[nt][4 * j + st], S[nt][u], 0, 0, 0);
+          }
         } else {
           const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
           const half8 a1 = cvt8<MODE>(raw[2], raw[3]);
@@ -411,7 +443,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
     float skp = sk * p.scale_log2;
     float lsv = PLAIN ? 0.0f : __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
     float rsv = PLAIN ? 1.0f : __builtin_amdgcn_exp2f(-lsv);
-    if (MODE == KVQ_INT8_TOKEN_HEAD && TAIL && pos0 + 16 * g4 + m16 >= L) {
+    if (TOKEN_SCALE && TAIL && pos0 + 16 * g4 + m16 >= L) {
       skp = 0.0f;  // a slot that was never written: its scales are not data
       lsv = 0.0f;
       rsv = 0.0f;
@@ -425,7 +457,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         float ze;
-        if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
+        if constexpr (TOKEN_SCALE) {
           ze = S[nt][u][i] * row_bcast<tix>(skp);
           ze = ze + row_bcast<tix>(lsv);
         } else if constexpr (PLAIN) {
@@ -453,7 +485,7 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
       static_for<16>([&](auto I) {
         constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
         const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
-        if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
+        if constexpr (TOKEN_SCALE) {
           const float t = pr * row_bcast<tix>(rsv);
           lsum = lsum + t;
         } else {
@@ -532,6 +564,23 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
           acc[nt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[nt][2 + hf], acc[nt][tt], 0, 0, 0);
         }
       }
+      return;
+    }
+    if constexpr (INT4) {
+      // a piece holds two channel tiles (2 x and 2 x + 1): words 0, 1 the first tile's tokens
+      // 0-7 and 8-15, words 2, 3 the second tile's
+#pragma unroll
+      for (int x = 0; x < VW; ++x)
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+          const half8 a0 = cvt_int4(vt[x][2 * par]);
+          const half8 a1 = cvt_int4(vt[x][2 * par + 1]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, pb[nt][0], acc[nt][2 * x + par], 0, 0, 0);
+            acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, pb[nt][1], acc[nt][2 * x + par], 0, 0, 0);
+          }
+        }
       return;
     }
     uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
@@ -825,6 +874,8 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   else if (a.mode == KVQ_FP8E4M3_TENSOR)
     e = a.head_dim == 128 ? launch_stream<KVQ_FP8E4M3_TENSOR, 128>(a, stream)
                           : launch_stream<KVQ_FP8E4M3_TENSOR, 64>(a, stream);
+  else if (a.mode == KVQ_INT4_TOKEN_HEAD)
+    e = launch_stream<KVQ_INT4_TOKEN_HEAD, 128>(a, stream);  // (the only head_dim it takes)
   else
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);

@@ -39,6 +39,23 @@ __host__ __device__ inline int v_elem16(int off, int d, int head_dim) {
   return (off >> 4) * (16 * head_dim) + ((off >> 3) & 1) * (8 * head_dim) + d * 8 + (off & 7);
 }
 __host__ __device__ inline int elem_bytes(int mode) { return mode == KVQ_BF16_PLAIN ? 2 : 1; }
+// bytes one token's head_dim values take in the cache
+__host__ __device__ inline int row_bytes(int mode, int head_dim) {
+  return mode == KVQ_BF16_PLAIN ? 2 * head_dim : mode == KVQ_INT4_TOKEN_HEAD ? head_dim / 2 : head_dim;
+}
+
+// int4 (head_dim 128): byte offset, inside a tile, of the 32-bit word that holds logical element
+// (off, d), and the nibble of that word it sits in.  A word holds the 8 codes one lane feeds to
+// one matrix instruction (K: 8 channels of a token; V: 8 tokens of a channel), element e of the
+// 8 in nibble e/2 (even e) or e/2 + 4 (odd e).
+__host__ __device__ inline int int4_k_word(int off, int d) {
+  return (off >> 2) * 256 + ((d & 31) >> 3) * 64 + (off & 3) * 16 + (d >> 5) * 4;
+}
+__host__ __device__ inline int int4_v_word(int off, int d) {
+  return (off >> 4) * 1024 + (d >> 5) * 256 + (d & 15) * 16 + ((d >> 4) & 1) * 8 +
+         ((off >> 3) & 1) * 4;
+}
+__host__ __device__ inline int int4_nibble(int e) { return (e >> 1) + ((e & 1) << 2); }
 
 // int8 codes are kept in the cache in offset-binary form (stored byte = code XOR 0x80, i.e.
 // code + 128), which is the form the byte -> f16 conversion in the attention kernel consumes

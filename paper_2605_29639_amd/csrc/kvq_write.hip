@@ -536,6 +536,184 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
   }
 }
 
+// ---- int4, one scale per (token, kv head), head_dim 128 ------------------------------------
+// As int8 with 7 in place of 127 and two codes per byte; a code is stored as the nibble
+// code + 8.  The 32-bit word / nibble a logical element lives in is given by int4_k_word,
+// int4_v_word and int4_nibble.
+__device__ inline uint32_t int4_nib(float x, float s) {  // stored nibble of x / s, exact rounding
+  double r = rint((double)x / (double)s);
+  r = r > 7.0 ? 7.0 : r;
+  r = r < -7.0 ? -7.0 : r;
+  return (uint32_t)((int)r + 8);
+}
+
+// One run (consecutive tokens with consecutive slots inside one 16-token sub-block).  A lane
+// owns channels 2 lane and 2 lane + 1.  K: the four lanes of a quad hold the eight codes of one
+// word and combine them with two cross-lane ORs.  V: the lane owns its two channels' 16-token
+// rows (8 bytes each) and rewrites them whole, keeping the nibbles of the other tokens.
+__device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
+                                int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
+  constexpr int D = 128;
+  const int64_t blk = slot0 >> __builtin_ctz(bs);
+  const int off0 = (int)(slot0 - blk * bs);
+  const int so = off0 & 15;
+  uint8_t* tile = cache + (size_t)tile_offset(blk, kv, h, H, bs, D / 2);
+  float* srow = scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0;
+  const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * 2;
+  const size_t tstride = (size_t)H * D;
+  unsigned long long img[2] = {0, 0}, mask = 0;  // V rows of the lane's two channels
+  for (int i = 0; i < run; ++i) {
+    const uint32_t w = *(const uint32_t*)(src + i * tstride);
+    const uint32_t b0 = w & 0xFFFFu, b1 = w >> 16;
+    uint32_t amax = (b0 & 0x7FFFu) > (b1 & 0x7FFFu) ? (b0 & 0x7FFFu) : (b1 & 0x7FFFu);
+    amax = wave_max_u32(amax);
+    const float s = (amax == 0) ? 0.0f : (float)((double)bf16_bits_to_float(amax) / 7.0);
+    const uint32_t n0 = (amax == 0) ? 8u : int4_nib(bf16_bits_to_float(b0), s);
+    const uint32_t n1 = (amax == 0) ? 8u : int4_nib(bf16_bits_to_float(b1), s);
+    if (kv == 0) {
+      // channels 2 lane, 2 lane + 1 are elements 2 (lane % 4) and + 1 of their word
+      uint32_t word = (n0 << (4 * (lane & 3))) | (n1 << (4 * ((lane & 3) + 4)));
+      word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0xB1, 0xF, 0xF, false);
+      word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x4E, 0xF, 0xF, false);
+      if ((lane & 3) == 0) *(uint32_t*)(tile + int4_k_word(off0 + i, 2 * lane)) = word;
+    } else {
+      const int t = so + i;  // position in the sub-block: word t / 8, element t % 8
+      const int sh = 32 * (t >> 3) + 4 * int4_nibble(t & 7);
+      img[0] |= (unsigned long long)n0 << sh;
+      img[1] |= (unsigned long long)n1 << sh;
+      mask |= 15ull << sh;
+    }
+    if (lane == 0) srow[i] = s;
+  }
+  if (kv == 1) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      unsigned long long* row =
+          (unsigned long long*)(tile + int4_v_word(off0 - so, 2 * lane + e));
+      *row = run == 16 ? img[e] : ((*row & ~mask) | img[e]);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kWaves * 64) void write_int4_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (unit >= (int64_t)num_tokens * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int t0 = (int)((unit >> 1) / H);
+  const int64_t slot0 = slot_mapping[t0];
+  if (slot0 < 0) return;
+  const int so = (int)(slot0 & 15);
+  if (t0 > 0 && so > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
+  int run = 1;
+  while (run < 16 - so && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
+  int4_run(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+}
+
+// A whole sub-block with 16-byte loads, as for int8: a lane owns 8 channels (8 c .. 8 c + 7,
+// c = lane % 16) of 4 tokens.  K (tokens 4 i + g): the lane's eight codes of a token are one
+// whole word.  V (tokens 4 g + i): the lane's four tokens of a channel are the nibbles
+// 2a, 2a+1 (one byte) and 2a+4, 2a+5 (another byte) of the channel's word g / 2, a = g % 2.
+__device__ inline void int4_subblock(const uint16_t* __restrict__ src, size_t tstride,
+                                     uint8_t* __restrict__ tile, float* __restrict__ srow,
+                                     int kv, int off0, int lane) {
+  const int c = lane & 15, g = lane >> 4;
+  uint4 raw[4];
+  int tok[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    tok[i] = kv ? g * 4 + i : i * 4 + g;
+    raw[i] = *(const uint4*)(src + (size_t)tok[i] * tstride + 8 * c);
+  }
+  uint32_t vnib[8][4];  // V: [channel][token i]
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+    uint32_t amax = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
+      amax = amax > lo ? amax : lo;
+      amax = amax > hi ? amax : hi;
+    }
+    amax = row_max_u32<16>(amax);
+    const float a = bf16_bits_to_float(amax);
+    const float s = (amax == 0) ? 0.0f : __fdiv_rn(a, 7.0f);
+    const bool fast = s > 1e-30f;
+    const float inv = fast ? __builtin_amdgcn_rcpf(s) : 0.0f;
+    uint32_t kword = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
+                              : __uint_as_float(w[e >> 1] << 16);
+      const float q = x * inv;
+      const float r = __builtin_rintf(q);
+      uint32_t nib = (uint32_t)((int)r + 8);
+      if (__builtin_expect(!fast || fabsf(q - r) > 0.5f - 4e-5f, 0))
+        nib = (amax == 0) ? 8u : int4_nib(x, s);
+      if (kv == 0) kword |= nib << (4 * int4_nibble(e));
+      else vnib[e][i] = nib;
+    }
+    if (kv == 0) *(uint32_t*)(tile + int4_k_word(off0 + tok[i], 8 * c)) = kword;
+    if (c == 0) srow[tok[i]] = s;
+  }
+  if (kv == 1) {
+    const int a = g & 1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint8_t* word = tile + int4_v_word(off0 + 8 * (g >> 1), 8 * c + e);
+      word[a] = (uint8_t)(vnib[e][0] | (vnib[e][2] << 4));      // elements 4a, 4a+2
+      word[a + 2] = (uint8_t)(vnib[e][1] | (vnib[e][3] << 4));  // elements 4a+1, 4a+3
+    }
+  }
+}
+
+__global__ __launch_bounds__(kWaves * 64) void write_int4_bulk_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  constexpr int D = 128;
+  const int lane = threadIdx.x & 63;
+  const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int windows = (num_tokens + 15) >> 4;
+  if (unit >= (int64_t)windows * H * 2) return;
+  const int kv = (int)(unit & 1);
+  const int h = (int)((unit >> 1) % H);
+  const int w0 = (int)((unit >> 1) / H) * 16;
+  bool first = false;
+  {
+    const int t = w0 + lane;
+    if (lane < 16 && t < num_tokens) {
+      const int64_t slot = slot_mapping[t];
+      if (slot >= 0) first = !(t > 0 && (slot & 15) > 0 && slot_mapping[t - 1] == slot - 1);
+    }
+  }
+  uint32_t starts = (uint32_t)__ballot(first);
+  const size_t tstride = (size_t)H * D;
+  while (starts) {
+    const int t0 = w0 + __builtin_ctz(starts);
+    starts &= starts - 1;
+    const int64_t slot0 = slot_mapping[t0];
+    const int so = (int)(slot0 & 15);
+    const bool cont = lane < 16 - so && t0 + lane < num_tokens && slot_mapping[t0 + lane] == slot0 + lane;
+    const int run = __builtin_ctz(~(uint32_t)__ballot(cont));
+    if (run == 16) {
+      const int64_t blk = slot0 >> __builtin_ctz(bs);
+      const int off0 = (int)(slot0 - blk * bs);
+      int4_subblock((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
+                    cache + (size_t)tile_offset(blk, kv, h, H, bs, D / 2),
+                    scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0, kv, off0, lane);
+    } else {
+      int4_run(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+    }
+  }
+}
+
 // ---- unquantized cache: the rows are copied to their slots ---------------------------------
 // unit = (token, kv head, K|V); a lane moves D/64 adjacent channels.
 template <int D>
@@ -585,7 +763,14 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
   hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
                      num_tokens, c, scales, desc.num_kv_heads, desc.block_size,               \
                      (int32_t)(desc.mode == KVQ_FP8E4M3_TENSOR))
-  if (desc.mode == KVQ_BF16_PLAIN) {
+  if (desc.mode == KVQ_INT4_TOKEN_HEAD) {
+    if (bulk)
+      hipLaunchKernelGGL(write_int4_bulk_kernel, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+    else
+      hipLaunchKernelGGL(write_int4_kernel, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+  } else if (desc.mode == KVQ_BF16_PLAIN) {
     const unsigned g = (unsigned)(((int64_t)num_tokens * desc.num_kv_heads * 2 + kWaves - 1) / kWaves);
     if (desc.head_dim == 128)
       hipLaunchKernelGGL((write_plain_kernel<128>), dim3(g), block, 0, stream, kk, vv, slot_mapping,

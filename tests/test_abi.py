@@ -44,6 +44,9 @@ def test_sizes():
     assert L.kvq_scales_bytes(C.byref(d(mode=2))) == 0
     assert L.kvq_cache_bytes(C.byref(d(mode=3))) == 8 * 2 * 2 * 16 * 64       # static fp8 scales:
     assert L.kvq_scales_bytes(C.byref(d(mode=3))) == 8                        # one for K, one for V
+    assert L.kvq_cache_bytes(C.byref(d(mode=4, D=128))) == 8 * 2 * 2 * 16 * 64    # int4: two codes a byte
+    assert L.kvq_scales_bytes(C.byref(d(mode=4, D=128))) == 8 * 2 * 2 * 16 * 4
+    assert L.kvq_cache_bytes(C.byref(d(mode=4, D=64))) == 0                       # head_dim 128 only
     assert L.kvq_cache_bytes(C.byref(d(D=96))) == 0
     assert L.kvq_cache_bytes(None) == 0
 

@@ -34,11 +34,17 @@ def check(wl, chunks=(0,), tol=TOL):
     return errs
 
 
-MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR]
+MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4]
+
+
+def skip_unsupported(mode, D):
+    if mode == W.MODE_INT4 and D != 128:
+        pytest.skip("int4 takes head_dim 128 only")
 
 
 @pytest.mark.parametrize("mode", MODES)
 def test_tiny_config(mode):
+    skip_unsupported(mode, 64)
     check(W.tiny(mode), chunks=(0, 64))
 
 
@@ -64,6 +70,7 @@ CASES = [
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_shapes_and_splits(mode, case):
     name, lens, q_len, Hq, Hkv, D, bs = case
+    skip_unsupported(mode, D)
     lens = [max(l, q_len) for l in lens]
     wl = W.custom(name, mode, lens, q_len, Hq, Hkv, D, bs, seed=zlib.crc32(name.encode()) % 1000 + mode)
     check(wl, chunks=(0, 64, 256))
@@ -89,7 +96,8 @@ def test_stale_bytes_after_the_last_position_are_never_used(mode):
     """Unwritten slots hold NaN codes / NaN or huge scales; block-table entries past the last
     block are -1.  The output must not change and must stay finite."""
     import torch
-    wl = W.custom("stale", mode, [37, 100, 64, 3], 1, 4, 2, 64, 16, seed=8)
+    D = 128 if mode == W.MODE_INT4 else 64
+    wl = W.custom("stale", mode, [37, 100, 64, 3], 1, 4, 2, D, 16, seed=8)
     oc, osc = oracle_fill(wl)
     want = oracle_out(wl, oc, osc)
     live = np.zeros(oc.shape[:1] + oc.shape[3:4], dtype=bool)       # [blk, off]
@@ -102,7 +110,7 @@ def test_stale_bytes_after_the_last_position_are_never_used(mode):
             dirty_c[blk, :, :, off, :] = 0x7FC0 if (blk + off) % 2 else 0xFF80
         else:
             dirty_c[blk, :, :, off, :] = 0x80 if mode == W.MODE_INT8 else 0x7F
-        if mode == W.MODE_INT8:
+        if mode in (W.MODE_INT8, W.MODE_INT4):
             dirty_s[blk, :, :, off] = np.nan if (blk + off) % 2 else 3e38
     if mode == W.MODE_FP8:
         dead_blocks = ~live.any(axis=1)

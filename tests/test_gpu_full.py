@@ -45,7 +45,9 @@ def compare_on_sample(wl, chunks, seqs=None):
     del canon
     bad = np.argwhere(got_c != oc[blocks])
     assert bad.size == 0, "codes differ, first at (sampled block, kv, h, off, d) %s" % bad[0]
-    if wl.mode != W.MODE_BF16:
+    if wl.mode == W.MODE_FP8_TENSOR:
+        assert np.array_equal(scales.cpu().numpy(), osc)
+    elif wl.mode != W.MODE_BF16:
         got_s = scales[idx].cpu().numpy()
         assert np.array_equal(got_s.view(np.uint32), osc[blocks].view(np.uint32))
 
@@ -95,6 +97,14 @@ def test_unquantized_baseline_full_size():
     compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=4))
     wl = W.verify_prefix(mode=W.MODE_BF16)
     compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=0))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT4, W.MODE_FP8_TENSOR])
+def test_other_formats_full_size(mode):
+    """Configuration 2's shapes with int4 per token-head codes and with e4m3 codes under static
+    per-tensor scales."""
+    wl = W.llama8b(mode=mode)
+    compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=6))
 
 
 @pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])

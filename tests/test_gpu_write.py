@@ -10,7 +10,12 @@ from paper_2605_29639_amd import workloads as W
 from helpers import bits_to_bf16_tensor, gpu_desc, gpu_fill, oracle_fill
 
 
-ALL_MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR]
+ALL_MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4]
+
+
+def skip_unsupported(mode, D):
+    if mode == W.MODE_INT4 and D != 128:
+        pytest.skip("int4 takes head_dim 128 only")
 
 
 def fetch(cache, scales, desc):
@@ -34,6 +39,7 @@ def assert_pool_equal(wl, got, want):
 
 @pytest.mark.parametrize("mode", ALL_MODES)
 def test_tiny_config(mode):
+    skip_unsupported(mode, 64)
     wl = W.tiny(mode)
     cache, scales, desc = gpu_fill(wl)
     assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
@@ -53,12 +59,13 @@ SHAPES = [
 @pytest.mark.parametrize("shape", SHAPES)
 def test_ragged_shapes_bulk_write(mode, shape):
     lens, H, D, bs = shape
+    skip_unsupported(mode, D)
     wl = W.custom("ragged", mode, lens, 1, H * 2, H, D, bs, seed=1000 + D + bs + mode)
     cache, scales, desc = gpu_fill(wl)
     assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4])
 @pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1)])
 def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     """Thousands of tokens in one call (the prefill kernels): ragged sequences back to back, so
@@ -66,6 +73,7 @@ def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     skipped tokens; rows full of rounding ties, tiny and huge rows."""
     import torch
     from paper_2605_29639_amd import kvq
+    skip_unsupported(mode, D)
     lens = [700, 33, 1, 1234, 16, 515, 47]
     wl = W.custom("prefill", mode, lens, 1, H, H, D, bs, seed=31 + bs + D + mode)
     desc = gpu_desc(wl)
@@ -86,7 +94,7 @@ def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
         k, v = wl.kv_rows(b, lo, L)
         kf, vf = W.bf16_bits_to_f32(k), W.bf16_bits_to_f32(v)
         if b == 0:
-            qmax = 127.0 if mode == 0 else 448.0
+            qmax = {W.MODE_INT8: 127.0, W.MODE_INT4: 7.0}.get(mode, 448.0)
             vf[64:128] = np.round(vf[64:128] * 16) / 2   # half-integers ...
             vf[64:128, :, 0] = qmax                      # ... at scale exactly 1: ties
             kf[128:160] *= np.float32(2.0 ** -120)       # scales below the normal fp32 range
@@ -155,11 +163,12 @@ def test_chunked_prefill_then_appends(mode):
     assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_INT4])
 def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     import torch
     from paper_2605_29639_amd import kvq
-    wl = W.custom("edge", mode, [48], 1, 2, 2, 64, 16, seed=3)
+    D = 128 if mode == W.MODE_INT4 else 64
+    wl = W.custom("edge", mode, [48], 1, 2, 2, D, 16, seed=3)
     k, v = wl.kv_rows(0, 0, 48)
     k[3] = 0                     # all-zero K row (both heads)
     v[3, 0] = 0x8000             # all negative-zero V row for head 0
@@ -171,7 +180,7 @@ def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     slots[47] = -1               # block still receives one run of consecutive slots)
     desc = gpu_desc(wl)
     # stale pool on both sides: NaN codes and a garbage scale everywhere
-    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, 64)
+    oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, D)
     oc[:] = 0x7F
     osc[:] = 123.0
     cache = kvq.cache_from_canonical(torch.from_numpy(oc).cuda(), desc)
