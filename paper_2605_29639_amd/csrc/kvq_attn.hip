@@ -748,19 +748,17 @@ __global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
   if constexpr (CEIL) p.ws_acc[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
 
-// ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query token,
-// query head), each lane owning D/64 channels.  It recomputes where the pair lies in the flat
-// list and which wavefront ranges cover it; the (max, sum) pairs of up to 64 ranges are
-// fetched by 64 lanes at once, so the chain of dependent memory round trips stays short. ----
+// ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query head), which
+// takes the sequence's query tokens one after another, each lane owning D/64 channels.  It
+// recomputes where the pair lies in the flat list and which wavefront ranges cover it; the
+// (max, sum) pairs of up to 64 ranges are fetched by 64 lanes at once, so the chain of
+// dependent memory round trips stays short. ----
 template <int D>
 __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   constexpr int E = D / 64;
   typedef float floatE __attribute__((ext_vector_type(E)));
-  int id = blockIdx.x;
-  const int hq = id % p.num_q_heads;
-  id /= p.num_q_heads;
-  const int j = id % p.q_len;
-  const int b = id / p.q_len;
+  const int hq = blockIdx.x % p.num_q_heads;
+  const int b = blockIdx.x / p.num_q_heads;
   const int lane = threadIdx.x;
   int before = 0, total = 0;
   for (int i = lane; i < p.batch; i += 64) {
@@ -774,54 +772,56 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   const int flat = total * Hp;
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
-  const int r = j * p.group + (hq - h * p.group);
-  const int rg = r / rt, rl = r - rg * rt;
-  const int pr = h * p.num_row_groups + rg;
   const int ng = (p.seq_lens[b] + 63) >> 6;
-  const int start = before * Hp + pr * ng;
-  const int w_first = range_of(start, p.range_groups, flat, p.num_waves);
-  const int w_last = range_of(start + ng - 1, p.range_groups, flat, p.num_waves);
-  if (w_first == w_last) return;  // the streaming kernel already wrote the final rows
-  const size_t pair = (size_t)b * Hp + pr;
+  for (int j = 0; j < p.q_len; ++j) {
+    const int r = j * p.group + (hq - h * p.group);
+    const int rg = r / rt, rl = r - rg * rt;
+    const int pr = h * p.num_row_groups + rg;
+    const int start = before * Hp + pr * ng;
+    const int w_first = range_of(start, p.range_groups, flat, p.num_waves);
+    const int w_last = range_of(start + ng - 1, p.range_groups, flat, p.num_waves);
+    if (w_first == w_last) continue;  // the streaming kernel already wrote the final rows
+    const size_t pair = (size_t)b * Hp + pr;
 
-  // pass 1: the maximum over all partials
-  float M = -INFINITY;
-  for (int w0 = w_first; w0 <= w_last; w0 += 64) {
-    const int w = w0 + lane;
-    // wavefronts whose range is empty left no partial
-    const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
-                                         range_begin(w + 1, p.range_groups, flat, p.num_waves);
-    const float m = live ? p.ws_ml[(((size_t)w + pair) * rt + rl) * 2] : -INFINITY;
-    M = fmaxf(M, m);
-  }
+    // pass 1: the maximum over all partials
+    float M = -INFINITY;
+    for (int w0 = w_first; w0 <= w_last; w0 += 64) {
+      const int w = w0 + lane;
+      // wavefronts whose range is empty left no partial
+      const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
+                                           range_begin(w + 1, p.range_groups, flat, p.num_waves);
+      const float m = live ? p.ws_ml[(((size_t)w + pair) * rt + rl) * 2] : -INFINITY;
+      M = fmaxf(M, m);
+    }
 #pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) M = fmaxf(M, __shfl_xor(M, s, 64));
+    for (int s = 32; s >= 1; s >>= 1) M = fmaxf(M, __shfl_xor(M, s, 64));
 
-  // pass 2: weights, denominator and the weighted sum of the accumulators
-  floatE num = {};
-  float den = 0.0f;
-  for (int w0 = w_first; w0 <= w_last; w0 += 64) {
-    const int w = w0 + lane;
-    const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
-                                         range_begin(w + 1, p.range_groups, flat, p.num_waves);
-    float wgt = 0.0f;
-    if (live) {
-      const size_t row = ((size_t)w + pair) * rt + rl;
-      wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
-      den += wgt * p.ws_ml[row * 2 + 1];
+    // pass 2: weights, denominator and the weighted sum of the accumulators
+    floatE num = {};
+    float den = 0.0f;
+    for (int w0 = w_first; w0 <= w_last; w0 += 64) {
+      const int w = w0 + lane;
+      const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
+                                           range_begin(w + 1, p.range_groups, flat, p.num_waves);
+      float wgt = 0.0f;
+      if (live) {
+        const size_t row = ((size_t)w + pair) * rt + rl;
+        wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
+        den += wgt * p.ws_ml[row * 2 + 1];
+      }
+      const int n = min(64, w_last - w0 + 1);
+      for (int k = 0; k < n; ++k) {
+        const float wk = __shfl(wgt, k, 64);
+        if (wk == 0.0f) continue;  // empty range (or a partial that carries no weight)
+        const size_t row = ((size_t)(w0 + k) + pair) * rt + rl;
+        const floatE a = *(const floatE*)(p.ws_acc + row * D + lane * E);
+        num += wk * a;
+      }
     }
-    const int n = min(64, w_last - w0 + 1);
-    for (int k = 0; k < n; ++k) {
-      const float wk = __shfl(wgt, k, 64);
-      if (wk == 0.0f) continue;  // empty range (or a partial that carries no weight)
-      const size_t row = ((size_t)(w0 + k) + pair) * rt + rl;
-      const floatE a = *(const floatE*)(p.ws_acc + row * D + lane * E);
-      num += wk * a;
-    }
+    den = wave_sum_f(den);
+    float* o = p.out + (((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + lane * E;
+    *(floatE*)o = num * (1.0f / den);
   }
-  den = wave_sum_f(den);
-  float* o = p.out + (((size_t)b * p.q_len + j) * p.num_q_heads + hq) * D + lane * E;
-  *(floatE*)o = num * (1.0f / den);
 }
 
 // measurement hooks: events recorded around the streaming kernel (kvq_profile_split_events)
@@ -880,7 +880,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);
   if (e != hipSuccess || g_read_ceiling || g_skip_reduce) return e;
-  const unsigned rgrid = (unsigned)((size_t)a.batch * a.q_len * a.num_q_heads);
+  const unsigned rgrid = (unsigned)((size_t)a.batch * a.num_q_heads);
   if (a.head_dim == 128)
     hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(64), 0, stream, a);
   else
