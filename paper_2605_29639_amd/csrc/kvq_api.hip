@@ -101,7 +101,9 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
                    const kvq_cache_desc_t* desc, void* stream) {
   int err;
   if (!desc_ok(desc, &err)) return err;
-  if (num_tokens < 0) return KVQ_E_BAD_SHAPE;
+  // one wavefront per (token, kv head, K|V) at most, four to a workgroup: the grid must fit
+  if (num_tokens < 0 || (int64_t)num_tokens * desc->num_kv_heads * 2 / 4 > 0x7FFFFFFF)
+    return KVQ_E_BAD_SHAPE;
   if (num_tokens == 0) return KVQ_OK;
   if (!k || !v || !slot_mapping || !cache) return KVQ_E_NULLPTR;
   if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;

@@ -71,6 +71,8 @@ def test_write_argument_checks():
     assert L.kv_quant_write(FAKE, FAKE, FAKE, 4, FAKE, FAKE, None, None) == kvq.E_NULLPTR
     assert L.kv_quant_write(FAKE, FAKE, FAKE, -1, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
     assert L.kv_quant_write(None, None, None, 0, None, None, C.byref(ok), None) == kvq.OK
+    huge = d(H=4096)                                       # 2^31-1 tokens x 4096 heads: no such grid
+    assert L.kv_quant_write(FAKE, FAKE, FAKE, 2 ** 31 - 1, FAKE, FAKE, C.byref(huge), None) == kvq.E_BAD_SHAPE
     odd = C.c_void_p(0x1008)                               # k, v and cache: 16-byte aligned
     assert L.kv_quant_write(odd, FAKE, FAKE, 4, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
     assert L.kv_quant_write(FAKE, odd, FAKE, 4, FAKE, FAKE, C.byref(ok), None) == kvq.E_BAD_SHAPE
