@@ -256,3 +256,53 @@ def test_empty_write_is_a_no_op():
     kvq.kv_quant_write(k, k, torch.empty(0, dtype=torch.int64, device="cuda"), cache, scales, desc)
     torch.cuda.synchronize()
     assert not cache.any() and not scales.any()
+
+
+def random_segments(rng, num_tokens, nblk, bs):
+    """slot_mapping of about num_tokens tokens: runs of consecutive slots of random length that
+    start anywhere inside a block, each block touched by at most one run, the runs in random
+    token order with skipped tokens (-1) sprinkled between them."""
+    segments, blk, total = [], 0, 0
+    while total < num_tokens and blk < nblk - 8:
+        off = int(rng.integers(0, bs))
+        length = int(rng.integers(1, 3 * bs + 1))
+        if rng.random() < 0.3:
+            off, length = 0, bs * int(rng.integers(1, 5))      # whole blocks, as a prompt writes
+        first = blk * bs + off
+        segments.append(np.arange(first, first + length, dtype=np.int64))
+        blk += (off + length + bs - 1) // bs + int(rng.integers(0, 3))
+        total += length
+    order = rng.permutation(len(segments))
+    parts = []
+    for i in order:
+        parts.append(segments[i])
+        if rng.random() < 0.25:
+            parts.append(np.full(int(rng.integers(1, 4)), -1, dtype=np.int64))
+    return np.concatenate(parts)
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+@pytest.mark.parametrize("num_tokens", [60, 1700])       # per-run kernels, prefill kernels
+@pytest.mark.parametrize("bs", [16, 64])
+def test_random_slot_patterns(mode, num_tokens, bs):
+    import torch
+    from paper_2605_29639_amd import kvq
+    H, D = 2, 128
+    rng = np.random.default_rng(900 + 10 * mode + num_tokens + bs)
+    nblk = num_tokens // bs * 3 + 40
+    slots = random_segments(rng, num_tokens, nblk, bs)
+    T = len(slots)
+    x = (rng.standard_normal((2, T, H, D), dtype=np.float32) *
+         rng.choice([0.01, 1.0, 30.0], size=(2, T, H, 1)).astype(np.float32))
+    k, v = W.to_bf16_bits(x[0]), W.to_bf16_bits(x[1])
+    desc = kvq.make_desc(mode, nblk, bs, H, D)
+    cache, scales = kvq.alloc_cache(desc)
+    oc, osc = oracle.alloc_cache(mode, nblk, bs, H, D)
+    if mode == W.MODE_FP8_TENSOR:
+        osc[:] = (0.07, 0.11)
+        scales.copy_(torch.from_numpy(osc))
+    oracle.kv_quant_write(k, v, slots, oc, osc, mode)
+    kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v), torch.from_numpy(slots).cuda(),
+                       cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(None, fetch(cache, scales, desc), (oc, osc))
