@@ -170,3 +170,24 @@ def test_empty_batch():
                           torch.empty((0, 4), dtype=torch.int32, device="cuda"),
                           torch.empty(0, dtype=torch.int32, device="cuda"), 1, 0, 0.125, out, ws)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(seed):
+    """Shapes nobody picked by hand: batch, lengths, group size, query tokens, block size, head
+    size, cache mode and split granule all drawn from a seeded generator."""
+    rng = np.random.default_rng(7000 + seed)
+    D = int(rng.choice([64, 128]))
+    modes = [m for m in MODES if not (m == W.MODE_INT4 and D != 128)]
+    mode = int(rng.choice(modes))
+    bs = int(rng.choice([16, 32, 64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 8, 16]))
+    q_len = int(rng.choice([1, 1, 2, 3, 4, 8]))
+    B = int(rng.integers(1, 10))
+    lens = [int(rng.choice([rng.integers(q_len, 70), rng.integers(q_len, 1500),
+                            64 * rng.integers(1, 9)])) for _ in range(B)]
+    lens = [max(l, q_len) for l in lens]
+    chunk = int(rng.choice([0, 64, 128, 512]))
+    wl = W.custom("random%d" % seed, mode, lens, q_len, G * Hkv, Hkv, D, bs, seed=seed)
+    check(wl, chunks=(chunk,))
