@@ -63,6 +63,9 @@ CASES = [
     ("qlen2_g16", [100, 400], 2, 32, 2, 128, 64),
     ("qlen3_g16_rowgroups", [100, 130], 3, 32, 2, 64, 16),
     ("qlen16_g4", [100, 16, 77], 16, 4, 1, 128, 16),
+    ("bs256", [700, 300, 256], 1, 8, 2, 128, 256),
+    ("g64_two_row_groups", [150, 90], 1, 64, 1, 64, 16),
+    ("qlen16_g8_four_row_groups", [200, 40], 16, 8, 1, 128, 32),
 ]
 
 

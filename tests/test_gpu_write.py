@@ -52,6 +52,7 @@ SHAPES = [
     ([300, 129, 64], 2, 128, 64),
     ([257, 5], 1, 64, 32),
     ([513], 4, 128, 128),
+    ([700, 300], 2, 128, 256),
 ]
 
 
