@@ -326,6 +326,37 @@ def main():
         del pc, ps
     result["block_moves"] = moves
 
+    # A chunk of a prompt through the same entry point: 512 query tokens per sequence attending
+    # causally over a 4096-token prefix already in the cache and over themselves, 8 sequences,
+    # this workload's heads and cache mode.  Useful flops = 4 * head_dim per (query row, visible
+    # position); the bound here is the matrix cores, not HBM.
+    from paper_2605_29639_amd import workloads as Wm
+    cq, cL, cB = 512, 4608, 8
+    wlc = Wm.custom("chunk_prefill", wl.mode, [cL] * cB, cq, Hq, wl.num_kv_heads, D, wl.block_size,
+                    seed=5)
+    cc, cs, cdesc = gpu_fill(wlc)
+    qc = bits_to_bf16_tensor(wlc.q)
+    btc = torch.from_numpy(wlc.block_tables).cuda()
+    slc = torch.from_numpy(wlc.seq_lens).cuda()
+    outc = torch.empty((cB * cq, Hq, D), dtype=torch.float32, device="cuda")
+    wsc = kvq.alloc_workspace(cdesc, cB, cq, Hq, cL, 0)
+    for _ in range(3):
+        kvq.paged_decode_attn(qc, cc, cs, cdesc, btc, slc, cq, cL, wlc.sm_scale, outc, wsc, stream=stream)
+    te0.record()
+    for _ in range(10):
+        kvq.paged_decode_attn(qc, cc, cs, cdesc, btc, slc, cq, cL, wlc.sm_scale, outc, wsc, stream=stream)
+    te1.record()
+    torch.cuda.synchronize()
+    chunk_s = te0.elapsed_time(te1) / 10 * 1e-3
+    visible = sum(cL - cq + j + 1 for j in range(cq))
+    chunk_flops = 4.0 * D * Hq * cB * visible
+    mfma_peak = 2500.0  # TFLOP/s, dense f16 / bf16
+    result["chunk_prefill"] = {"sequences": cB, "chunk_tokens": cq, "context": cL, "us": chunk_s * 1e6,
+                               "roofline": {"bound": "mfma", "achieved": chunk_flops / chunk_s / 1e12,
+                                            "peak": mfma_peak, "unit": "TFLOP/s",
+                                            "frac": chunk_flops / chunk_s / 1e12 / mfma_peak}}
+    del cc, cs, qc, outc, wsc
+
     step(1)  # (the second layer cache: the prefill measurement above rewrote part of the first)
     torch.cuda.synchronize()
     out_main = out.cpu().numpy()  # the measured path's output, for the parity figure below

@@ -33,6 +33,10 @@
 extern "C" {
 #endif
 
+/* Most query tokens per sequence in one paged_decode_attn call (1 in a decode step, a handful
+ * when verifying speculated tokens, hundreds for a chunk of a prompt). */
+#define KVQ_MAX_Q_LEN 1024
+
 typedef enum {
   KVQ_INT8_TOKEN_HEAD = 0,    /* int8 codes in [-127,127], one fp32 scale per (token, kv head) */
   KVQ_FP8E4M3_BLOCK_HEAD = 1, /* OCP E4M3 (finite-only, max 448) codes, one fp32 scale per
@@ -160,7 +164,11 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
  * unnormalised partial (running max, sum, accumulator) in the workspace and a second kernel
  * merges a pair's partials by the log-sum-exp rule.  Results are deterministic run to run
  * (no atomics).
- * Requires 1 <= q_len <= 16 and num_q_heads % num_kv_heads == 0. */
+ * q_len is 1 in a decode step, a handful when speculated tokens are verified, and may be
+ * hundreds for a chunk of a prompt attending over its quantized prefix and itself: the query
+ * rows of a kv head are taken 32 at a time, each such group streaming the keys and values again
+ * (from the caches, mostly), so that use is bound by arithmetic, not by HBM.
+ * Requires 1 <= q_len <= KVQ_MAX_Q_LEN and num_q_heads % num_kv_heads == 0. */
 int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       const kvq_cache_desc_t* desc, const int32_t* block_tables,
                       int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,

@@ -37,7 +37,7 @@ int ilog2(int x) {
 bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t num_q_heads,
                int32_t max_seq_len, int32_t chunk_tokens, kvq::AttnPlan* plan, int* err) {
   if (!desc_ok(d, err)) return false;
-  if (batch < 0 || q_len < 1 || q_len > 16 || num_q_heads <= 0 ||
+  if (batch < 0 || q_len < 1 || q_len > KVQ_MAX_Q_LEN || num_q_heads <= 0 ||
       num_q_heads % d->num_kv_heads != 0 || max_seq_len < 0 || chunk_tokens < 0 ||
       chunk_tokens % 64 != 0) {
     *err = KVQ_E_BAD_SHAPE;

@@ -97,7 +97,7 @@ def test_attn_argument_checks():
     assert attn(L, d(mode=99)) == kvq.E_BAD_MODE
     assert attn(L, ok, Hq=3) == kvq.E_BAD_SHAPE            # 3 % 2 != 0
     assert attn(L, ok, q_len=0) == kvq.E_BAD_SHAPE
-    assert attn(L, ok, q_len=17) == kvq.E_BAD_SHAPE
+    assert attn(L, ok, q_len=1025) == kvq.E_BAD_SHAPE        # above KVQ_MAX_Q_LEN
     assert attn(L, ok, batch=-1) == kvq.E_BAD_SHAPE
     assert attn(L, ok, chunk=100) == kvq.E_BAD_SHAPE       # not a multiple of 64
     assert attn(L, ok, max_blocks=6) == kvq.E_BAD_SHAPE    # 6 * 16 < 100

@@ -66,6 +66,10 @@ CASES = [
     ("bs256", [700, 300, 256], 1, 8, 2, 128, 256),
     ("g64_two_row_groups", [150, 90], 1, 64, 1, 64, 16),
     ("qlen16_g8_four_row_groups", [200, 40], 16, 8, 1, 128, 32),
+    # a chunk of a prompt attending over the quantized prefix and itself (causal)
+    ("chunk64", [200, 70], 64, 8, 2, 128, 16),
+    ("chunk200_bs64", [700], 200, 4, 1, 64, 64),
+    ("chunk256", [300, 1029], 256, 16, 2, 128, 16),
 ]
 
 
