@@ -226,6 +226,11 @@ void kvq_profile_read_ceiling(int on);
  * is a run of back-to-back streaming kernels that two events can bracket.  Off initially. */
 void kvq_profile_skip_reduce(int on);
 
+/* Measurement and test hook: 0 makes paged_decode_attn use its streaming kernels also for 128
+ * and more query rows per kv head, where it otherwise takes the kernel that shares the
+ * dequantization among 128 rows (int8 and both e4m3 modes).  On initially.  Process-global. */
+void kvq_profile_prefill_kernel(int on);
+
 /* Measurement hook, not part of the path: while `buf` (device, 8 x uint64 per launched
  * wavefront, i.e. 8 * 8 * (number of wavefronts) bytes) is registered, every wavefront of the
  * streaming kernel stores in buf[8*w + k]: the shader clock at entry (k = 0), after its first

@@ -243,6 +243,7 @@ void kvq_profile_split_events(void* before, void* after) {
 void kvq_profile_read_ceiling(int on) { kvq::set_read_ceiling(on != 0); }
 
 void kvq_profile_skip_reduce(int on) { kvq::set_skip_reduce(on != 0); }
+void kvq_profile_prefill_kernel(int on) { kvq::set_prefill_kernel(on != 0); }
 
 void kvq_profile_wave_clock(void* buf) { kvq::set_wave_clock((unsigned long long*)buf); }
 

@@ -1,0 +1,96 @@
+// Device helpers shared by the attention kernels (kvq_attn.hip, kvq_prefill.hip): vector
+// types, stored codes -> f16, the cross-lane pieces of the softmax.
+#pragma once
+
+#include <utility>
+
+#include "kvq_internal.h"
+
+namespace kvq {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef short short2v __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr float kPOffset = 10.0f;   // probabilities are scaled by 2^10 (cancels in acc / l)
+constexpr float kMinVScale = 7.888609052210118e-31f;  // 2^-100
+
+template <class F, int... Is>
+__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ inline void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// value of lane I of the caller's 16-lane row
+template <int I>
+__device__ inline float row_bcast(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + I, 0xF, 0xF, true));
+}
+
+__device__ inline float xor16_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+__device__ inline float xor16_sum(float v) {
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
+}
+
+// Four stored code bytes (one dword) -> four f16, in byte order.
+template <int MODE>
+__device__ inline void cvt4(uint32_t x, half2v& lo, half2v& hi) {
+  if constexpr (MODE == KVQ_INT8_TOKEN_HEAD) {
+    // stored byte u = code + 128; 0x6400 | u is the f16 1024 + u, so subtracting 1152 gives code
+    const uint32_t a = __builtin_amdgcn_perm(0x64646464u, x, 0x04010400u);
+    const uint32_t b = __builtin_amdgcn_perm(0x64646464u, x, 0x04030402u);
+    const half2v bias = {(_Float16)1152.0f, (_Float16)1152.0f};
+    lo = __builtin_bit_cast(half2v, a) - bias;
+    hi = __builtin_bit_cast(half2v, b) - bias;
+  } else {
+    // gfx950's packed e4m3 -> f16 conversion (exact); NaN codes must not reach it as V data
+    lo = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(x, 1.0f, false);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(x, 1.0f, true);
+  }
+}
+
+// Eight stored int4 nibbles (code + 8) of one word -> eight f16 codes; element 2i comes from
+// nibble i, element 2i + 1 from nibble i + 4.  An AND-OR drops two nibbles, 16 bits apart,
+// into the mantissas of a pair of f16 1024.0: nibbles at bits 0-3 give 1024 + n, nibbles at
+// bits 4-7 give 1024 + 16 n; one packed add or fused multiply-add turns either into n - 8.
+__device__ inline half8 cvt_int4(uint32_t x) {
+  const half2v k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+  const half2v k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+  const half2v k72 = {(_Float16)72.0f, (_Float16)72.0f};
+  const uint32_t y = x >> 8;
+  const half2v a = __builtin_bit_cast(half2v, (x & 0x000F000Fu) | 0x64006400u) - k1032;
+  const half2v b = __builtin_bit_cast(half2v, (x & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+  const half2v c = __builtin_bit_cast(half2v, (y & 0x000F000Fu) | 0x64006400u) - k1032;
+  const half2v d = __builtin_bit_cast(half2v, (y & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+  half8 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+  return r;
+}
+
+template <int MODE>
+__device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
+  half2v a, b, c, d;
+  cvt4<MODE>(x0, a, b);
+  cvt4<MODE>(x1, c, d);
+  half8 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+  return r;
+}
+
+}  // namespace
+}  // namespace kvq

@@ -95,6 +95,10 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
                         int32_t num_tokens, void* cache, float* scales,
                         const kvq_cache_desc_t& desc, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
+// the kernel for 128 and more query rows per kv head (kvq_prefill.hip)
+bool prefill_applies(const AttnArgs& a);
+hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream);
+void set_prefill_kernel(bool on);
 void set_profile_events(hipEvent_t before, hipEvent_t after);
 void set_read_ceiling(bool on);
 void set_skip_reduce(bool on);

@@ -1,0 +1,351 @@
+// paged_decode_attn for many query rows per kv head (a chunk of a prompt attending over its
+// quantized prefix and itself, Section 2's prefill phase fed from the Section 7.2.2 cache).
+//
+// With 128 and more query rows per kv head the work is arithmetic, not memory traffic, and what
+// has to be shared is the dequantization: the streaming kernel converts a group's codes once
+// per 32 rows, this kernel once per 128.  A workgroup of four wavefronts owns 128 query rows of
+// one (sequence, kv head) and walks the context from position 0 to the last position any of its
+// rows may see (no split over the context, so no partials and no merge).  Per 64-token group
+// each wavefront loads a quarter of the K and V codes, converts them to f16 and puts them in
+// LDS in the order the matrix instruction wants its A operand (one 16-byte read per lane and
+// instruction, no bank conflicts); after a barrier every wavefront runs QK^T, the online
+// softmax and P.V for its own 32 rows against the shared operands.  LDS holds two groups, so
+// one barrier per group suffices: while a group is consumed, the next one's codes are in
+// flight and are converted into the other half.
+//
+// The arithmetic (logits in base 2 with the K scale applied after the contraction, V scale
+// folded into the probability, f16 probabilities scaled by 2^10, masks) is the streaming
+// kernel's.
+#include "kvq_attn_common.h"
+
+namespace kvq {
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kRowsPerWorkgroup = kWavesPerGroup * 32;
+
+template <int MODE, int D>
+__global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(const AttnArgs p) {
+  constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
+  constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD;
+  constexpr int NT = 2;
+  constexpr int DT = D / 16;       // 16-channel tiles of V / of the output
+  constexpr int KJ = D / 64;       // 16-byte K pieces per lane and quad
+  constexpr int KS = D / 32;       // matrix-instruction steps over the channels
+  constexpr int VT = DT / kWavesPerGroup;  // V tiles a wavefront converts
+  __shared__ half8 k_ops[2][4][KS][64];    // [half][quad of the sub-block][step][lane]
+  __shared__ half8 v_ops[2][DT][2][64];    // [half][channel tile][tokens 0-7 | 8-15][lane]
+
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int m16 = lane & 15, g4 = lane >> 4;
+  const int H = p.num_kv_heads, G = p.group, bs = p.block_size, bs_shift = p.bs_shift;
+  const int row_blocks = (p.rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
+  int id = blockIdx.x;
+  const int rb = id % row_blocks;
+  id /= row_blocks;
+  const int h = id % H;
+  const int b = id / H;
+  const int L = p.seq_lens[b];
+
+  // this wavefront's rows, and how far the workgroup has to walk
+  const int r0 = rb * kRowsPerWorkgroup + wv * 32;
+  const bool wave_live = r0 < p.rows;
+  const int r_last = min(p.rows, (rb + 1) * kRowsPerWorkgroup) - 1;
+  const int n_max = L - p.q_len + r_last / G + 1;
+  const int ng = (n_max + 63) >> 6;
+  const int n_min = wave_live ? L - p.q_len + r0 / G + 1 : L;  // shortest causal length here
+
+  const uint8_t* __restrict__ cache = p.cache;
+  const float* __restrict__ scales = p.scales;
+  const int32_t* __restrict__ table = p.block_tables + (size_t)b * p.max_blocks_per_seq;
+  const uint32_t tile_bytes = (uint32_t)bs * D;
+  const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;
+  const int sbk = m16 >> 2;  // sub-block this lane reads K from
+  const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3) + (uint32_t)wv * (4 * D);  // quad wv
+  const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16 + 256u * (wv * VT);
+  const uint32_t s_block_stride = TOKEN_SCALE ? 2u * H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : 2u * H);
+  const uint32_t s_kv = TOKEN_SCALE ? (uint32_t)H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 1u : (uint32_t)H);
+  const int last_sb = ((L - 1) >> 4) << 4;
+
+  // ---- q as the B operand of QK^T, causal lengths, running state ----
+  half8 qb[NT][KS];
+  int nrow[NT];
+  floatx4 acc[NT][DT];
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int r = r0 + nt * 16 + m16;
+    const bool live = r < p.rows;
+    const int j = live ? r / G : 0;
+    const int gi = live ? r - j * G : 0;
+    nrow[nt] = live ? L - p.q_len + j + 1 : L;
+    const uint16_t* qrow =
+        p.q + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int d0 = 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+      const uintx4 raw = *(const uintx4*)(qrow + d0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
+        const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
+        qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
+        qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+      }
+    }
+    m_run[nt] = -INFINITY;
+    l_run[nt] = 0.0f;
+#pragma unroll
+    for (int tt = 0; tt < DT; ++tt) acc[nt][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // ---- producer side: this wavefront's quarter of a group's codes ----
+  struct Entries {
+    int k, v;
+  };
+  auto fetch_entries = [&](int g, Entries& e) {  // g is clamped by the caller
+    const int pos0 = g << 6;
+    e.k = table[min(pos0 + 16 * sbk, last_sb) >> bs_shift];
+    e.v = table[min(pos0 + 16 * g4, last_sb) >> bs_shift];
+  };
+  uintx4 rk[KJ], rv[VT];
+  float sk_next, sv_next;
+  auto issue_loads = [&](int g, const Entries& e) {
+    const int pos0 = g << 6;
+    const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
+    const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
+    const uint8_t* kbase = cache + (size_t)e.k * block_stride + (h * tile_bytes + off_k * D + k_lane);
+    const uint8_t* vbase = cache + (size_t)e.v * block_stride + (h * tile_bytes + off_v * D + v_lane);
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) rk[j] = *(const uintx4*)(kbase + 256 * j);
+#pragma unroll
+    for (int t = 0; t < VT; ++t) rv[t] = *(const uintx4*)(vbase + 256 * t);
+    const uint32_t s_lane = TOKEN_SCALE ? h * bs + m16 + off_v : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : (uint32_t)h);
+    const float* sp = scales + (size_t)e.v * s_block_stride + s_lane;
+    sk_next = sp[0];
+    sv_next = sp[s_kv];
+  };
+  auto publish = [&](int g, int half) {  // convert the loaded codes and put them in LDS
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+      k_ops[half][wv][2 * j][lane] = cvt8<MODE>(rk[j][0], rk[j][1]);
+      k_ops[half][wv][2 * j + 1][lane] = cvt8<MODE>(rk[j][2], rk[j][3]);
+    }
+    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
+    if (FP8 && (g << 6) + 64 > L) {  // V bytes of missing tokens: an e4m3 NaN times 0 is NaN
+      const int live = L - ((g << 6) + 16 * g4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int n = min(max(live - 4 * e, 0), 4);
+        keep[e] = n == 4 ? ~0u : (1u << (8 * n)) - 1u;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < VT; ++t) {
+      uintx4 raw = rv[t];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) raw[e] &= keep[e];
+      v_ops[half][wv * VT + t][0][lane] = cvt8<MODE>(raw[0], raw[1]);
+      v_ops[half][wv * VT + t][1][lane] = cvt8<MODE>(raw[2], raw[3]);
+    }
+  };
+
+  // ---- consumer side ----
+  floatx4 S[NT][4];
+  half8 pb[NT][2];
+  auto qk = [&](int half) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) S[nt][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // step by step over the channels: eight independent instructions (4 quads x 2 row tiles)
+    // per step, the next step's four operands read from LDS while they run.  The scheduling
+    // barriers keep that order; left alone, the compiler reads two operands, waits, issues
+    // four instructions and so exposes the LDS latency eight times per group.
+    half8 a[2][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a[0][u] = k_ops[half][u][0][lane];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (s + 1 < KS) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[(s + 1) & 1][u] = k_ops[half][u][s + 1][lane];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s & 1][u], qb[nt][s], S[nt][u], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto softmax_impl = [&](auto TAILC, int g, float sk, float sv) {
+#pragma clang fp contract(off)
+    constexpr bool TAIL = decltype(TAILC)::value;
+    const int pos0 = g << 6;
+    float skp = sk * p.scale_log2;
+    float lsv = __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
+    float rsv = __builtin_amdgcn_exp2f(-lsv);
+    if (TOKEN_SCALE && TAIL && pos0 + 16 * g4 + m16 >= L) {
+      skp = 0.0f;  // a slot that was never written: its scales are not data
+      lsv = 0.0f;
+      rsv = 0.0f;
+    }
+    float mx[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
+    static_for<16>([&](auto I) {
+      constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float ze;
+        if constexpr (TOKEN_SCALE) {
+          ze = S[nt][u][i] * row_bcast<tix>(skp);
+          ze = ze + row_bcast<tix>(lsv);
+        } else {
+          ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
+        }
+        if constexpr (TAIL) ze = (pos0 + 16 * g4 + tix < nrow[nt]) ? ze : -INFINITY;
+        S[nt][u][i] = ze;
+        mx[nt] = fmaxf(mx[nt], ze);
+      }
+    });
+    bool rescale = false;
+    float alpha[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const float m_new = fmaxf(m_run[nt], xor16_max(mx[nt]));
+      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+      alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
+      rescale |= (alpha[nt] != 1.0f);
+      m_run[nt] = m_new;
+      const float msub = m_safe - kPOffset;
+      float lsum = 0.0f;
+      static_for<16>([&](auto I) {
+        constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+        const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
+        if constexpr (TOKEN_SCALE) {
+          const float t = pr * row_bcast<tix>(rsv);
+          lsum = lsum + t;
+        } else {
+          lsum = lsum + pr;
+        }
+        pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+      });
+      if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
+      l_run[nt] = l_run[nt] * alpha[nt] + lsum;
+    }
+    if (__any(rescale)) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
+    }
+  };
+  auto pv = [&](int half) {
+    // two channel tiles at a time: their four operands are read while the previous pair's
+    // eight instructions run; the instructions alternate between four accumulators
+    half8 a[2][2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) a[0][x][hf] = v_ops[half][x][hf][lane];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t2 = 0; t2 < DT / 2; ++t2) {
+      if (t2 + 1 < DT / 2) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf)
+            a[(t2 + 1) & 1][x][hf] = v_ops[half][2 * (t2 + 1) + x][hf][lane];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[nt][2 * t2 + x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                a[t2 & 1][x][hf], pb[nt][hf], acc[nt][2 * t2 + x], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // ---- the walk: group g is consumed from half g % 2 while group g + 1 is converted into the
+  // other half and group g + 2 is requested (indices past the end repeat the last group) ----
+  Entries e_next, e_after;
+  {
+    Entries e0;
+    fetch_entries(0, e0);
+    fetch_entries(min(1, ng - 1), e_next);
+    issue_loads(0, e0);
+  }
+  float sk = sk_next, sv = sv_next;
+  publish(0, 0);
+  issue_loads(min(1, ng - 1), e_next);
+  fetch_entries(min(2, ng - 1), e_after);
+  __syncthreads();
+  for (int g = 0; g < ng; ++g) {
+    const int half = g & 1;
+    if (wave_live) {
+      qk(half);
+      if ((g << 6) + 64 > n_min) softmax_impl(std::true_type{}, g, sk, sv);
+      else softmax_impl(std::false_type{}, g, sk, sv);
+      pv(half);
+    }
+    // group g + 1 (requested one iteration ago) into the other half; request group g + 2
+    sk = sk_next;
+    sv = sv_next;
+    publish(min(g + 1, ng - 1), half ^ 1);
+    issue_loads(min(g + 2, ng - 1), e_after);
+    fetch_entries(min(g + 3, ng - 1), e_after);
+    __syncthreads();
+  }
+
+  // ---- normalised rows ----
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const float l = xor16_sum(l_run[nt]);
+    const int r = r0 + nt * 16 + m16;
+    if (r >= p.rows) continue;
+    const int j = r / G, gi = r - j * G;
+    float* orow = p.out + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int tt = 0; tt < DT; ++tt) *(floatx4*)(orow + 16 * tt + 4 * g4) = acc[nt][tt] * inv;
+  }
+}
+
+}  // namespace
+
+bool prefill_applies(const AttnArgs& a) {
+  return a.rows >= kRowsPerWorkgroup &&
+         (a.mode == KVQ_INT8_TOKEN_HEAD || a.mode == KVQ_FP8E4M3_BLOCK_HEAD ||
+          a.mode == KVQ_FP8E4M3_TENSOR);
+}
+
+hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
+  const int row_blocks = (a.rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
+  const dim3 grid((unsigned)((size_t)a.batch * a.num_kv_heads * row_blocks));
+  const dim3 block(64 * kWavesPerGroup);
+#define KVQ_LAUNCH_PREFILL(MODE)                                                              \
+  if (a.head_dim == 128)                                                                      \
+    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 128>), grid, block, 0, stream, a);          \
+  else                                                                                        \
+    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 64>), grid, block, 0, stream, a)
+  if (a.mode == KVQ_INT8_TOKEN_HEAD) {
+    KVQ_LAUNCH_PREFILL(KVQ_INT8_TOKEN_HEAD);
+  } else if (a.mode == KVQ_FP8E4M3_BLOCK_HEAD) {
+    KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_BLOCK_HEAD);
+  } else {
+    KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_TENSOR);
+  }
+#undef KVQ_LAUNCH_PREFILL
+  return hipGetLastError();
+}
+
+}  // namespace kvq

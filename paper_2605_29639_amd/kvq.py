@@ -22,6 +22,7 @@ EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
            "kvq_blocks_export", "kvq_blocks_import",
            "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
+           "kvq_profile_prefill_kernel",
            "kvq_profile_wave_clock",
            "kvq_strerror")
 
@@ -86,6 +87,8 @@ def lib():
         L.kvq_profile_split_events.argtypes = [P, P]
         L.kvq_profile_skip_reduce.restype = None
         L.kvq_profile_skip_reduce.argtypes = [C.c_int]
+        L.kvq_profile_prefill_kernel.restype = None
+        L.kvq_profile_prefill_kernel.argtypes = [C.c_int]
         L.kvq_profile_wave_clock.restype = None
         L.kvq_profile_wave_clock.argtypes = [P]
         L.kvq_profile_read_ceiling.restype = None

@@ -70,6 +70,9 @@ CASES = [
     ("chunk64", [200, 70], 64, 8, 2, 128, 16),
     ("chunk200_bs64", [700], 200, 4, 1, 64, 64),
     ("chunk256", [300, 1029], 256, 16, 2, 128, 16),
+    ("chunk40_ragged_row_block", [300, 41], 40, 8, 2, 128, 16),       # 160 rows: 128 + 32
+    ("prompt_from_an_empty_cache", [130, 130], 130, 4, 1, 128, 16),    # q_len = the whole sequence
+    ("chunk512_bs64_d64", [600, 512], 512, 8, 2, 64, 64),
 ]
 
 
@@ -198,3 +201,23 @@ def test_random_shapes(seed):
     chunk = int(rng.choice([0, 64, 128, 512]))
     wl = W.custom("random%d" % seed, mode, lens, q_len, G * Hkv, Hkv, D, bs, seed=seed)
     check(wl, chunks=(chunk,))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR])
+def test_many_query_rows_through_both_kernels(mode):
+    """128 and more query rows per kv head take the kernel that shares the dequantization among
+    128 rows; the streaming kernels must give the same answer (both within the bound of the
+    checker, and close to each other)."""
+    from paper_2605_29639_amd import kvq
+    wl = W.custom("both", mode, [700, 129, 64], 64, 8, 2, 128, 16, seed=40 + mode)
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    shared = gpu_attention(wl, cache, scales, desc)
+    kvq.lib().kvq_profile_prefill_kernel(0)
+    try:
+        streamed = gpu_attention(wl, cache, scales, desc)
+    finally:
+        kvq.lib().kvq_profile_prefill_kernel(1)
+    assert attn_err(shared, want) <= TOL and attn_err(streamed, want) <= TOL
+    assert attn_err(shared, streamed.astype(np.float64)) <= 2e-4
