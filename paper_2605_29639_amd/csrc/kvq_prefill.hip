@@ -35,6 +35,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   constexpr int VT = DT / kWavesPerGroup;  // V tiles a wavefront converts
   __shared__ half8 k_ops[2][4][KS][64];    // [half][quad of the sub-block][step][lane]
   __shared__ half8 v_ops[2][DT][2][64];    // [half][channel tile][tokens 0-7 | 8-15][lane]
+  __shared__ floatx4 s_ops[2][64];         // [half][token]: K scale * log2e / sqrt(D), log2 and
+                                           // reciprocal of the V scale
 
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int m16 = lane & 15, g4 = lane >> 4;
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     e.v = table[min(pos0 + 16 * g4, last_sb) >> bs_shift];
   };
   uintx4 rk[KJ], rv[VT];
-  float sk_next, sv_next;
+  float sk_next = 0.0f, sv_next = 0.0f;
   auto issue_loads = [&](int g, const Entries& e) {
     const int pos0 = g << 6;
     const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
@@ -120,10 +122,12 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     for (int j = 0; j < KJ; ++j) rk[j] = *(const uintx4*)(kbase + 256 * j);
 #pragma unroll
     for (int t = 0; t < VT; ++t) rv[t] = *(const uintx4*)(vbase + 256 * t);
-    const uint32_t s_lane = TOKEN_SCALE ? h * bs + m16 + off_v : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : (uint32_t)h);
-    const float* sp = scales + (size_t)e.v * s_block_stride + s_lane;
-    sk_next = sp[0];
-    sv_next = sp[s_kv];
+    if (wv == 0) {  // the scales of the group's 64 tokens, lane = token
+      const uint32_t s_lane = TOKEN_SCALE ? h * bs + m16 + off_v : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : (uint32_t)h);
+      const float* sp = scales + (size_t)e.v * s_block_stride + s_lane;
+      sk_next = sp[0];
+      sv_next = sp[s_kv];
+    }
   };
   auto publish = [&](int g, int half) {  // convert the loaded codes and put them in LDS
 #pragma unroll
@@ -147,6 +151,20 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
       for (int e = 0; e < 4; ++e) raw[e] &= keep[e];
       v_ops[half][wv * VT + t][0][lane] = cvt8<MODE>(raw[0], raw[1]);
       v_ops[half][wv * VT + t][1][lane] = cvt8<MODE>(raw[2], raw[3]);
+    }
+    // The scales go the same way: held in registers from the load to the softmax two iterations
+    // later, they would have to be copied at the end of the iteration that requested them, and
+    // that copy waits for the whole round trip to memory.
+    if (wv == 0) {
+      float skp = sk_next * p.scale_log2;
+      float lsv = __builtin_amdgcn_logf(fmaxf(sv_next, kMinVScale));
+      float rsv = __builtin_amdgcn_exp2f(-lsv);
+      if (TOKEN_SCALE && (g << 6) + lane >= L) {
+        skp = 0.0f;  // a slot that was never written: its scales are not data
+        lsv = 0.0f;
+        rsv = 0.0f;
+      }
+      s_ops[half][lane] = floatx4{skp, lsv, rsv, 0.0f};
     }
   };
 
@@ -181,18 +199,12 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto softmax_impl = [&](auto TAILC, int g, float sk, float sv) {
+  auto softmax_impl = [&](auto TAILC, int g, int half) {
 #pragma clang fp contract(off)
     constexpr bool TAIL = decltype(TAILC)::value;
     const int pos0 = g << 6;
-    float skp = sk * p.scale_log2;
-    float lsv = __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
-    float rsv = __builtin_amdgcn_exp2f(-lsv);
-    if (TOKEN_SCALE && TAIL && pos0 + 16 * g4 + m16 >= L) {
-      skp = 0.0f;  // a slot that was never written: its scales are not data
-      lsv = 0.0f;
-      rsv = 0.0f;
-    }
+    const floatx4 sc = s_ops[half][lane];
+    const float skp = sc[0], lsv = sc[1], rsv = sc[2];
     float mx[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
@@ -284,7 +296,6 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     fetch_entries(min(1, ng - 1), e_next);
     issue_loads(0, e0);
   }
-  float sk = sk_next, sv = sv_next;
   publish(0, 0);
   issue_loads(min(1, ng - 1), e_next);
   fetch_entries(min(2, ng - 1), e_after);
@@ -293,13 +304,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     const int half = g & 1;
     if (wave_live) {
       qk(half);
-      if ((g << 6) + 64 > n_min) softmax_impl(std::true_type{}, g, sk, sv);
-      else softmax_impl(std::false_type{}, g, sk, sv);
+      if ((g << 6) + 64 > n_min) softmax_impl(std::true_type{}, g, half);
+      else softmax_impl(std::false_type{}, g, half);
       pv(half);
     }
     // group g + 1 (requested one iteration ago) into the other half; request group g + 2
-    sk = sk_next;
-    sv = sv_next;
     publish(min(g + 1, ng - 1), half ^ 1);
     issue_loads(min(g + 2, ng - 1), e_after);
     fetch_entries(min(g + 3, ng - 1), e_after);
