@@ -348,10 +348,21 @@ def main():
     te1.record()
     torch.cuda.synchronize()
     chunk_s = te0.elapsed_time(te1) / 10 * 1e-3
+    L.kvq_profile_prefill_kernel(0)  # the same call through the streaming kernels, for comparison
+    for _ in range(2):
+        kvq.paged_decode_attn(qc, cc, cs, cdesc, btc, slc, cq, cL, wlc.sm_scale, outc, wsc, stream=stream)
+    te0.record()
+    for _ in range(5):
+        kvq.paged_decode_attn(qc, cc, cs, cdesc, btc, slc, cq, cL, wlc.sm_scale, outc, wsc, stream=stream)
+    te1.record()
+    torch.cuda.synchronize()
+    L.kvq_profile_prefill_kernel(1)
+    chunk_stream_s = te0.elapsed_time(te1) / 5 * 1e-3
     visible = sum(cL - cq + j + 1 for j in range(cq))
     chunk_flops = 4.0 * D * Hq * cB * visible
     mfma_peak = 2500.0  # TFLOP/s, dense f16 / bf16
     result["chunk_prefill"] = {"sequences": cB, "chunk_tokens": cq, "context": cL, "us": chunk_s * 1e6,
+                               "us_through_streaming_kernels": chunk_stream_s * 1e6,
                                "roofline": {"bound": "mfma", "achieved": chunk_flops / chunk_s / 1e12,
                                             "peak": mfma_peak, "unit": "TFLOP/s",
                                             "frac": chunk_flops / chunk_s / 1e12 / mfma_peak}}
