@@ -332,8 +332,8 @@ def main():
     # position); the bound here is the matrix cores, not HBM.
     from paper_2605_29639_amd import workloads as Wm
     cq, cL, cB = 512, 4608, 8
-    wlc = Wm.custom("chunk_prefill", wl.mode, [cL] * cB, cq, Hq, wl.num_kv_heads, D, wl.block_size,
-                    seed=5)
+    wlc = Wm.chunk_prefill(wl.mode, batch=cB, chunk=cq, prefix=cL - cq, Hq=Hq, Hkv=wl.num_kv_heads,
+                           D=D, bs=wl.block_size)
     cc, cs, cdesc = gpu_fill(wlc)
     qc = bits_to_bf16_tensor(wlc.q)
     btc = torch.from_numpy(wlc.block_tables).cuda()

@@ -225,6 +225,13 @@ def verify_prefix(batch=128, lo=2048, hi=16384, mode=MODE_INT8, shared_prefix=10
                    shared_prefix=shared_prefix)
 
 
+def chunk_prefill(mode=MODE_INT8, batch=8, chunk=512, prefix=4096, Hq=32, Hkv=8, D=128, bs=16):
+    """A chunk of a prompt per sequence: `chunk` query tokens attending causally over a
+    `prefix`-token context already in the cache and over themselves (Section 2's prefill phase
+    cut into chunks, fed from the Section 7.2.2 cache); configuration 2's heads by default."""
+    return custom("chunk_prefill", mode, [prefix + chunk] * batch, chunk, Hq, Hkv, D, bs, seed=5)
+
+
 def custom(name, mode, seq_lens, q_len, Hq, Hkv, D, bs, seed, outliers=True, shared_prefix=0,
            append_tokens=0, chunk_tokens=0):
     """Any other shape, for parity cases (ragged tails, odd lengths, other group sizes)."""

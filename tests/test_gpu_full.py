@@ -115,3 +115,13 @@ def test_verify_prefix_full_size(mode):
     assert wl.batch == 128 and wl.q_len == 4 and wl.group == 8 and wl.shared_prefix == 1024
     assert np.all(wl.block_tables[:, :64] == wl.block_tables[0, :64])
     compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=1))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8])
+def test_chunk_prefill_full_size(mode):
+    """The chunked-prefill shape bench.py times (8 sequences, 512 query tokens each over a
+    4096-token prefix and themselves, 2048 query rows per kv head): every row of one sequence
+    against the checker, the rest finite."""
+    wl = W.chunk_prefill(mode)
+    assert wl.batch == 8 and wl.q_len == 512 and int(wl.seq_lens[0]) == 4608
+    compare_on_sample(wl, chunks=(0,), seqs=[5])
