@@ -165,9 +165,12 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
  * merges a pair's partials by the log-sum-exp rule.  Results are deterministic run to run
  * (no atomics).
  * q_len is 1 in a decode step, a handful when speculated tokens are verified, and may be
- * hundreds for a chunk of a prompt attending over its quantized prefix and itself: the query
- * rows of a kv head are taken 32 at a time, each such group streaming the keys and values again
- * (from the caches, mostly), so that use is bound by arithmetic, not by HBM.
+ * hundreds for a chunk of a prompt attending over its quantized prefix and itself.  With 128
+ * and more query rows per kv head ((num_q_heads / num_kv_heads) * q_len) and int8 or e4m3 codes
+ * the call runs a kernel of its own that walks each (sequence, kv head) without a split and
+ * dequantizes every K/V tile once for 128 rows (no workspace use, no second kernel); otherwise
+ * the rows are taken 32 at a time, each such group streaming the keys and values again.  Either
+ * way that use is bound by arithmetic, not by HBM.
  * Requires 1 <= q_len <= KVQ_MAX_Q_LEN and num_q_heads % num_kv_heads == 0. */
 int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       const kvq_cache_desc_t* desc, const int32_t* block_tables,

@@ -81,8 +81,12 @@ __device__ inline int range_of(int f, int requested, int flat_groups, int num_wa
 // CEIL = true builds the read-ceiling twin used for measurement only: same ranges, same
 // addresses, same load instructions and the same pipeline, but the arithmetic is replaced by
 // an XOR of the loaded words (one dword per wavefront is stored so that the loads stay).
+// (The second launch bound, two wavefronts per SIMD, for the quantized one-tile kernels: they
+// fit either way, but told so the compiler keeps everything in 200-224 VGPRs instead of parking
+// values in AGPRs and copying them back, 1-2 % faster.)
 template <int MODE, int D, int NT, bool CEIL, int DEPTH>
-__global__ __launch_bounds__(64) void attn_stream_kernel(const AttnArgs p) {
+__global__ __launch_bounds__(64, (NT == 1 && !CEIL && MODE != KVQ_BF16_PLAIN) ? 2 : 1) void
+attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
   // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;

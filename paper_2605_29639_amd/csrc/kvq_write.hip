@@ -10,17 +10,13 @@
 // x and an fp32 scale the fp64 quotient is either exactly a rounding tie or at least 2^-25
 // (relative 2^-29 for the fp8 midpoints) away from one, so rounding it equals rounding the
 // exact quotient.  The scale itself is the fp64 quotient absmax/qmax rounded once to fp32.
-#include "kvq_internal.h"
+#include "kvq_quant.h"
 
 namespace kvq {
 namespace {
 
 constexpr int kWaves = 4;  // wavefronts per workgroup
 constexpr int kBulkTokens = 1024;  // calls with at least this many tokens take the prefill kernels
-
-__device__ inline float bf16_bits_to_float(uint32_t bits16) {
-  return __uint_as_float(bits16 << 16);
-}
 
 __device__ inline uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
@@ -29,13 +25,6 @@ __device__ inline uint32_t wave_max_u32(uint32_t v) {
     v = v > o ? v : o;
   }
   return v;
-}
-
-__device__ inline uint8_t int8_code(float x, float s) {
-  double r = rint((double)x / (double)s);  // v_rndne_f64: ties to even
-  r = r > 127.0 ? 127.0 : r;
-  r = r < -127.0 ? -127.0 : r;
-  return (uint8_t)(int8_t)(int)r;
 }
 
 // Nearest E4M3 (finite-only) code of the real y: ties to even, saturating at 448.
@@ -174,16 +163,6 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
 // within 4e-5 of a half-integer its nearest integer is the exact quotient's; the rare
 // elements that do are decided in fp64 like everywhere else.  The scale is one correctly
 // rounded fp32 division, which equals the fp64 quotient rounded once for every bf16 absmax.
-template <int CL>
-__device__ inline uint32_t row_max_u32(uint32_t v) {  // max over the CL lanes that share a row
-  auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
-  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
-  if constexpr (CL == 16)
-    v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
-  return v;
-}
 
 template <int D>
 __device__ inline void int8_subblock(const uint16_t* __restrict__ src, size_t tstride,
@@ -212,8 +191,7 @@ __device__ inline void int8_subblock(const uint16_t* __restrict__ src, size_t ts
       amax = amax > hi ? amax : hi;
     }
     amax = row_max_u32<CL>(amax);
-    const float a = bf16_bits_to_float(amax);
-    const float s = (amax == 0) ? 0.0f : __fdiv_rn(a, 127.0f);
+    const float s = int8_scale(amax);
     const bool fast = s > 1e-30f;  // rcp of a denormal is not usable
     const float inv = fast ? __builtin_amdgcn_rcpf(s) : 0.0f;
     uint32_t kcode[2] = {0, 0};
@@ -221,12 +199,7 @@ __device__ inline void int8_subblock(const uint16_t* __restrict__ src, size_t ts
     for (int e = 0; e < 8; ++e) {
       const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
                               : __uint_as_float(w[e >> 1] << 16);
-      const float q = x * inv;
-      float r = __builtin_rintf(q);
-      if (__builtin_expect(!fast || fabsf(q - r) > 0.5f - 4e-5f, 0)) {
-        r = (amax == 0) ? 0.0f : (float)(int8_t)int8_code(x, s);
-      }
-      const float stored = r + 128.0f;  // offset-binary, exact
+      const float stored = int8_code_f32(x, s, inv, fast) + 128.0f;  // offset-binary, exact
       if (kv == 0) kcode[e >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(stored, e & 3, kcode[e >> 2]);
       else vcode[e] = __builtin_amdgcn_cvt_pk_u8_f32(stored, i, vcode[e]);
     }

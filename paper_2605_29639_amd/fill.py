@@ -17,10 +17,24 @@ def gpu_desc(wl):
     return kvq.make_desc(wl.mode, wl.num_blocks, wl.block_size, wl.num_kv_heads, wl.head_dim)
 
 
-def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=None):
+def append_inputs(wl, sequences=None):
+    """(k, v, slot_mapping) device tensors of the workload's append step: the last
+    `append_tokens` positions of every sequence, sequence-major."""
+    import torch
+    ks, vs, ss = [], [], []
+    for b in (range(wl.batch) if sequences is None else sequences):
+        p0, p1 = wl.prefill_len(b), int(wl.seq_lens[b])
+        k, v = wl.kv_rows(b, p0, p1)
+        ks.append(k), vs.append(v), ss.append(wl.slots(b, p0, p1))
+    return (bits_to_bf16_tensor(np.concatenate(ks)), bits_to_bf16_tensor(np.concatenate(vs)),
+            torch.from_numpy(np.concatenate(ss)).cuda())
+
+
+def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=None, append=True):
     """The library writes the workload into a (zeroed unless given) device pool: one call per
-    sequence carrying all of its prefill tokens, then, if the workload has an append step, one
-    call carrying the appended token of every sequence.  Returns (cache, scales, desc)."""
+    sequence carrying all of its prefill tokens, then, if the workload has an append step (and
+    `append` is set), one call carrying the appended tokens of every sequence.  Returns
+    (cache, scales, desc)."""
     import torch
     from . import kvq
     desc = gpu_desc(wl)
@@ -36,15 +50,9 @@ def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=No
             kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
                                torch.from_numpy(wl.slots(b, start, stop)).cuda(), cache, scales,
                                desc)
-    if wl.append_tokens:
-        ks, vs, ss = [], [], []
-        for b in seqs:
-            p0, p1 = wl.prefill_len(b), int(wl.seq_lens[b])
-            k, v = wl.kv_rows(b, p0, p1)
-            ks.append(k), vs.append(v), ss.append(wl.slots(b, p0, p1))
-        kvq.kv_quant_write(bits_to_bf16_tensor(np.concatenate(ks)),
-                           bits_to_bf16_tensor(np.concatenate(vs)),
-                           torch.from_numpy(np.concatenate(ss)).cuda(), cache, scales, desc)
+    if wl.append_tokens and append:
+        k, v, slots = append_inputs(wl, seqs)
+        kvq.kv_quant_write(k, v, slots, cache, scales, desc)
     torch.cuda.synchronize()
     return cache, scales, desc
 
