@@ -30,11 +30,10 @@ def append_inputs(wl, sequences=None):
             torch.from_numpy(np.concatenate(ss)).cuda())
 
 
-def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=None, append=True):
+def gpu_fill(wl, sequences=None, cache=None, scales=None):
     """The library writes the workload into a (zeroed unless given) device pool: one call per
-    sequence carrying all of its prefill tokens, then, if the workload has an append step (and
-    `append` is set), one call carrying the appended tokens of every sequence.  Returns
-    (cache, scales, desc)."""
+    sequence carrying all of its prefill tokens, then, if the workload has an append step, one
+    call carrying the appended tokens of every sequence.  Returns (cache, scales, desc)."""
     import torch
     from . import kvq
     desc = gpu_desc(wl)
@@ -50,7 +49,7 @@ def gpu_fill(wl, sequences=None, cache=None, scales=None, max_tokens_per_call=No
             kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
                                torch.from_numpy(wl.slots(b, start, stop)).cuda(), cache, scales,
                                desc)
-    if wl.append_tokens and append:
+    if wl.append_tokens:
         k, v, slots = append_inputs(wl, seqs)
         kvq.kv_quant_write(k, v, slots, cache, scales, desc)
     torch.cuda.synchronize()
