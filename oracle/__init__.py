@@ -16,6 +16,7 @@ head_dim / 2 bytes (channel 2j in the low nibble of byte j, channel 2j+1 in the 
 4-bit two's complement), scales as mode 0.
 """
 import ctypes as C
+import os
 
 import numpy as np
 
@@ -33,7 +34,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(_build.build())
+        # KVQ_ORACLE_SO: load this build instead (tests/test_oracle_mutants.py runs the pins
+        # against deliberately wrong copies of the source to show that they notice)
+        _lib = C.CDLL(os.environ.get("KVQ_ORACLE_SO") or _build.build())
         L = _lib
         L.oracle_bf16_to_f64.restype = C.c_double
         L.oracle_bf16_to_f64.argtypes = [C.c_uint16]

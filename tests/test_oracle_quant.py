@@ -586,3 +586,13 @@ def test_int4_scale_is_correctly_rounded_and_zero_rows():
     codes, sc, cache, _ = write_rows_int4(row)
     assert sc[0] == 0 and not cache[0, 0, 0, 0].any()
     assert sc[1] == np.float32(2.0 / 7) and codes[1, 3] == -7 and np.count_nonzero(codes[1]) == 1
+
+
+def test_encoders_clamp_symmetrically_whatever_the_scale():
+    """The range is [-127, 127] (int8) and [-7, 7] (int4) also for a quotient beyond it, which a
+    row's own scale never produces but a scale taken from elsewhere can: -128 and -8 are never
+    codes (configuration 1: "clamped to [-127, 127]")."""
+    assert list(oracle.int8_encode(np.array([-1000.0, -127.5, -127.4, 127.5, 1e9]), np.float32(1.0))) \
+        == [-127, -127, -127, 127, 127]
+    assert list(oracle.int4_encode(np.array([-1000.0, -7.5, -7.4, 7.5, 1e9]), np.float32(1.0))) \
+        == [-7, -7, -7, 7, 7]
