@@ -36,40 +36,62 @@ def lib():
     if _lib is None:
         # KVQ_ORACLE_SO: load this build instead (tests/test_oracle_mutants.py runs the pins
         # against deliberately wrong copies of the source to show that they notice)
-        _lib = C.CDLL(os.environ.get("KVQ_ORACLE_SO") or _build.build())
-        L = _lib
-        L.oracle_bf16_to_f64.restype = C.c_double
-        L.oracle_bf16_to_f64.argtypes = [C.c_uint16]
-        L.oracle_fp8_decode.restype = C.c_double
-        L.oracle_fp8_decode.argtypes = [C.c_uint8]
-        L.oracle_fp8_encode.restype = C.c_uint8
-        L.oracle_fp8_encode.argtypes = [C.c_double]
-        L.oracle_int8_encode.restype = C.c_int8
-        L.oracle_int8_encode.argtypes = [C.c_double, C.c_float]
-        L.oracle_int4_encode.restype = C.c_int8
-        L.oracle_int4_encode.argtypes = [C.c_double, C.c_float]
-        L.oracle_scale.restype = C.c_float
-        L.oracle_scale.argtypes = [C.c_double, C.c_double]
-        L.oracle_kv_quant_write.restype = C.c_int
-        L.oracle_kv_quant_write.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                            C.c_void_p, C.c_void_p] + [C.c_int32] * 5
-        L.oracle_dequant_at.restype = C.c_double
-        L.oracle_dequant_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int,
-                                        C.c_int, C.c_int, C.c_int, C.c_int32, C.c_int32, C.c_int32]
-        L.oracle_gather_dequant.restype = None
-        L.oracle_gather_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
-                                            C.c_int32, C.c_int, C.c_int, C.c_int32, C.c_int32,
-                                            C.c_int32, C.c_void_p]
-        L.oracle_paged_decode_attn.restype = C.c_int
-        L.oracle_paged_decode_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + \
-            [C.c_int32] * 5 + [C.c_void_p, C.c_int32, C.c_void_p] + [C.c_int32] * 3 + \
-            [C.c_double, C.c_void_p]
-        L.oracle_attn_weights.restype = C.c_int32
-        L.oracle_attn_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4 + \
-            [C.c_void_p] + [C.c_int32] * 6 + [C.c_double, C.c_void_p]
-        L.oracle_num_threads.restype = C.c_int
-        L.oracle_num_threads.argtypes = []
+        _lib = _load(os.environ.get("KVQ_ORACLE_SO") or _build.build())
     return _lib
+
+
+class use_library:
+    """Context manager for tests of the tests: inside it every function of this package runs
+    on the given build of the C source (a copy with a planted mistake) instead of the real one."""
+
+    def __init__(self, so_path):
+        self.mutant = _load(so_path)
+
+    def __enter__(self):
+        global _lib
+        self.saved, _lib = lib(), self.mutant
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
+
+
+def _load(path):
+    L = C.CDLL(path)
+    L.oracle_bf16_to_f64.restype = C.c_double
+    L.oracle_bf16_to_f64.argtypes = [C.c_uint16]
+    L.oracle_fp8_decode.restype = C.c_double
+    L.oracle_fp8_decode.argtypes = [C.c_uint8]
+    L.oracle_fp8_encode.restype = C.c_uint8
+    L.oracle_fp8_encode.argtypes = [C.c_double]
+    L.oracle_int8_encode.restype = C.c_int8
+    L.oracle_int8_encode.argtypes = [C.c_double, C.c_float]
+    L.oracle_int4_encode.restype = C.c_int8
+    L.oracle_int4_encode.argtypes = [C.c_double, C.c_float]
+    L.oracle_scale.restype = C.c_float
+    L.oracle_scale.argtypes = [C.c_double, C.c_double]
+    L.oracle_kv_quant_write.restype = C.c_int
+    L.oracle_kv_quant_write.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_void_p] + [C.c_int32] * 5
+    L.oracle_dequant_at.restype = C.c_double
+    L.oracle_dequant_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int,
+                                    C.c_int, C.c_int, C.c_int, C.c_int32, C.c_int32, C.c_int32]
+    L.oracle_gather_dequant.restype = None
+    L.oracle_gather_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                        C.c_int32, C.c_int, C.c_int, C.c_int32, C.c_int32,
+                                        C.c_int32, C.c_void_p]
+    L.oracle_paged_decode_attn.restype = C.c_int
+    L.oracle_paged_decode_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + \
+        [C.c_int32] * 5 + [C.c_void_p, C.c_int32, C.c_void_p] + [C.c_int32] * 3 + \
+        [C.c_double, C.c_void_p]
+    L.oracle_attn_weights.restype = C.c_int32
+    L.oracle_attn_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4 + \
+        [C.c_void_p] + [C.c_int32] * 6 + [C.c_double, C.c_void_p]
+    L.oracle_num_threads.restype = C.c_int
+    L.oracle_num_threads.argtypes = []
+    return L
 
 
 def _ptr(a):
