@@ -366,6 +366,23 @@ def main():
                                "roofline": {"bound": "mfma", "achieved": chunk_flops / chunk_s / 1e12,
                                             "peak": mfma_peak, "unit": "TFLOP/s",
                                             "frac": chunk_flops / chunk_s / 1e12 / mfma_peak}}
+    if wl.mode != 2 and not args.no_bf16_baseline:   # the same chunk over an unquantized cache
+        wlb = Wm.chunk_prefill(2, batch=cB, chunk=cq, prefix=cL - cq, Hq=Hq, Hkv=wl.num_kv_heads,
+                               D=D, bs=wl.block_size)
+        cb, sb_, bdesc = gpu_fill(wlb)
+        wsb = kvq.alloc_workspace(bdesc, cB, cq, Hq, cL, 0)
+        btb = torch.from_numpy(wlb.block_tables).cuda()
+        for _ in range(3):
+            kvq.paged_decode_attn(qc, cb, sb_, bdesc, btb, slc, cq, cL, wlb.sm_scale, outc, wsb, stream=stream)
+        te0.record()
+        for _ in range(10):
+            kvq.paged_decode_attn(qc, cb, sb_, bdesc, btb, slc, cq, cL, wlb.sm_scale, outc, wsb, stream=stream)
+        te1.record()
+        torch.cuda.synchronize()
+        chunk_bf16_s = te0.elapsed_time(te1) / 10 * 1e-3
+        result["chunk_prefill"]["us_bf16_cache"] = chunk_bf16_s * 1e6
+        result["chunk_prefill"]["time_ratio_quantized_to_bf16"] = chunk_s / chunk_bf16_s
+        del cb, sb_, wsb, btb
     del cc, cs, qc, outc, wsc
 
     step(1)  # (the second layer cache: the prefill measurement above rewrote part of the first)

@@ -15,7 +15,8 @@
 //
 // The arithmetic (logits in base 2 with the K scale applied after the contraction, V scale
 // folded into the probability, f16 probabilities scaled by 2^10, masks) is the streaming
-// kernel's.
+// kernel's, and so is the treatment of an unquantized cache: its bf16 rows are the operands
+// as they are (copied to LDS, no conversion) and a probability enters P.V as two bf16 terms.
 #include "kvq_attn_common.h"
 
 namespace kvq {
@@ -26,13 +27,19 @@ constexpr int kRowsPerWorkgroup = kWavesPerGroup * 32;
 
 template <int MODE, int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(const AttnArgs p) {
+  constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: the operands are its bytes
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
   constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD;
   constexpr int NT = 2;
+  constexpr int EB = PLAIN ? 2 : 1;  // bytes per cache element
+  constexpr int RB = D * EB;       // bytes per token row in a tile
   constexpr int DT = D / 16;       // 16-channel tiles of V / of the output
-  constexpr int KJ = D / 64;       // 16-byte K pieces per lane and quad
+  constexpr int KJ = RB / 64;      // 16-byte K pieces per lane and quad
   constexpr int KS = D / 32;       // matrix-instruction steps over the channels
   constexpr int VT = DT / kWavesPerGroup;  // V tiles a wavefront converts
+  constexpr int VP = VT * EB;      // 16-byte V pieces per lane
+  // matrix-instruction operand of 8 values: f16 (from codes) or the cache's own bf16
+  using Operand = std::conditional_t<PLAIN, bf16x8, half8>;
   __shared__ half8 k_ops[2][4][KS][64];    // [half][quad of the sub-block][step][lane]
   __shared__ half8 v_ops[2][DT][2][64];    // [half][channel tile][tokens 0-7 | 8-15][lane]
   __shared__ floatx4 s_ops[2][64];         // [half][token]: K scale * log2e / sqrt(D), log2 and
@@ -60,17 +67,17 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
   const int32_t* __restrict__ table = p.block_tables + (size_t)b * p.max_blocks_per_seq;
-  const uint32_t tile_bytes = (uint32_t)bs * D;
+  const uint32_t tile_bytes = (uint32_t)bs * RB;
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;
   const int sbk = m16 >> 2;  // sub-block this lane reads K from
-  const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3) + (uint32_t)wv * (4 * D);  // quad wv
+  const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3) + (uint32_t)wv * (4 * RB);  // quad wv
   const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16 + 256u * (wv * VT);
   const uint32_t s_block_stride = TOKEN_SCALE ? 2u * H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : 2u * H);
   const uint32_t s_kv = TOKEN_SCALE ? (uint32_t)H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 1u : (uint32_t)H);
   const int last_sb = ((L - 1) >> 4) << 4;
 
   // ---- q as the B operand of QK^T, causal lengths, running state ----
-  half8 qb[NT][KS];
+  Operand qb[NT][KS];
   int nrow[NT];
   floatx4 acc[NT][DT];
   float m_run[NT], l_run[NT];
@@ -85,14 +92,18 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
         p.q + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const int d0 = 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+      const int d0 = PLAIN ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
       const uintx4 raw = *(const uintx4*)(qrow + d0);
+      if constexpr (PLAIN) {
+        qb[nt][s] = __builtin_bit_cast(bf16x8, live ? raw : uintx4{0u, 0u, 0u, 0u});
+      } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
-        const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
-        qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
-        qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+        for (int e = 0; e < 4; ++e) {
+          const _Float16 lo = (_Float16)__uint_as_float(raw[e] << 16);
+          const _Float16 hi = (_Float16)__uint_as_float(raw[e] & 0xFFFF0000u);
+          qb[nt][s][2 * e] = live ? lo : (_Float16)0.0f;
+          qb[nt][s][2 * e + 1] = live ? hi : (_Float16)0.0f;
+        }
       }
     }
     m_run[nt] = -INFINITY;
@@ -110,19 +121,21 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     e.k = table[min(pos0 + 16 * sbk, last_sb) >> bs_shift];
     e.v = table[min(pos0 + 16 * g4, last_sb) >> bs_shift];
   };
-  uintx4 rk[KJ], rv[VT];
+  uintx4 rk[KJ], rv[VP];
   float sk_next = 0.0f, sv_next = 0.0f;
   auto issue_loads = [&](int g, const Entries& e) {
     const int pos0 = g << 6;
     const uint32_t off_k = (uint32_t)(min(pos0 + 16 * sbk, last_sb) & (bs - 1));
     const uint32_t off_v = (uint32_t)(min(pos0 + 16 * g4, last_sb) & (bs - 1));
-    const uint8_t* kbase = cache + (size_t)e.k * block_stride + (h * tile_bytes + off_k * D + k_lane);
-    const uint8_t* vbase = cache + (size_t)e.v * block_stride + (h * tile_bytes + off_v * D + v_lane);
+    const uint8_t* kbase = cache + (size_t)e.k * block_stride + (h * tile_bytes + off_k * RB + k_lane);
+    const uint8_t* vbase = cache + (size_t)e.v * block_stride + (h * tile_bytes + off_v * RB + v_lane);
 #pragma unroll
     for (int j = 0; j < KJ; ++j) rk[j] = *(const uintx4*)(kbase + 256 * j);
+    // (unquantized: piece 2 t + hf is channel tile t, tokens 8 hf .. 8 hf + 7)
 #pragma unroll
-    for (int t = 0; t < VT; ++t) rv[t] = *(const uintx4*)(vbase + 256 * t);
-    if (wv == 0) {  // the scales of the group's 64 tokens, lane = token
+    for (int x = 0; x < VP; ++x)
+      rv[x] = *(const uintx4*)(vbase + (PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x));
+    if (!PLAIN && wv == 0) {  // the scales of the group's 64 tokens, lane = token
       const uint32_t s_lane = TOKEN_SCALE ? h * bs + m16 + off_v : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : (uint32_t)h);
       const float* sp = scales + (size_t)e.v * s_block_stride + s_lane;
       sk_next = sp[0];
@@ -130,6 +143,24 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     }
   };
   auto publish = [&](int g, int half) {  // convert the loaded codes and put them in LDS
+    if constexpr (PLAIN) {  // bf16 rows are operands as they are; the LDS arrays hold their bits
+#pragma unroll
+      for (int j = 0; j < KJ; ++j) k_ops[half][wv][j][lane] = __builtin_bit_cast(half8, rk[j]);
+      const int live = L - ((g << 6) + 16 * g4);  // tokens of this lane's sub-block below L
+#pragma unroll
+      for (int x = 0; x < VP; ++x) {
+        uintx4 raw = rv[x];
+        if ((g << 6) + 64 > L) {  // bf16 bit patterns of missing tokens: a NaN times 0 is NaN
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = live - (8 * (x & 1) + 2 * e);
+            raw[e] &= n >= 2 ? ~0u : n == 1 ? 0xFFFFu : 0u;
+          }
+        }
+        v_ops[half][wv * VT + (x >> 1)][x & 1][lane] = __builtin_bit_cast(half8, raw);
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < KJ; ++j) {
       k_ops[half][wv][2 * j][lane] = cvt8<MODE>(rk[j][0], rk[j][1]);
@@ -170,7 +201,15 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 
   // ---- consumer side ----
   floatx4 S[NT][4];
-  half8 pb[NT][2];
+  Operand pb[NT][2 * EB];  // unquantized: a probability goes in as two bf16 terms (hi, lo)
+  auto load_op = [&](const half8& bits) {
+    if constexpr (PLAIN) return __builtin_bit_cast(bf16x8, bits);
+    else return bits;
+  };
+  auto mma = [&](const Operand& a, const Operand& b, const floatx4& c) {
+    if constexpr (PLAIN) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  };
   auto qk = [&](int half) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -180,22 +219,22 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     // per step, the next step's four operands read from LDS while they run.  The scheduling
     // barriers keep that order; left alone, the compiler reads two operands, waits, issues
     // four instructions and so exposes the LDS latency eight times per group.
-    half8 a[2][4];
+    Operand a[2][4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) a[0][u] = k_ops[half][u][0][lane];
+    for (int u = 0; u < 4; ++u) a[0][u] = load_op(k_ops[half][u][0][lane]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s + 1 < KS) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[(s + 1) & 1][u] = k_ops[half][u][s + 1][lane];
+        for (int u = 0; u < 4; ++u) a[(s + 1) & 1][u] = load_op(k_ops[half][u][s + 1][lane]);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s & 1][u], qb[nt][s], S[nt][u], 0, 0, 0);
+          S[nt][u] = mma(a[s & 1][u], qb[nt][s], S[nt][u]);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -203,8 +242,13 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 #pragma clang fp contract(off)
     constexpr bool TAIL = decltype(TAILC)::value;
     const int pos0 = g << 6;
-    const floatx4 sc = s_ops[half][lane];
-    const float skp = sc[0], lsv = sc[1], rsv = sc[2];
+    float skp = p.scale_log2, lsv = 0.0f, rsv = 1.0f;
+    if constexpr (!PLAIN) {
+      const floatx4 sc = s_ops[half][lane];
+      skp = sc[0];
+      lsv = sc[1];
+      rsv = sc[2];
+    }
     float mx[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
@@ -216,6 +260,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
         if constexpr (TOKEN_SCALE) {
           ze = S[nt][u][i] * row_bcast<tix>(skp);
           ze = ze + row_bcast<tix>(lsv);
+        } else if constexpr (PLAIN) {
+          ze = S[nt][u][i] * skp;
         } else {
           ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
         }
@@ -235,6 +281,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
       m_run[nt] = m_new;
       const float msub = m_safe - kPOffset;
       float lsum = 0.0f;
+      [[maybe_unused]] uint32_t hi_bits[16], lo_bits[16];
       static_for<16>([&](auto I) {
         constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
         const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
@@ -244,8 +291,28 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
         } else {
           lsum = lsum + pr;
         }
-        pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+        if constexpr (PLAIN) {
+          // bf16 keeps 8 bits of a probability: it goes in as two terms, the value cut to
+          // bf16 and the (exactly representable) rest cut to bf16, 16 bits in all
+          hi_bits[tix] = __float_as_uint(pr) & 0xFFFF0000u;
+          lo_bits[tix] = __float_as_uint(pr - __uint_as_float(hi_bits[tix]));
+        } else {
+          pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+        }
       });
+      if constexpr (PLAIN) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          uintx4 ph, pl;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {  // the upper halves of two tokens' words, packed
+            ph[e] = __builtin_amdgcn_perm(hi_bits[8 * hf + 2 * e + 1], hi_bits[8 * hf + 2 * e], 0x07060302u);
+            pl[e] = __builtin_amdgcn_perm(lo_bits[8 * hf + 2 * e + 1], lo_bits[8 * hf + 2 * e], 0x07060302u);
+          }
+          pb[nt][hf] = __builtin_bit_cast(bf16x8, ph);
+          pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
+        }
+      }
       if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
       l_run[nt] = l_run[nt] * alpha[nt] + lsum;
     }
@@ -259,11 +326,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   auto pv = [&](int half) {
     // two channel tiles at a time: their four operands are read while the previous pair's
     // eight instructions run; the instructions alternate between four accumulators
-    half8 a[2][2][2];
+    Operand a[2][2][2];
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) a[0][x][hf] = v_ops[half][x][hf][lane];
+      for (int hf = 0; hf < 2; ++hf) a[0][x][hf] = load_op(v_ops[half][x][hf][lane]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t2 = 0; t2 < DT / 2; ++t2) {
@@ -272,7 +339,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
         for (int x = 0; x < 2; ++x)
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf)
-            a[(t2 + 1) & 1][x][hf] = v_ops[half][2 * (t2 + 1) + x][hf][lane];
+            a[(t2 + 1) & 1][x][hf] = load_op(v_ops[half][2 * (t2 + 1) + x][hf][lane]);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -280,9 +347,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[nt][2 * t2 + x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                a[t2 & 1][x][hf], pb[nt][hf], acc[nt][2 * t2 + x], 0, 0, 0);
+          for (int nt = 0; nt < NT; ++nt) {
+            acc[nt][2 * t2 + x] = mma(a[t2 & 1][x][hf], pb[nt][hf], acc[nt][2 * t2 + x]);
+            if constexpr (PLAIN)
+              acc[nt][2 * t2 + x] = mma(a[t2 & 1][x][hf], pb[nt][2 + hf], acc[nt][2 * t2 + x]);
+          }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -332,9 +401,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 }  // namespace
 
 bool prefill_applies(const AttnArgs& a) {
-  return a.rows >= kRowsPerWorkgroup &&
-         (a.mode == KVQ_INT8_TOKEN_HEAD || a.mode == KVQ_FP8E4M3_BLOCK_HEAD ||
-          a.mode == KVQ_FP8E4M3_TENSOR);
+  return a.rows >= kRowsPerWorkgroup && a.mode != KVQ_INT4_TOKEN_HEAD;
 }
 
 hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
@@ -350,6 +417,8 @@ hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
     KVQ_LAUNCH_PREFILL(KVQ_INT8_TOKEN_HEAD);
   } else if (a.mode == KVQ_FP8E4M3_BLOCK_HEAD) {
     KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_BLOCK_HEAD);
+  } else if (a.mode == KVQ_BF16_PLAIN) {
+    KVQ_LAUNCH_PREFILL(KVQ_BF16_PLAIN);
   } else {
     KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_TENSOR);
   }

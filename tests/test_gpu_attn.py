@@ -101,13 +101,15 @@ def test_gpu_written_cache_gives_the_same_attention(mode):
     assert attn_err(a, want) <= TOL
 
 
+@pytest.mark.parametrize("q_len", [1, 40])   # 40 tokens x 4 heads: the many-row kernel
 @pytest.mark.parametrize("mode", MODES)
-def test_stale_bytes_after_the_last_position_are_never_used(mode):
+def test_stale_bytes_after_the_last_position_are_never_used(mode, q_len):
     """Unwritten slots hold NaN codes / NaN or huge scales; block-table entries past the last
     block are -1.  The output must not change and must stay finite."""
     import torch
     D = 128 if mode == W.MODE_INT4 else 64
-    wl = W.custom("stale", mode, [37, 100, 64, 3], 1, 4, 2, D, 16, seed=8)
+    lens = [max(l, q_len) for l in (37, 100, 64, 3)]
+    wl = W.custom("stale", mode, lens, q_len, 4 if q_len == 1 else 8, 2, D, 16, seed=8)
     oc, osc = oracle_fill(wl)
     want = oracle_out(wl, oc, osc)
     live = np.zeros(oc.shape[:1] + oc.shape[3:4], dtype=bool)       # [blk, off]
@@ -203,7 +205,7 @@ def test_random_shapes(seed):
     check(wl, chunks=(chunk,))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_BF16])
 def test_many_query_rows_through_both_kernels(mode):
     """128 and more query rows per kv head take the kernel that shares the dequantization among
     128 rows; the streaming kernels must give the same answer (both within the bound of the
