@@ -166,7 +166,7 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
  * (no atomics).
  * q_len is 1 in a decode step, a handful when speculated tokens are verified, and may be
  * hundreds for a chunk of a prompt attending over its quantized prefix and itself.  With 128
- * and more query rows per kv head ((num_q_heads / num_kv_heads) * q_len) and any mode but int4
+ * and more query rows per kv head ((num_q_heads / num_kv_heads) * q_len)
  * the call runs a kernel of its own that walks each (sequence, kv head) without a split and
  * dequantizes every K/V tile once for 128 rows (no workspace use, no second kernel); otherwise
  * the rows are taken 32 at a time, each such group streaming the keys and values again.  Either

@@ -29,15 +29,17 @@ template <int MODE, int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: the operands are its bytes
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
-  constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD;
+  constexpr bool INT4 = MODE == KVQ_INT4_TOKEN_HEAD;  // two codes per byte (head_dim 128)
+  constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD || INT4;
+  static_assert(!INT4 || D == 128, "int4 codes come with head_dim 128 only");
   constexpr int NT = 2;
   constexpr int EB = PLAIN ? 2 : 1;  // bytes per cache element
-  constexpr int RB = D * EB;       // bytes per token row in a tile
+  constexpr int RB = INT4 ? D / 2 : D * EB;  // bytes per token row in a tile
   constexpr int DT = D / 16;       // 16-channel tiles of V / of the output
   constexpr int KJ = RB / 64;      // 16-byte K pieces per lane and quad
   constexpr int KS = D / 32;       // matrix-instruction steps over the channels
   constexpr int VT = DT / kWavesPerGroup;  // V tiles a wavefront converts
-  constexpr int VP = VT * EB;      // 16-byte V pieces per lane
+  constexpr int VP = INT4 ? VT / 2 : VT * EB;  // 16-byte V pieces per lane (int4: one piece = two tiles)
   // matrix-instruction operand of 8 values: f16 (from codes) or the cache's own bf16
   using Operand = std::conditional_t<PLAIN, bf16x8, half8>;
   __shared__ half8 k_ops[2][4][KS][64];    // [half][quad of the sub-block][step][lane]
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;
   const int sbk = m16 >> 2;  // sub-block this lane reads K from
   const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3) + (uint32_t)wv * (4 * RB);  // quad wv
-  const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16 + 256u * (wv * VT);
+  const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16 + 256u * (wv * (INT4 ? VP : VT));
   const uint32_t s_block_stride = TOKEN_SCALE ? 2u * H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 0u : 2u * H);
   const uint32_t s_kv = TOKEN_SCALE ? (uint32_t)H * bs : (MODE == KVQ_FP8E4M3_TENSOR ? 1u : (uint32_t)H);
   const int last_sb = ((L - 1) >> 4) << 4;
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
         p.q + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const int d0 = PLAIN ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
+      const int d0 = PLAIN || INT4 ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
       const uintx4 raw = *(const uintx4*)(qrow + d0);
       if constexpr (PLAIN) {
         qb[nt][s] = __builtin_bit_cast(bf16x8, live ? raw : uintx4{0u, 0u, 0u, 0u});
@@ -161,27 +163,39 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
       }
       return;
     }
+    if constexpr (INT4) {
+      // K: word st of the lane's piece holds the 8 channels of step st; V: a piece holds two
+      // channel tiles, words 0, 1 the first tile's tokens 0-7 and 8-15, words 2, 3 the second's
 #pragma unroll
-    for (int j = 0; j < KJ; ++j) {
-      k_ops[half][wv][2 * j][lane] = cvt8<MODE>(rk[j][0], rk[j][1]);
-      k_ops[half][wv][2 * j + 1][lane] = cvt8<MODE>(rk[j][2], rk[j][3]);
-    }
-    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
-    if (FP8 && (g << 6) + 64 > L) {  // V bytes of missing tokens: an e4m3 NaN times 0 is NaN
-      const int live = L - ((g << 6) + 16 * g4);
+      for (int st = 0; st < 4; ++st) k_ops[half][wv][st][lane] = cvt_int4(rk[0][st]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int n = min(max(live - 4 * e, 0), 4);
-        keep[e] = n == 4 ? ~0u : (1u << (8 * n)) - 1u;
+      for (int x = 0; x < VP; ++x)
+#pragma unroll
+        for (int w4 = 0; w4 < 4; ++w4)
+          v_ops[half][2 * (wv * VP + x) + (w4 >> 1)][w4 & 1][lane] = cvt_int4(rv[x][w4]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < KJ; ++j) {
+        k_ops[half][wv][2 * j][lane] = cvt8<MODE>(rk[j][0], rk[j][1]);
+        k_ops[half][wv][2 * j + 1][lane] = cvt8<MODE>(rk[j][2], rk[j][3]);
       }
-    }
+      uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
+      if (FP8 && (g << 6) + 64 > L) {  // V bytes of missing tokens: an e4m3 NaN times 0 is NaN
+        const int live = L - ((g << 6) + 16 * g4);
 #pragma unroll
-    for (int t = 0; t < VT; ++t) {
-      uintx4 raw = rv[t];
+        for (int e = 0; e < 4; ++e) {
+          const int n = min(max(live - 4 * e, 0), 4);
+          keep[e] = n == 4 ? ~0u : (1u << (8 * n)) - 1u;
+        }
+      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) raw[e] &= keep[e];
-      v_ops[half][wv * VT + t][0][lane] = cvt8<MODE>(raw[0], raw[1]);
-      v_ops[half][wv * VT + t][1][lane] = cvt8<MODE>(raw[2], raw[3]);
+      for (int t = 0; t < VT; ++t) {
+        uintx4 raw = rv[t];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) raw[e] &= keep[e];
+        v_ops[half][wv * VT + t][0][lane] = cvt8<MODE>(raw[0], raw[1]);
+        v_ops[half][wv * VT + t][1][lane] = cvt8<MODE>(raw[2], raw[3]);
+      }
     }
     // The scales go the same way: held in registers from the load to the softmax two iterations
     // later, they would have to be copied at the end of the iteration that requested them, and
@@ -401,7 +415,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 }  // namespace
 
 bool prefill_applies(const AttnArgs& a) {
-  return a.rows >= kRowsPerWorkgroup && a.mode != KVQ_INT4_TOKEN_HEAD;
+  return a.rows >= kRowsPerWorkgroup;
 }
 
 hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
@@ -419,6 +433,8 @@ hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
     KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_BLOCK_HEAD);
   } else if (a.mode == KVQ_BF16_PLAIN) {
     KVQ_LAUNCH_PREFILL(KVQ_BF16_PLAIN);
+  } else if (a.mode == KVQ_INT4_TOKEN_HEAD) {  // (head_dim 128 only)
+    hipLaunchKernelGGL((attn_prefill_kernel<KVQ_INT4_TOKEN_HEAD, 128>), grid, block, 0, stream, a);
   } else {
     KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_TENSOR);
   }

@@ -205,7 +205,7 @@ def test_random_shapes(seed):
     check(wl, chunks=(chunk,))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_BF16])
+@pytest.mark.parametrize("mode", MODES)
 def test_many_query_rows_through_both_kernels(mode):
     """128 and more query rows per kv head take the kernel that shares the dequantization among
     128 rows; the streaming kernels must give the same answer (both within the bound of the

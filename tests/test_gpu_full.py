@@ -117,7 +117,7 @@ def test_verify_prefix_full_size(mode):
     compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=1))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_INT4])
 def test_chunk_prefill_full_size(mode):
     """The chunked-prefill shape bench.py times (8 sequences, 512 query tokens each over a
     4096-token prefix and themselves, 2048 query rows per kv head): every row of one sequence
