@@ -667,8 +667,9 @@ attn_stream_kernel(const AttnArgs p) {
   if constexpr (CEIL) p.ws_acc[(size_t)w * 64 + lane] = __uint_as_float(ceil_x & 0x3FFFFFFFu);
 }
 
-// ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query head), which
-// takes the sequence's query tokens one after another, each lane owning D/64 channels.  It
+// ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query head) and
+// slice of the sequence's query tokens (blockIdx.y; up to 64 slices, so a handful of tokens get
+// a wavefront each), each lane owning D/64 channels.  It
 // recomputes where the pair lies in the flat list and which wavefront ranges cover it; the
 // (max, sum) pairs of up to 64 ranges are fetched by 64 lanes at once, so the chain of
 // dependent memory round trips stays short. ----
@@ -692,7 +693,7 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
   const int ng = (p.seq_lens[b] + 63) >> 6;
-  for (int j = 0; j < p.q_len; ++j) {
+  for (int j = blockIdx.y; j < p.q_len; j += gridDim.y) {
     const int r = j * p.group + (hq - h * p.group);
     const int rg = r / rt, rl = r - rg * rt;
     const int pr = h * p.num_row_groups + rg;
@@ -802,11 +803,11 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);
   if (e != hipSuccess || g_read_ceiling || g_skip_reduce) return e;
-  const unsigned rgrid = (unsigned)((size_t)a.batch * a.num_q_heads);
+  const dim3 rgrid((unsigned)((size_t)a.batch * a.num_q_heads), (unsigned)(a.q_len < 64 ? a.q_len : 64));
   if (a.head_dim == 128)
-    hipLaunchKernelGGL((attn_reduce_kernel<128>), dim3(rgrid), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_reduce_kernel<128>), rgrid, dim3(64), 0, stream, a);
   else
-    hipLaunchKernelGGL((attn_reduce_kernel<64>), dim3(rgrid), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL((attn_reduce_kernel<64>), rgrid, dim3(64), 0, stream, a);
   return hipGetLastError();
 }
 
