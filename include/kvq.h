@@ -181,8 +181,8 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
 
 /* Conversions between the physical cache above and the canonical
  * [num_blocks][2][num_kv_heads][block_size][head_dim] array of plain codes (int8 two's
- * complement / e4m3 bytes / bf16 bit patterns); both device, kvq_cache_bytes() long, must not overlap.  Used by
- * tests and tools; not on the hot path. */
+ * complement / e4m3 bytes / bf16 bit patterns / int4 pairs); both device, kvq_cache_bytes()
+ * long, must not overlap.  Used by tests and tools; not on the hot path. */
 int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,
                            void* stream);
 int kvq_cache_from_canonical(const void* canonical, void* cache, const kvq_cache_desc_t* desc,
@@ -231,7 +231,7 @@ void kvq_profile_skip_reduce(int on);
 
 /* Measurement and test hook: 0 makes paged_decode_attn use its streaming kernels also for 128
  * and more query rows per kv head, where it otherwise takes the kernel that shares the
- * dequantization among 128 rows (int8 and both e4m3 modes).  On initially.  Process-global. */
+ * dequantization among 128 rows.  On initially.  Process-global. */
 void kvq_profile_prefill_kernel(int on);
 
 /* Measurement hook, not part of the path: while `buf` (device, 8 x uint64 per launched
