@@ -1,11 +1,16 @@
-// kv_quant_write kernels (gfx950): bf16 K/V rows -> int8 or fp8-e4m3 codes + fp32 scales in
-// the paged cache (Section 7.2.2, on-the-fly quantization with dynamic scaling).
+// kv_quant_write kernels (gfx950): bf16 K/V rows -> int8, int4 or fp8-e4m3 codes + fp32 scales
+// in the paged cache (Section 7.2.2, on-the-fly quantization with dynamic scaling), or the
+// rows themselves for an unquantized cache.
 //
 // One 64-lane wavefront owns one unit of work, so every output byte and every scale has
 // exactly one writer and no atomics are needed:
-//   int8 per (token, head): unit = (token, kv head, K|V) row of head_dim values;
+//   int8 / int4 per (token, head): unit = (run, kv head, K|V), a run being consecutive tokens
+//                           of the call with consecutive slots inside one 16-token sub-block;
 //   fp8 per (block, head):  unit = (run, kv head, K|V), a run being the consecutive tokens
-//                           of the call that fall into one cache block.
+//                           of the call that fall into one cache block;
+//   fp8 under static scales, bf16 rows: as int8 without the scale.
+// Each format has a general routine (any run) and one for whole 16-token sub-blocks, which
+// calls carrying a prompt take (16-byte loads, fp32 rounding with an fp64 decision near ties).
 // The decisions that fix an integer (the rounding of x/scale) are taken in fp64: for a bf16
 // x and an fp32 scale the fp64 quotient is either exactly a rounding tie or at least 2^-25
 // (relative 2^-29 for the fp8 midpoints) away from one, so rounding it equals rounding the
