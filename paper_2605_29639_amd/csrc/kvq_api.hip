@@ -73,6 +73,7 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   const size_t rows = slots * 16 * plan->row_tiles;
   plan->acc_floats = rows * d->head_dim;
   plan->ml_floats = rows * 2;
+  plan->prefix_ints = ((size_t)batch + 1 + 3) & ~(size_t)3;
   return true;
 }
 
@@ -120,7 +121,7 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
   int err;
   if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
     return 0;
-  return (plan.acc_floats + plan.ml_floats) * sizeof(float);
+  return (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
 }
 
 int paged_decode_attn(const void* q, const void* cache, const float* scales,
@@ -140,7 +141,7 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
   if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
   if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
-  const size_t need = (plan.acc_floats + plan.ml_floats) * sizeof(float);
+  const size_t need = (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
   if (need > 0) {
     if (!workspace) return KVQ_E_NULLPTR;
     if (workspace_bytes < need) return KVQ_E_WORKSPACE;
@@ -156,6 +157,7 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   a.out = out;
   a.ws_acc = (float*)workspace;
   a.ws_ml = (float*)workspace + plan.acc_floats;
+  a.ws_prefix = (int32_t*)((float*)workspace + plan.acc_floats + plan.ml_floats);
   a.max_blocks_per_seq = max_blocks_per_seq;
   a.batch = batch;
   a.q_len = q_len;

@@ -124,6 +124,16 @@ attn_stream_kernel(const AttnArgs p) {
     total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
   }
   const int flat = uni(wave_sum(total)) * Hp;
+  if (!CEIL && w == 0) {  // for the reduce: 64-token groups of the sequences before each one
+    int base = 0;
+    for (int k0 = 0; k0 < B; k0 += 64) {
+      const int i = k0 + lane;
+      const int incl = wave_incl_scan((i < B) ? (seq_lens[i] + 63) >> 6 : 0, lane);
+      if (i < B) p.ws_prefix[i + 1] = base + incl;
+      base += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) p.ws_prefix[0] = 0;
+  }
   const int f0 = range_begin(w, p.range_groups, flat, p.num_waves);
   const int f1 = range_begin(w + 1, p.range_groups, flat, p.num_waves);
   if (f0 >= f1) return;
@@ -669,10 +679,11 @@ attn_stream_kernel(const AttnArgs p) {
 
 // ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query head) and
 // slice of the sequence's query tokens (blockIdx.y; up to 64 slices, so a handful of tokens get
-// a wavefront each), each lane owning D/64 channels.  It
-// recomputes where the pair lies in the flat list and which wavefront ranges cover it; the
-// (max, sum) pairs of up to 64 ranges are fetched by 64 lanes at once, so the chain of
-// dependent memory round trips stays short. ----
+// a wavefront each), each lane owning D/64 channels.  Where the pair lies in the flat list
+// comes from the prefix sums the streaming kernel's first wavefront left in the workspace (a
+// scan of seq_lens in every one of these wavefronts would cost batch^2 * heads loads); which
+// wavefront ranges cover it is arithmetic; the (max, sum) pairs of up to 64 ranges are fetched
+// by 64 lanes at once, so the chain of dependent memory round trips stays short. ----
 template <int D>
 __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   constexpr int E = D / 64;
@@ -680,19 +691,13 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   const int hq = blockIdx.x % p.num_q_heads;
   const int b = blockIdx.x / p.num_q_heads;
   const int lane = threadIdx.x;
-  int before = 0, total = 0;
-  for (int i = lane; i < p.batch; i += 64) {
-    const int n = (p.seq_lens[i] + 63) >> 6;
-    total += n;
-    before += (i < b) ? n : 0;
-  }
-  before = uni(wave_sum(before));
-  total = uni(wave_sum(total));
+  // where the sequence lies in the flat list: the prefix sums the streaming kernel left
+  const int before = p.ws_prefix[b], total = p.ws_prefix[p.batch];
   const int Hp = p.pairs_per_seq;
   const int flat = total * Hp;
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
-  const int ng = (p.seq_lens[b] + 63) >> 6;
+  const int ng = p.ws_prefix[b + 1] - before;
   for (int j = blockIdx.y; j < p.q_len; j += gridDim.y) {
     const int r = j * p.group + (hq - h * p.group);
     const int rg = r / rt, rl = r - rg * rt;

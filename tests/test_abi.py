@@ -105,10 +105,11 @@ def test_attn_argument_checks():
     assert attn(L, ok, batch=0) == kvq.OK                  # empty batch: nothing launched
     for name in ("q", "cache", "scales", "tables", "lens", "out"):
         assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
-    # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each
+    # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each, and the
+    # prefix sums of the sequences' group counts (batch + 1 ints, padded to a multiple of 4)
     need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
     flat_max = 2 * 2 * 2                                   # batch * ceil(100/64) * kv heads
-    assert need == (flat_max + 2 * 2) * 16 * (64 + 2) * 4
+    assert need == (flat_max + 2 * 2) * 16 * (64 + 2) * 4 + 4 * 4
     assert attn(L, ok, chunk=64, ws=None) == kvq.E_NULLPTR
     assert attn(L, ok, chunk=64, ws_bytes=need - 1) == kvq.E_WORKSPACE
     assert attn(L, ok, chunk=64, ws=C.c_void_p(0x1004), ws_bytes=need) == kvq.E_BAD_SHAPE
@@ -116,11 +117,11 @@ def test_attn_argument_checks():
     assert auto == need                                    # fewer groups than resident waves
     big = kvq.make_desc(0, 1000, 16, 8, 128)
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
-        (2048 + 64 * 8) * 16 * (128 + 2) * 4
+        (2048 + 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
     # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
-        (1024 + 128 * 8) * 32 * (128 + 2) * 4
+        (1024 + 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
 
 
 def test_repack_argument_checks():
