@@ -146,3 +146,30 @@ def test_block_move_argument_checks():
         odd = C.c_void_p(0x1004)
         assert f(odd, FAKE, C.byref(ok), FAKE, 2, FAKE, FAKE, None) == kvq.E_BAD_SHAPE
         assert f(FAKE, FAKE, C.byref(ok), FAKE, 2, odd, FAKE, None) == kvq.E_BAD_SHAPE
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/kvq.h is the boundary for C callers: it must compile as C99 and as C++ on its
+    own, and a C translation unit that calls every entry point must link against the library."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "kvq.h")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                           "-fsyntax-only", "-x", "c", hdr])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                           "-x", "c++", hdr])
+    src = tmp_path / "caller.c"
+    src.write_text('#include "kvq.h"\n#include <stdio.h>\n'
+                   "int main(void) {\n"
+                   "  kvq_cache_desc_t d = {KVQ_INT8_TOKEN_HEAD, 8, 16, 2, 64};\n"
+                   "  if (kvq_cache_bytes(&d) != 8u * 2 * 2 * 16 * 64) return 1;\n"
+                   "  if (kv_quant_write(0, 0, 0, 0, 0, 0, &d, 0) != KVQ_OK) return 2;\n"
+                   "  if (paged_decode_attn(0, 0, 0, &d, 0, 8, 0, 0, 1, 4, 100, 0.125f, 0, 0, 0, 0, 0)"
+                   " != KVQ_OK) return 3;\n"
+                   "  if (kvq_blocks_export(0, 0, &d, 0, 0, 0, 0, 0) != KVQ_OK) return 4;\n"
+                   '  puts(kvq_strerror(KVQ_E_WORKSPACE));\n  return 0;\n}\n')
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(kvq.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                           str(exe), "-L", libdir, "-lkvq", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], stdout=subprocess.PIPE, text=True)
+    assert out.returncode == 0 and out.stdout.strip()
