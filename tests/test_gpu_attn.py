@@ -73,6 +73,8 @@ CASES = [
     ("chunk40_ragged_row_block", [300, 41], 40, 8, 2, 128, 16),       # 160 rows: 128 + 32
     ("prompt_from_an_empty_cache", [130, 130], 130, 4, 1, 128, 16),    # q_len = the whole sequence
     ("chunk512_bs64_d64", [600, 512], 512, 8, 2, 64, 64),
+    ("chunk96_g2_bs256", [700, 300], 96, 4, 2, 128, 256),              # 192 rows, 256-token blocks
+    ("chunk130_g1_bs32_d64", [257, 140], 130, 2, 2, 64, 32),           # 130 rows: 128 + 2
 ]
 
 
