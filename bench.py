@@ -221,6 +221,15 @@ def main():
     torch.cuda.synchronize()
     attn_s = (time.perf_counter() - t0) / args.steps
 
+    # the write alone (the step's newest tokens), for the record: a run of back-to-back calls
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        cache_i, scales_i = caches[i % layers]
+        kvq.kv_quant_write(k_new, v_new, slots_new, cache_i, scales_i, desc, stream=stream)
+    torch.cuda.synchronize()
+    write_s = (time.perf_counter() - t0) / args.steps
+
     if args.calibrate_copy_mib:
         src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -249,6 +258,7 @@ def main():
         "us_per_layer": step_s * 1e6,
         "pct_of_hbm_peak": 100.0 * alg["total"] / step_s / 1e9 / HBM_PEAK_GBPS,
         "attn_only_us_per_layer": attn_s * 1e6,
+        "write_only_us_per_layer": write_s * 1e6,
         "algorithmic_bytes": alg,
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel",
                      "achieved": alg["total"] / kern_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
