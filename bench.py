@@ -245,9 +245,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("bf16 rows, bf16 MFMA operands, f32 accumulate" if wl.mode == 2 else
-                  "u4 codes, f16 MFMA operands, f32 accumulate" if wl.mode == 4 else
-                  "u8 codes, f16 MFMA operands, f32 accumulate"),
+        "dtype": "bf16" if wl.mode == 2 else "f16",   # the matrix instructions' operand type
+        "dtype_detail": ("bf16 rows, bf16 MFMA operands, f32 accumulate and softmax" if wl.mode == 2 else
+                         "u4 codes, f16 MFMA operands, f32 accumulate and softmax" if wl.mode == 4 else
+                         "u8 codes, f16 MFMA operands, f32 accumulate and softmax"),
         "data": "synthetic" if not args.alias_blocks else "INVALID: aliased block tables (diagnostic)",
         "config": {"workload": wl.name, "mode": {0: "int8_token_head", 1: "fp8e4m3_block_head", 2: "bf16_unquantized",
                             3: "fp8e4m3_static_tensor_scales", 4: "int4_token_head"}[wl.mode],
