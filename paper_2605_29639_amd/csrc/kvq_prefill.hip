@@ -51,11 +51,24 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   const int m16 = lane & 15, g4 = lane >> 4;
   const int H = p.num_kv_heads, G = p.group, bs = p.block_size, bs_shift = p.bs_shift;
   const int row_blocks = (p.rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
-  int id = blockIdx.x;
-  const int rb = id % row_blocks;
-  id /= row_blocks;
-  const int h = id % H;
-  const int b = id / H;
+  // Workgroup -> (sequence, kv head, row block).  The hardware hands consecutive workgroups to
+  // the eight XCDs in turn, each with an L2 of its own, and the row blocks of one (sequence,
+  // kv head) read the same codes: they are placed on one XCD (workgroups x, x + 8, x + 16, ...)
+  // so that the codes leave HBM once, not once per XCD.
+  int pair, rb;
+  {
+    const int pairs = p.batch * H, id = blockIdx.x;
+    if (pairs % 8 == 0) {
+      const int x = id & 7, k = id >> 3;
+      pair = x + 8 * (k / row_blocks);
+      rb = k % row_blocks;
+    } else {
+      pair = id / row_blocks;
+      rb = id - pair * row_blocks;
+    }
+  }
+  const int h = pair % H;
+  const int b = pair / H;
   const int L = p.seq_lens[b];
 
   // this wavefront's rows, and how far the workgroup has to walk

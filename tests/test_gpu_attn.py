@@ -75,6 +75,7 @@ CASES = [
     ("chunk512_bs64_d64", [600, 512], 512, 8, 2, 64, 64),
     ("chunk96_g2_bs256", [700, 300], 96, 4, 2, 128, 256),              # 192 rows, 256-token blocks
     ("chunk130_g1_bs32_d64", [257, 140], 130, 2, 2, 64, 32),           # 130 rows: 128 + 2
+    ("chunk140_g2_eight_pairs", [300, 140, 200, 141], 140, 4, 2, 64, 16),  # 8 (seq, head) pairs x 3 row blocks
 ]
 
 
