@@ -131,8 +131,10 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
  *   the codes already stored below the run's first offset are re-encoded as
  *   encode(decode(c) * s_prev / s_new); the new codes are encode(x / s_new) (0x00 when
  *   s_new == 0).  encode = nearest E4M3 value, ties to even, saturating at +-448.
- * A block must not be written by two runs of one call, nor while another sequence's table
- * references it. */
+ *   (Only this mode restricts the order of a call's tokens: a block's scale depends on all of
+ *   the block's tokens.  Every other mode takes the tokens of a call in any order, with skipped
+ *   tokens anywhere, as long as no slot appears twice.)
+ * A block must not be written while another sequence's table references it. */
 int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
                    int32_t num_tokens, void* cache, float* scales,
                    const kvq_cache_desc_t* desc, void* stream);

@@ -493,7 +493,7 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
     const int64_t slot0 = slot_mapping[t0];
     const int o_min = (int)(slot0 & (bs - 1));
     int run = 0;
-    for (int base = 0; base < bs - o_min; base += 64) {  // block sizes reach 128
+    for (int base = 0; base < bs - o_min; base += 64) {  // block sizes reach 256
       const int j = base + lane;
       const bool cont = j < bs - o_min && t0 + j < num_tokens && slot_mapping[t0 + j] == slot0 + j;
       const unsigned long long m = __ballot(cont);
@@ -528,7 +528,11 @@ __device__ inline uint32_t int4_nib(float x, float s) {  // stored nibble of x /
 // One run (consecutive tokens with consecutive slots inside one 16-token sub-block).  A lane
 // owns channels 2 lane and 2 lane + 1.  K: the four lanes of a quad hold the eight codes of one
 // word and combine them with two cross-lane ORs.  V: the lane owns its two channels' 16-token
-// rows (8 bytes each) and rewrites them whole, keeping the nibbles of the other tokens.
+// rows (8 bytes each): a run that fills the sub-block stores them whole; a shorter run clears and
+// sets only its own nibbles with integer atomics on the two 32-bit words, because other runs of
+// the same call (a skipped token in mid sub-block, tokens not in slot order) are handled by
+// other wavefronts and share those words.  The nibbles of different tokens are disjoint, so the
+// result does not depend on the order in which the wavefronts arrive.
 __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                 uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
                                 int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
@@ -567,9 +571,19 @@ __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* 
   if (kv == 1) {
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-      unsigned long long* row =
-          (unsigned long long*)(tile + int4_v_word(off0 - so, 2 * lane + e));
-      *row = run == 16 ? img[e] : ((*row & ~mask) | img[e]);
+      uint8_t* row = tile + int4_v_word(off0 - so, 2 * lane + e);
+      if (run == 16) {
+        *(unsigned long long*)row = img[e];
+      } else {
+#pragma unroll
+        for (int wd = 0; wd < 2; ++wd) {  // tokens 0-7 and 8-15 of the sub-block
+          const uint32_t mw = (uint32_t)(mask >> (32 * wd));
+          if (mw == 0) continue;
+          uint32_t* word = (uint32_t*)row + wd;
+          atomicAnd(word, ~mw);
+          atomicOr(word, (uint32_t)(img[e] >> (32 * wd)));
+        }
+      }
     }
   }
 }

@@ -177,8 +177,10 @@ def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     v[40, :, :] = 0
     v[40, 0, 5] = 0x8000
     slots = wl.slots(0, 0, 48)
-    slots[15] = -1               # skipped tokens (fp8: at the end of a block's run, so each
-    slots[47] = -1               # block still receives one run of consecutive slots)
+    # skipped tokens: for the block-scaled fp8 cache at the end of a block's run (its tokens of
+    # one call must be one run of consecutive slots per block), anywhere for the other formats
+    slots[15 if mode == W.MODE_FP8 else 7] = -1
+    slots[47 if mode == W.MODE_FP8 else 41] = -1
     desc = gpu_desc(wl)
     # stale pool on both sides: NaN codes and a garbage scale everywhere
     oc, osc = oracle.alloc_cache(mode, wl.num_blocks, 16, 2, D)
@@ -302,6 +304,47 @@ def test_random_slot_patterns(mode, num_tokens, bs):
     if mode == W.MODE_FP8_TENSOR:
         osc[:] = (0.07, 0.11)
         scales.copy_(torch.from_numpy(osc))
+    oracle.kv_quant_write(k, v, slots, oc, osc, mode)
+    kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v), torch.from_numpy(slots).cuda(),
+                       cache, scales, desc)
+    torch.cuda.synchronize()
+    assert_pool_equal(None, fetch(cache, scales, desc), (oc, osc))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4])
+@pytest.mark.parametrize("num_tokens", [150, 1500])      # per-run kernels, prefill kernels
+@pytest.mark.parametrize("bs", [16, 64])
+def test_tokens_in_any_order_with_skips_anywhere(mode, num_tokens, bs):
+    """Every format but the block-scaled fp8 takes a call's tokens in any order: distinct slots
+    in fully shuffled token order, so that almost every token is a run of its own and the
+    tokens of one 16-token sub-block are handled by different wavefronts; skipped tokens (-1)
+    anywhere; a stretch left in slot order with single tokens knocked out of it in mid
+    sub-block; a stale pool underneath, so that a lost or misplaced update shows."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    H, D = 2, 128
+    rng = np.random.default_rng(4100 + 10 * mode + num_tokens + bs)
+    nblk = num_tokens // bs + 12
+    # 3/4 of the pool's slots, shuffled; the last quarter of the tokens back in slot order
+    slots = rng.permutation(nblk * bs)[: num_tokens].astype(np.int64)
+    tail = num_tokens // 4
+    slots[-tail:] = np.sort(slots[-tail:])
+    dense = np.arange(5 * bs, 7 * bs, dtype=np.int64)     # two whole blocks in slot order ...
+    slots = np.concatenate([slots[~np.isin(slots, dense)], dense])
+    slots[-2 * bs + 5] = -1                               # ... with holes in mid sub-block
+    slots[-bs + 9] = -1
+    slots[rng.random(len(slots)) < 0.05] = -1
+    T = len(slots)
+    x = (rng.standard_normal((2, T, H, D), dtype=np.float32) *
+         rng.choice([0.01, 1.0, 30.0], size=(2, T, H, 1)).astype(np.float32))
+    k, v = W.to_bf16_bits(x[0]), W.to_bf16_bits(x[1])
+    desc = kvq.make_desc(mode, nblk, bs, H, D)
+    oc, osc = oracle.alloc_cache(mode, nblk, bs, H, D)
+    oc[:] = 0x5A                                          # stale codes and scales on both sides
+    osc[:] = (0.07, 0.11) if mode == W.MODE_FP8_TENSOR else 3.0
+    canon = torch.from_numpy(oc.view(np.int16) if oc.dtype == np.uint16 else oc).cuda()
+    cache = kvq.cache_from_canonical(canon, desc)
+    scales = torch.from_numpy(osc).cuda()
     oracle.kv_quant_write(k, v, slots, oc, osc, mode)
     kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v), torch.from_numpy(slots).cuda(),
                        cache, scales, desc)
