@@ -181,6 +181,26 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       int32_t chunk_tokens, float* out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops
+ * and harnesses that forbid allocation): paged_decode_attn with the library's own scratch buffer
+ * in place of the caller's workspace.  Same arguments otherwise, same kernels, same results.
+ * The buffer is a static device array of KVQ_STATIC_WORKSPACE_BYTES that every GPU the library
+ * runs on holds until the process ends; its device address is looked up on the first call made
+ * on a device (a host-side lookup, not a stream operation; make that first call outside a
+ * graph capture).  The call allocates and frees nothing.
+ * Returns KVQ_E_WORKSPACE if paged_decode_attn_workspace_bytes() for these arguments exceeds
+ * KVQ_STATIC_WORKSPACE_BYTES (the five benchmark configurations need 18 to 35 MB) and
+ * KVQ_E_HIP if the buffer's address cannot be obtained.  All calls on one GPU share the one
+ * buffer: calls that may overlap in time on one GPU (different streams, different threads) race
+ * and must be serialised by the caller.  Nothing in it has to start at zero and its contents
+ * after a call are unspecified. */
+#define KVQ_STATIC_WORKSPACE_BYTES (64u << 20)
+int paged_decode_attn_static(const void* q, const void* cache, const float* scales,
+                             const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                             int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                             int32_t q_len, int32_t num_q_heads, int32_t max_seq_len,
+                             float sm_scale, int32_t chunk_tokens, float* out, void* stream);
+
 /* Conversions between the physical cache above and the canonical
  * [num_blocks][2][num_kv_heads][block_size][head_dim] array of plain codes (int8 two's
  * complement / e4m3 bytes / bf16 bit patterns / int4 pairs); both device, kvq_cache_bytes()

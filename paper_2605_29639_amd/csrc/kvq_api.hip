@@ -2,6 +2,8 @@
 // is made for a bad argument), then the kernel launches on the caller's stream.
 #include <math.h>
 
+#include <mutex>
+
 #include "kvq_internal.h"
 
 namespace {
@@ -124,12 +126,42 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
   return (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
 }
 
-int paged_decode_attn(const void* q, const void* cache, const float* scales,
-                      const kvq_cache_desc_t* desc, const int32_t* block_tables,
-                      int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
-                      int32_t q_len, int32_t num_q_heads, int32_t max_seq_len, float sm_scale,
-                      int32_t chunk_tokens, float* out, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+// The scratch buffer of paged_decode_attn_static: device memory of the library's own, so that
+// the call needs no workspace from a caller who cannot allocate one.  In host code this name is
+// only a handle for hipGetSymbolAddress; the address kernels may use is looked up once per
+// device (each device has its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[KVQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device, filled on the first call made there
+
+// Device address of `scratch` on the current device (nullptr if the lookup fails).
+void* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// Validation and launch shared by paged_decode_attn and paged_decode_attn_static.  With
+// own_scratch the workspace is the library's static buffer, looked up only after every other
+// check has passed (so that bad arguments are rejected without any HIP call).
+int attn_call(const void* q, const void* cache, const float* scales,
+              const kvq_cache_desc_t* desc, const int32_t* block_tables,
+              int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch, int32_t q_len,
+              int32_t num_q_heads, int32_t max_seq_len, float sm_scale, int32_t chunk_tokens,
+              float* out, void* workspace, size_t workspace_bytes, bool own_scratch,
+              void* stream) {
   kvq::AttnPlan plan;
   int err;
   if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
@@ -142,7 +174,11 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
   if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
   const size_t need = (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
-  if (need > 0) {
+  if (own_scratch) {
+    if (need > (size_t)KVQ_STATIC_WORKSPACE_BYTES) return KVQ_E_WORKSPACE;
+    workspace = scratch_on_current_device();
+    if (!workspace) return KVQ_E_HIP;
+  } else if (need > 0) {
     if (!workspace) return KVQ_E_NULLPTR;
     if (workspace_bytes < need) return KVQ_E_WORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return KVQ_E_BAD_SHAPE;
@@ -178,6 +214,31 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
   a.wave_clock = nullptr;
   const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int paged_decode_attn(const void* q, const void* cache, const float* scales,
+                      const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                      int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                      int32_t q_len, int32_t num_q_heads, int32_t max_seq_len, float sm_scale,
+                      int32_t chunk_tokens, float* out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  return attn_call(q, cache, scales, desc, block_tables, max_blocks_per_seq, seq_lens, batch,
+                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, out, workspace,
+                   workspace_bytes, false, stream);
+}
+
+int paged_decode_attn_static(const void* q, const void* cache, const float* scales,
+                             const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                             int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                             int32_t q_len, int32_t num_q_heads, int32_t max_seq_len,
+                             float sm_scale, int32_t chunk_tokens, float* out, void* stream) {
+  return attn_call(q, cache, scales, desc, block_tables, max_blocks_per_seq, seq_lens, batch,
+                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, out, nullptr, 0, true,
+                   stream);
 }
 
 int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,

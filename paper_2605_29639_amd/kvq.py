@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_workspace_bytes",
-           "paged_decode_attn", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
+           "paged_decode_attn", "paged_decode_attn_static", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
            "kvq_blocks_export", "kvq_blocks_import",
            "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
            "kvq_profile_prefill_kernel",
@@ -75,6 +75,9 @@ def lib():
         L.paged_decode_attn.restype = C.c_int
         L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
                                         I32, P, P, SZ, P]
+        L.paged_decode_attn_static.restype = C.c_int
+        L.paged_decode_attn_static.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
+                                               I32, P, P]
         L.kvq_cache_to_canonical.restype = C.c_int
         L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
         L.kvq_cache_from_canonical.restype = C.c_int
@@ -173,6 +176,24 @@ def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != OK:
         raise KvqError(rc, "paged_decode_attn")
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20   # KVQ_STATIC_WORKSPACE_BYTES
+
+
+def paged_decode_attn_static(q, cache, scales, desc, block_tables, seq_lens, q_len, max_seq_len,
+                             sm_scale, out, chunk_tokens=0, stream=None):
+    """paged_decode_attn on the library's own static scratch buffer (no workspace argument)."""
+    import torch
+    batch = seq_lens.shape[0]
+    rc = lib().paged_decode_attn_static(
+        _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
+        _dev(scales, torch.float32, "scales"), C.byref(desc),
+        _dev(block_tables, torch.int32, "block_tables"), block_tables.shape[1],
+        _dev(seq_lens, torch.int32, "seq_lens"), batch, q_len, q.shape[1], max_seq_len,
+        float(sm_scale), chunk_tokens, _dev(out, torch.float32, "out"), _stream(stream))
+    if rc != OK:
+        raise KvqError(rc, "paged_decode_attn_static")
 
 
 def _any(t, dtype, name):

@@ -14,6 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def header_functions():
     text = open(os.path.join(ROOT, "include", "kvq.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"^\s*#.*$", "", text, flags=re.M)      # preprocessor lines
     return re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)
 
 
@@ -122,6 +123,23 @@ def test_attn_argument_checks():
     # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
         (1024 + 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
+
+
+def test_static_scratch_rejects_what_does_not_fit():
+    """Validation on the host: a workspace need above the static buffer's size is an error, not
+    a launch (no device pointer below is ever dereferenced)."""
+    L = kvq.lib()
+    fake = C.c_void_p(0x1000)
+    desc = kvq.make_desc(0, 1 << 20, 16, 8, 128)
+    batch, q_len, Hq, max_len = 4096, 4, 64, 4096
+    assert kvq.workspace_bytes(desc, batch, q_len, Hq, max_len) > kvq.STATIC_WORKSPACE_BYTES
+    rc = L.paged_decode_attn_static(fake, fake, fake, C.byref(desc), fake, 256, fake, batch, q_len,
+                                    Hq, max_len, 0.1, 0, fake, None)
+    assert rc == kvq.E_WORKSPACE
+    assert L.paged_decode_attn_static(fake, fake, fake, C.byref(desc), fake, 256, fake, 0, q_len,
+                                      Hq, max_len, 0.1, 0, fake, None) == kvq.OK
+    assert L.paged_decode_attn_static(None, fake, fake, C.byref(desc), fake, 256, fake, 2, 1,
+                                      Hq, max_len, 0.1, 0, fake, None) == kvq.E_NULLPTR
 
 
 def test_repack_argument_checks():
