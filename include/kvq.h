@@ -12,7 +12,8 @@
  *
  * Conventions for every entry point
  *   - Every pointer marked "device" is GPU memory owned by the caller; the library
- *     allocates nothing, frees nothing and keeps no state between calls.
+ *     allocates nothing, frees nothing and keeps no state between calls (the one exception,
+ *     documented there, is the device address paged_decode_attn_static remembers).
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and return at once: no host synchronisation, no device-to-host copy.
  *   - Return value: KVQ_OK (0) or a negative KVQ_E_* code.  Arguments are validated on the
@@ -231,39 +232,6 @@ int kvq_blocks_export(const void* cache, const float* scales, const kvq_cache_de
 int kvq_blocks_import(const void* packed_cache, const float* packed_scales,
                       const kvq_cache_desc_t* desc, const int32_t* block_ids, int32_t num,
                       void* cache, float* scales, void* stream);
-
-/* Measurement hook, not part of the path: while `before` and `after` (hipEvent_t handles
- * created by the caller) are set, every paged_decode_attn call records `before` on its stream
- * immediately ahead of its split kernel (the kernel that streams the K/V codes) and `after`
- * immediately behind it, so that a benchmark can time that kernel alone.  Pass NULL, NULL to
- * switch the hook off (the initial state).  Process-global and not thread-safe. */
-void kvq_profile_split_events(void* before, void* after);
-
-/* Measurement hook, not part of the path: while switched on, paged_decode_attn launches a
- * read-only twin of its streaming kernel (same work split, addresses, load instructions and
- * software pipeline, the arithmetic replaced by an XOR of the loaded words) and skips the
- * reduce; `out` is not written and the workspace is scribbled on.  Its duration is the
- * read ceiling of this access pattern on the machine at hand.  Process-global; off initially. */
-void kvq_profile_read_ceiling(int on);
-
-/* Measurement hook, not part of the path: while switched on, paged_decode_attn launches only
- * its streaming kernel and skips the reduce (`out` is then incomplete), so that a run of calls
- * is a run of back-to-back streaming kernels that two events can bracket.  Off initially. */
-void kvq_profile_skip_reduce(int on);
-
-/* Measurement and test hook: 0 makes paged_decode_attn use its streaming kernels also for 128
- * and more query rows per kv head, where it otherwise takes the kernel that shares the
- * dequantization among 128 rows.  On initially.  Process-global. */
-void kvq_profile_prefill_kernel(int on);
-
-/* Measurement hook, not part of the path: while `buf` (device, 8 x uint64 per launched
- * wavefront, i.e. 8 * 8 * (number of wavefronts) bytes) is registered, every wavefront of the
- * streaming kernel stores in buf[8*w + k]: the shader clock at entry (k = 0), after its first
- * loads are issued (2), after its steady loop (3), after its last group (4) and after its
- * results are stored (5); its hardware placement XCC_ID << 32 | HW_ID (1); and the constant
- * 100 MHz clock at entry (6) and exit (7).
- * Pass NULL to switch off (the initial state).  Process-global. */
-void kvq_profile_wave_clock(void* buf);
 
 /* Static, never-NULL description of a return code. */
 const char* kvq_strerror(int code);

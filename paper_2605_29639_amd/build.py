@@ -10,27 +10,40 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkvq.so")
+OBJ_PROF = os.path.join(HERE, "_build", "prof")
+LIB_PROF = os.path.join(HERE, "libkvq_prof.so")
 SOURCES = ["kvq_api.hip", "kvq_write.hip", "kvq_attn.hip", "kvq_prefill.hip", "kvq_repack.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 
 
-def _compile(src):
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    subprocess.check_call(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+def _compile(job):
+    src, objdir, defines = job
+    obj = os.path.join(objdir, src.replace(".hip", ".o"))
+    subprocess.check_call(["hipcc", *FLAGS, *defines, "-c", os.path.join(CSRC, src), "-o", obj])
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    tmp = LIB + ".tmp%d" % os.getpid()
+def _link(objs, lib):
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
+
+
+def build(verbose: bool = False) -> str:
+    """libkvq.so (the library) and libkvq_prof.so (the same sources with -DKVQ_PROFILE: the
+    measurement switches of include/kvq_prof.h on top)."""
+    jobs = []
+    for objdir, defines in ((OBJ, []), (OBJ_PROF, ["-DKVQ_PROFILE"])):
+        os.makedirs(objdir, exist_ok=True)
+        jobs += [(src, objdir, defines) for src in SOURCES]
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(_compile, jobs))
+    _link(objs[:len(SOURCES)], LIB)
+    _link(objs[len(SOURCES):], LIB_PROF)
     if verbose:
-        print("built", LIB)
+        print("built", LIB, "and", LIB_PROF)
     return LIB
 
 

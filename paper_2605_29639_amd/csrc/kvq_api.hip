@@ -5,6 +5,9 @@
 #include <mutex>
 
 #include "kvq_internal.h"
+#ifdef KVQ_PROFILE
+#include "../../include/kvq_prof.h"
+#endif
 
 namespace {
 
@@ -299,6 +302,7 @@ int kvq_blocks_import(const void* packed_cache, const float* packed_scales,
                     (float*)packed_scales, false, stream);
 }
 
+#ifdef KVQ_PROFILE  // exported by the measurement build only (include/kvq_prof.h)
 void kvq_profile_split_events(void* before, void* after) {
   kvq::set_profile_events((hipEvent_t)before, (hipEvent_t)after);
 }
@@ -309,6 +313,7 @@ void kvq_profile_skip_reduce(int on) { kvq::set_skip_reduce(on != 0); }
 void kvq_profile_prefill_kernel(int on) { kvq::set_prefill_kernel(on != 0); }
 
 void kvq_profile_wave_clock(void* buf) { kvq::set_wave_clock((unsigned long long*)buf); }
+#endif
 
 const char* kvq_strerror(int code) {
   switch (code) {

@@ -78,14 +78,17 @@ __device__ inline int range_of(int f, int requested, int flat_groups, int num_wa
   return (int)((((long long)f + 1) * num_waves + flat_groups - 1) / flat_groups) - 1;
 }
 
-// CEIL = true builds the read-ceiling twin used for measurement only: same ranges, same
-// addresses, same load instructions and the same pipeline, but the arithmetic is replaced by
-// an XOR of the loaded words (one dword per wavefront is stored so that the loads stay).
+// CEIL and CLOCK are false in the library proper; the measurement build (KVQ_PROFILE) also
+// instantiates
+//   CEIL = true: the read-ceiling twin, with the same ranges, addresses, load instructions and
+//   pipeline, but the arithmetic replaced by an XOR of the loaded words (one dword per lane is
+//   stored so that the loads stay);
+//   CLOCK = true: the kernel itself, every wavefront also storing clock readings at fixed points.
 // (The second launch bound, two wavefronts per SIMD, for the quantized one-tile kernels: they
 // fit either way, but told so the compiler keeps everything in 200-224 VGPRs instead of parking
 // values in AGPRs and copying them back, 1-2 % faster.)
-template <int MODE, int D, int NT, bool CEIL, int DEPTH>
-__global__ __launch_bounds__(64, (NT == 1 && !CEIL && MODE != KVQ_BF16_PLAIN) ? 2 : 1) void
+template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK>
+__global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN) ? 2 : 1) void
 attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
   // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
@@ -105,12 +108,15 @@ attn_stream_kernel(const AttnArgs p) {
   const int m16 = lane & 15, g4 = lane >> 4;
   const int w = blockIdx.x;
   const int B = p.batch, Hp = p.pairs_per_seq;
-  auto stamp = [&](int k) {  // measurement hook, off unless a buffer was registered
-    if (p.wave_clock) {
-      // slots 0..5: shader clock; slots 6, 7: the constant 100 MHz clock at entry and exit
+  auto stamp = [&](int k, bool drain = false) {  // measurement build only
+    if constexpr (CLOCK) {
+      // slots 0..5 and 8..: shader clock; slots 6, 7: the constant 100 MHz clock at entry and
+      // exit.  drain: first wait for every outstanding load, so that the reading marks the
+      // arrival of what was requested so far.
+      if (drain) __builtin_amdgcn_s_waitcnt(0);
       const unsigned long long t =
-          k < 6 ? __builtin_amdgcn_s_memtime() : __builtin_amdgcn_s_memrealtime();
-      if (lane == 0) p.wave_clock[(size_t)w * 8 + k] = t;
+          (k == 6 || k == 7) ? __builtin_amdgcn_s_memrealtime() : __builtin_amdgcn_s_memtime();
+      if (lane == 0) p.wave_clock[(size_t)w * 16 + k] = t;
     }
   };
   stamp(6);
@@ -134,6 +140,7 @@ attn_stream_kernel(const AttnArgs p) {
     }
     if (lane == 0) p.ws_prefix[0] = 0;
   }
+  stamp(8, true);  // the sequence lengths have arrived
   const int f0 = range_begin(w, p.range_groups, flat, p.num_waves);
   const int f1 = range_begin(w + 1, p.range_groups, flat, p.num_waves);
   if (f0 >= f1) return;
@@ -161,6 +168,7 @@ attn_stream_kernel(const AttnArgs p) {
     cur.pr = local / cur.ng;
     cur.g = local - cur.pr * cur.ng;
   }
+  stamp(9);  // the range and its first group are known
   auto advance = [&](Cursor& c) {
     if (++c.g < c.ng) return;
     c.g = 0;
@@ -173,8 +181,8 @@ attn_stream_kernel(const AttnArgs p) {
     } while (c.b < B && c.ng == 0);
   };
 
-  if (p.wave_clock && lane == 0)  // slot 1: where the wavefront runs (XCC_ID << 32 | HW_ID)
-    p.wave_clock[(size_t)w * 8 + 1] =
+  if (CLOCK && lane == 0)  // slot 1: where the wavefront runs (XCC_ID << 32 | HW_ID)
+    p.wave_clock[(size_t)w * 16 + 1] =
         ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
         (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
   const int bs = p.block_size, bs_shift = p.bs_shift, H = p.num_kv_heads, NRG = p.num_row_groups;
@@ -566,6 +574,7 @@ attn_stream_kernel(const AttnArgs p) {
       fetch_entries(nxt, blk_k, blk_v);
       begin_pair(cur);  // q is requested ahead of the codes so that it is not queued behind them
       __builtin_amdgcn_sched_barrier(0);
+      stamp(10, true);  // the first table entries (and q) have arrived
       load_k(kt, sk, sv, vbase, cur, bk0, bv0);
       load_v(vt, vbase);
     }
@@ -749,49 +758,71 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   }
 }
 
-// measurement hooks: events recorded around the streaming kernel (kvq_profile_split_events)
-// and the read-ceiling twin in place of the real kernel (kvq_profile_read_ceiling)
+#ifdef KVQ_PROFILE
+// Measurement build only (libkvq_prof.so): events recorded around the streaming kernel, the
+// read-ceiling twin or the clock-stamping variant in place of the kernel, the reduce skipped,
+// many-row calls kept on the streaming kernels.  Process-global, not thread-safe.
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 bool g_read_ceiling = false;
 bool g_skip_reduce = false;
 bool g_prefill_kernel = true;
 unsigned long long* g_wave_clock = nullptr;
+#endif
+
+// one 16-row tile: two wavefronts per SIMD, single register buffers; two tiles: one
+// wavefront per SIMD, so the loads are double-buffered instead
+// (an unquantized cache has twice the bytes per group: no room for a second buffer)
+template <int MODE, int D, bool CEIL, bool CLOCK>
+void launch_variant(const AttnArgs& a, hipStream_t stream) {
+  constexpr int kDepth = MODE == KVQ_BF16_PLAIN ? 1 : 2;
+  if (a.row_tiles == 1)
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, CEIL, 1, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  else
+    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, CEIL, kDepth, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
+}
 
 template <int MODE, int D>
 hipError_t launch_stream(const AttnArgs& a0, hipStream_t stream) {
+#ifdef KVQ_PROFILE
   AttnArgs a = a0;
   a.wave_clock = g_wave_clock;
   if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
-  // one 16-row tile: two wavefronts per SIMD, single register buffers; two tiles: one
-  // wavefront per SIMD, so the loads are double-buffered instead
   if (g_read_ceiling)
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, true, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  else if (a.row_tiles == 1)
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  else {
-    // an unquantized cache has twice the bytes per group: no room for a second buffer
-    constexpr int kDepth = MODE == KVQ_BF16_PLAIN ? 1 : 2;
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, kDepth>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  }
+    launch_variant<MODE, D, true, false>(a, stream);
+  else if (g_wave_clock)
+    launch_variant<MODE, D, false, true>(a, stream);
+  else
+    launch_variant<MODE, D, false, false>(a, stream);
   const hipError_t e = hipGetLastError();
   if (g_ev_after) (void)hipEventRecord(g_ev_after, stream);
   return e;
+#else
+  launch_variant<MODE, D, false, false>(a0, stream);
+  return hipGetLastError();
+#endif
 }
 
 }  // namespace
 
+#ifdef KVQ_PROFILE
 void set_profile_events(hipEvent_t before, hipEvent_t after) {
   g_ev_before = before;
   g_ev_after = after;
 }
-
 void set_read_ceiling(bool on) { g_read_ceiling = on; }
 void set_skip_reduce(bool on) { g_skip_reduce = on; }
 void set_prefill_kernel(bool on) { g_prefill_kernel = on; }
 void set_wave_clock(unsigned long long* buf) { g_wave_clock = buf; }
+#endif
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
-  if (g_prefill_kernel && !g_read_ceiling && prefill_applies(a)) return launch_prefill(a, stream);
+#ifdef KVQ_PROFILE
+  const bool stream_only = g_read_ceiling || g_skip_reduce;
+  const bool many_rows_kernel = g_prefill_kernel && !g_read_ceiling;
+#else
+  constexpr bool stream_only = false, many_rows_kernel = true;
+#endif
+  if (many_rows_kernel && prefill_applies(a)) return launch_prefill(a, stream);
   hipError_t e;
   if (a.mode == KVQ_INT8_TOKEN_HEAD)
     e = a.head_dim == 128 ? launch_stream<KVQ_INT8_TOKEN_HEAD, 128>(a, stream)
@@ -807,7 +838,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
   else
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);
-  if (e != hipSuccess || g_read_ceiling || g_skip_reduce) return e;
+  if (e != hipSuccess || stream_only) return e;
   const dim3 rgrid((unsigned)((size_t)a.batch * a.num_q_heads), (unsigned)(a.q_len < 64 ? a.q_len : 64));
   if (a.head_dim == 128)
     hipLaunchKernelGGL((attn_reduce_kernel<128>), rgrid, dim3(64), 0, stream, a);

@@ -91,7 +91,7 @@ struct AttnArgs {
   int32_t block_size, bs_shift, head_dim, mode;
   int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;
   float scale_log2;  // sm_scale * log2(e)
-  unsigned long long* wave_clock;  // measurement hook: 8 timestamps per wavefront, or null
+  unsigned long long* wave_clock;  // measurement build: 8 clock readings per wavefront; else null
 };
 
 hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mapping,
@@ -101,11 +101,13 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
 // the kernel for 128 and more query rows per kv head (kvq_prefill.hip)
 bool prefill_applies(const AttnArgs& a);
 hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream);
+#ifdef KVQ_PROFILE  // the measurement build's switches (include/kvq_prof.h)
 void set_prefill_kernel(bool on);
 void set_profile_events(hipEvent_t before, hipEvent_t after);
 void set_read_ceiling(bool on);
 void set_skip_reduce(bool on);
 void set_wave_clock(unsigned long long* buf);
+#endif
 hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
                              const kvq_cache_desc_t& desc, const int32_t* block_ids, int32_t num,
                              void* packed_cache, float* packed_scales, bool to_packed,

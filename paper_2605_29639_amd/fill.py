@@ -30,27 +30,39 @@ def append_inputs(wl, sequences=None):
             torch.from_numpy(np.concatenate(ss)).cuda())
 
 
-def gpu_fill(wl, sequences=None, cache=None, scales=None):
+def gpu_fill(wl, sequences=None, cache=None, scales=None, workers=8):
     """The library writes the workload into a (zeroed unless given) device pool: one call per
     sequence carrying all of its prefill tokens, then, if the workload has an append step, one
-    call carrying the appended tokens of every sequence.  Returns (cache, scales, desc)."""
+    call carrying the appended tokens of every sequence.  Returns (cache, scales, desc).
+    The rows are drawn on `workers` host threads ahead of the calls that consume them."""
     import torch
+    from concurrent.futures import ThreadPoolExecutor
     from . import kvq
     desc = gpu_desc(wl)
     if cache is None:
         cache, scales = kvq.alloc_cache(desc)
         if wl.mode == W.MODE_FP8_TENSOR:
             scales.copy_(torch.tensor(W.STATIC_SCALES, dtype=torch.float32))
-    seqs = range(wl.batch) if sequences is None else sequences
-    for b in seqs:
+    seqs = [b for b in (range(wl.batch) if sequences is None else sequences)
+            if wl.write_range(b)[1] > wl.write_range(b)[0]]
+
+    def draw(b):
         start, stop = wl.write_range(b)
-        if stop > start:
-            k, v = wl.kv_rows(b, start, stop)
+        k, v = wl.kv_rows(b, start, stop)
+        return k, v, wl.slots(b, start, stop)
+
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
+        ahead = 2 * max(1, workers)
+        pending = [pool.submit(draw, b) for b in seqs[:ahead]]
+        for i in range(len(seqs)):
+            k, v, slots = pending[i].result()
+            pending[i] = None
+            if i + ahead < len(seqs):
+                pending.append(pool.submit(draw, seqs[i + ahead]))
             kvq.kv_quant_write(bits_to_bf16_tensor(k), bits_to_bf16_tensor(v),
-                               torch.from_numpy(wl.slots(b, start, stop)).cuda(), cache, scales,
-                               desc)
+                               torch.from_numpy(slots).cuda(), cache, scales, desc)
     if wl.append_tokens:
-        k, v, slots = append_inputs(wl, seqs)
+        k, v, slots = append_inputs(wl, range(wl.batch) if sequences is None else sequences)
         kvq.kv_quant_write(k, v, slots, cache, scales, desc)
     torch.cuda.synchronize()
     return cache, scales, desc

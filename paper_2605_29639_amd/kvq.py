@@ -21,10 +21,11 @@ EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_workspace_bytes",
            "paged_decode_attn", "paged_decode_attn_static", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
            "kvq_blocks_export", "kvq_blocks_import",
-           "kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
-           "kvq_profile_prefill_kernel",
-           "kvq_profile_wave_clock",
            "kvq_strerror")
+# what the measurement build (libkvq_prof.so, include/kvq_prof.h) exports on top
+PROF_EXPORTS = ("kvq_profile_split_events", "kvq_profile_read_ceiling", "kvq_profile_skip_reduce",
+                "kvq_profile_prefill_kernel", "kvq_profile_wave_clock")
+PROF_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq_prof.so")
 
 
 class CacheDesc(C.Structure):
@@ -53,39 +54,39 @@ class KvqError(RuntimeError):
 
 
 _lib = None
+_prof_lib = None
 
 
-def lib():
-    """The loaded shared library (raw ctypes handle)."""
-    global _lib
-    if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(
-                "%s is not built: run `python -m paper_2605_29639_amd.build` "
-                "(there is no CPU fallback)" % LIB_PATH)
-        L = C.CDLL(LIB_PATH)
-        P, I32, SZ = C.c_void_p, C.c_int32, C.c_size_t
-        D = C.POINTER(CacheDesc)
-        L.kvq_cache_bytes.restype, L.kvq_cache_bytes.argtypes = SZ, [D]
-        L.kvq_scales_bytes.restype, L.kvq_scales_bytes.argtypes = SZ, [D]
-        L.kv_quant_write.restype = C.c_int
-        L.kv_quant_write.argtypes = [P, P, P, I32, P, P, D, P]
-        L.paged_decode_attn_workspace_bytes.restype = SZ
-        L.paged_decode_attn_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32]
-        L.paged_decode_attn.restype = C.c_int
-        L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
-                                        I32, P, P, SZ, P]
-        L.paged_decode_attn_static.restype = C.c_int
-        L.paged_decode_attn_static.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
-                                               I32, P, P]
-        L.kvq_cache_to_canonical.restype = C.c_int
-        L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
-        L.kvq_cache_from_canonical.restype = C.c_int
-        L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
-        L.kvq_blocks_export.restype = C.c_int
-        L.kvq_blocks_export.argtypes = [P, P, D, P, I32, P, P, P]
-        L.kvq_blocks_import.restype = C.c_int
-        L.kvq_blocks_import.argtypes = [P, P, D, P, I32, P, P, P]
+def _load(path, prof):
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "%s is not built: run `python -m paper_2605_29639_amd.build` "
+            "(there is no CPU fallback)" % path)
+    L = C.CDLL(path)
+    P, I32, SZ = C.c_void_p, C.c_int32, C.c_size_t
+    D = C.POINTER(CacheDesc)
+    L.kvq_cache_bytes.restype, L.kvq_cache_bytes.argtypes = SZ, [D]
+    L.kvq_scales_bytes.restype, L.kvq_scales_bytes.argtypes = SZ, [D]
+    L.kv_quant_write.restype = C.c_int
+    L.kv_quant_write.argtypes = [P, P, P, I32, P, P, D, P]
+    L.paged_decode_attn_workspace_bytes.restype = SZ
+    L.paged_decode_attn_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32]
+    L.paged_decode_attn.restype = C.c_int
+    L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
+                                    I32, P, P, SZ, P]
+    L.paged_decode_attn_static.restype = C.c_int
+    L.paged_decode_attn_static.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
+                                           I32, P, P]
+    L.kvq_cache_to_canonical.restype = C.c_int
+    L.kvq_cache_to_canonical.argtypes = [P, P, D, P]
+    L.kvq_cache_from_canonical.restype = C.c_int
+    L.kvq_cache_from_canonical.argtypes = [P, P, D, P]
+    L.kvq_blocks_export.restype = C.c_int
+    L.kvq_blocks_export.argtypes = [P, P, D, P, I32, P, P, P]
+    L.kvq_blocks_import.restype = C.c_int
+    L.kvq_blocks_import.argtypes = [P, P, D, P, I32, P, P, P]
+    L.kvq_strerror.restype, L.kvq_strerror.argtypes = C.c_char_p, [C.c_int]
+    if prof:
         L.kvq_profile_split_events.restype = None
         L.kvq_profile_split_events.argtypes = [P, P]
         L.kvq_profile_skip_reduce.restype = None
@@ -96,9 +97,24 @@ def lib():
         L.kvq_profile_wave_clock.argtypes = [P]
         L.kvq_profile_read_ceiling.restype = None
         L.kvq_profile_read_ceiling.argtypes = [C.c_int]
-        L.kvq_strerror.restype, L.kvq_strerror.argtypes = C.c_char_p, [C.c_int]
-        _lib = L
+    return L
+
+
+def lib():
+    """The loaded library (raw ctypes handle)."""
+    global _lib
+    if _lib is None:
+        _lib = _load(LIB_PATH, False)
     return _lib
+
+
+def prof_lib():
+    """The measurement build of the library (benchmarks and tests only): every entry point of
+    lib() plus the switches of include/kvq_prof.h.  Pass it as `L=` to the wrappers below."""
+    global _prof_lib
+    if _prof_lib is None:
+        _prof_lib = _load(PROF_LIB_PATH, True)
+    return _prof_lib
 
 
 def strerror(code):
@@ -141,9 +157,9 @@ def alloc_cache(desc, device="cuda", zero=True):
     return cache, scales
 
 
-def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None):
+def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None, L=None):
     import torch
-    rc = lib().kv_quant_write(_dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
+    rc = (L or lib()).kv_quant_write(_dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
                               _dev(slot_mapping, torch.int64, "slot_mapping"), k.shape[0],
                               _dev(cache, torch.uint8, "cache"),
                               _dev(scales, torch.float32, "scales"), C.byref(desc),
@@ -164,10 +180,10 @@ def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0
 
 
 def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max_seq_len,
-                      sm_scale, out, workspace, chunk_tokens=0, stream=None):
+                      sm_scale, out, workspace, chunk_tokens=0, stream=None, L=None):
     import torch
     batch = seq_lens.shape[0]
-    rc = lib().paged_decode_attn(
+    rc = (L or lib()).paged_decode_attn(
         _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
         _dev(scales, torch.float32, "scales"), C.byref(desc),
         _dev(block_tables, torch.int32, "block_tables"), block_tables.shape[1],

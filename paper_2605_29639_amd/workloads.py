@@ -130,8 +130,11 @@ class Workload:
         kv = self.unique_tokens() * H * per_token_head
         rows = self.batch * self.q_len * self.num_q_heads * D
         tables = int(((self.seq_lens.astype(np.int64) + bs - 1) // bs).sum()) * 4
+        total = kv + rows * 6.0 + tables + 4.0 * self.batch
+        # "logical": a shared prefix counted once per sequence that reads it
+        logical_kv = int(self.seq_lens.astype(np.int64).sum()) * H * per_token_head
         return {"kv": kv, "q_out": rows * 6.0, "tables": tables + 4.0 * self.batch,
-                "total": kv + rows * 6.0 + tables + 4.0 * self.batch}
+                "total": total, "logical_total": total - kv + logical_kv}
 
 
 def _tables(rng, seq_lens, block_size, shared_prefix=0, pool_factor=2):

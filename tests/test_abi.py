@@ -11,8 +11,8 @@ from paper_2605_29639_amd import kvq
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "kvq.h")).read()
+def header_functions(name="kvq.h"):
+    text = open(os.path.join(ROOT, "include", name)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"^\s*#.*$", "", text, flags=re.M)      # preprocessor lines
     return re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)
@@ -24,6 +24,17 @@ def test_library_loads_and_exports_every_declared_function():
     L = kvq.lib()
     for n in names:
         assert getattr(L, n) is not None
+
+
+def test_measurement_build_exports_the_library_plus_its_switches_and_the_library_none_of_them():
+    prof = header_functions("kvq_prof.h")
+    assert set(prof) == set(kvq.PROF_EXPORTS) and len(prof) == len(kvq.PROF_EXPORTS)
+    P = kvq.prof_lib()
+    for n in list(kvq.EXPORTS) + prof:
+        assert getattr(P, n) is not None
+    L = C.CDLL(kvq.LIB_PATH)
+    for n in prof:
+        assert not hasattr(L, n), "%s must not be exported by the library proper" % n
 
 
 def test_strerror_is_static_text_for_any_code():
@@ -175,6 +186,8 @@ def test_header_is_plain_c(tmp_path):
                            "-fsyntax-only", "-x", "c", hdr])
     subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
                            "-x", "c++", hdr])
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                           "-fsyntax-only", "-x", "c", os.path.join(ROOT, "include", "kvq_prof.h")])
     src = tmp_path / "caller.c"
     src.write_text('#include "kvq.h"\n#include <stdio.h>\n'
                    "int main(void) {\n"
