@@ -44,38 +44,78 @@ struct Cursor {
   int b, pr, g, ng, L;
 };
 
-__device__ inline int wave_sum(int v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+// Cross-lane scans and reductions on the DPP network (no LDS round trips): Hillis-Steele
+// inside each row of 16 lanes (row_shr 1, 2, 4, 8), then the last lane of row 0 / row 2 into
+// row 1 / row 3 (row_bcast:15) and lane 31 into rows 2 and 3 (row_bcast:31).  Lanes a step does
+// not reach receive the operation's identity.  Lane 63 ends up holding the reduction.
+template <class Op>
+__device__ inline int dpp_scan_bits(int v, int identity, Op op) {
+#define KVQ_DPP_STEP(CTRL, ROWS) \
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, CTRL, ROWS, 0xF, false))
+  KVQ_DPP_STEP(0x111, 0xF);  // row_shr:1
+  KVQ_DPP_STEP(0x112, 0xF);  // row_shr:2
+  KVQ_DPP_STEP(0x114, 0xF);  // row_shr:4
+  KVQ_DPP_STEP(0x118, 0xF);  // row_shr:8
+  KVQ_DPP_STEP(0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+  KVQ_DPP_STEP(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+#undef KVQ_DPP_STEP
   return v;
 }
+__device__ inline int wave_incl_scan(int v) {
+  return dpp_scan_bits(v, 0, [](int a, int b) { return a + b; });
+}
+__device__ inline int lane_value(int v, int lane_index) {  // lane_index wave-uniform
+  return __builtin_amdgcn_readlane(v, lane_index);
+}
+__device__ inline float lane_value(float v, int lane_index) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane_index));
+}
+__device__ inline int wave_sum(int v) { return lane_value(wave_incl_scan(v), 63); }
 __device__ inline float wave_sum_f(float v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
+  const int r = dpp_scan_bits(__float_as_int(v), 0, [](int a, int b) {
+    return __float_as_int(__int_as_float(a) + __int_as_float(b));
+  });
+  return __int_as_float(__builtin_amdgcn_readlane(r, 63));
 }
-__device__ inline int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) {
-    const int o = __shfl_up(v, s, 64);
-    v += (lane >= s) ? o : 0;
-  }
-  return v;
+__device__ inline float wave_max_f(float v) {
+  const int r = dpp_scan_bits(__float_as_int(v), __float_as_int(-INFINITY), [](int a, int b) {
+    return __float_as_int(fmaxf(__int_as_float(a), __int_as_float(b)));
+  });
+  return __int_as_float(__builtin_amdgcn_readlane(r, 63));
 }
-__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// First flat group of wavefront w's range.  With a caller-given granule every range has
-// `requested` groups; otherwise the list is cut into num_waves ranges whose sizes differ by at
-// most one group (floor(w * flat / num_waves)), so that every compute unit, which holds the
-// same number of wavefronts, streams the same number of bytes.
-__device__ inline int range_begin(int w, int requested, int flat_groups, int num_waves) {
-  if (requested > 0) return (int)min((long long)w * requested, (long long)flat_groups);
-  return (int)(((long long)w * flat_groups) / num_waves);
+// How the flat list of `flat` groups is cut into wavefront ranges.  With a caller-given granule
+// every range has `requested` groups; otherwise the list is cut into num_waves ranges whose
+// sizes differ by at most one group, range w starting at floor(w * flat / num_waves), so that
+// every compute unit, which holds the same number of wavefronts, streams the same number of
+// bytes.  That floor is evaluated as w * q + floor(w * r / num_waves) with flat = q * num_waves
+// + r: 32-bit arithmetic only (num_waves is below 2^16, so w * r is below 2^32).
+struct Split {
+  int requested, flat, num_waves, q, r;
+};
+__device__ inline Split make_split(int requested, int flat, int num_waves) {
+  Split s;
+  s.requested = requested;
+  s.flat = flat;
+  s.num_waves = num_waves;
+  s.q = flat / num_waves;
+  s.r = flat - s.q * num_waves;
+  return s;
 }
-// The wavefront whose range holds flat group f.
-__device__ inline int range_of(int f, int requested, int flat_groups, int num_waves) {
-  if (requested > 0) return f / requested;
-  return (int)((((long long)f + 1) * num_waves + flat_groups - 1) / flat_groups) - 1;
+// First flat group of wavefront w's range (0 <= w <= num_waves).
+__device__ inline int range_begin(const Split& s, int w) {
+  if (s.requested > 0) return (int)min((long long)w * s.requested, (long long)s.flat);
+  return w * s.q + (int)(((uint32_t)w * (uint32_t)s.r) / (uint32_t)s.num_waves);
+}
+// The wavefront whose range holds flat group f (0 <= f < flat): the w with
+// range_begin(w) <= f < range_begin(w + 1), found from an estimate and at most a few steps.
+__device__ inline int range_of(const Split& s, int f) {
+  if (s.requested > 0) return f / s.requested;
+  int w = (int)(((float)f + 0.5f) * ((float)s.num_waves / (float)s.flat));
+  w = min(max(w, 0), s.num_waves - 1);
+  while (range_begin(s, w) > f) --w;
+  while (w + 1 < s.num_waves && range_begin(s, w + 1) <= f) ++w;
+  return w;
 }
 
 // CEIL and CLOCK are false in the library proper; the measurement build (KVQ_PROFILE) also
@@ -124,47 +164,74 @@ attn_stream_kernel(const AttnArgs p) {
   const int32_t* __restrict__ seq_lens = p.seq_lens;
 
   // ---- this wave's range [f0, f1) of the flat list, and where it starts ----
-  int total = 0;
-  for (int k0 = 0; k0 < B; k0 += 64) {
-    const int i = k0 + lane;
-    total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
-  }
-  const int flat = uni(wave_sum(total)) * Hp;
-  if (!CEIL && w == 0) {  // for the reduce: 64-token groups of the sequences before each one
-    int base = 0;
+  Cursor cur;
+  int f0, f1;
+  if (B <= 64) {
+    // lane i holds sequence i: one load and one scan give the list's length, the prefix sums
+    // the reduce wants and, by a ballot, the sequence this wave's range starts in
+    const int Li = lane < B ? seq_lens[lane] : 0;
+    const int incl = wave_incl_scan((Li + 63) >> 6);
+    const int flat = lane_value(incl, 63) * Hp;
+    if (!CEIL && w == 0) {
+      if (lane < B) p.ws_prefix[lane + 1] = incl;
+      if (lane == 0) p.ws_prefix[0] = 0;
+    }
+    stamp(8, true);  // the sequence lengths have arrived
+    const Split split = make_split(p.range_groups, flat, p.num_waves);
+    f0 = range_begin(split, w);
+    f1 = range_begin(split, w + 1);
+    if (f0 >= f1) return;
+    // sequences wholly before f0 (lanes past the batch hold the total: never counted)
+    const int cnt = __popcll(__ballot(incl * Hp <= f0));
+    const int before = cnt ? lane_value(incl, cnt - 1) : 0;
+    cur.b = cnt;
+    cur.L = lane_value(Li, cnt);
+    cur.ng = (cur.L + 63) >> 6;
+    const int local = f0 - before * Hp;
+    cur.pr = local / cur.ng;
+    cur.g = local - cur.pr * cur.ng;
+  } else {
+    int total = 0;
     for (int k0 = 0; k0 < B; k0 += 64) {
       const int i = k0 + lane;
-      const int incl = wave_incl_scan((i < B) ? (seq_lens[i] + 63) >> 6 : 0, lane);
-      if (i < B) p.ws_prefix[i + 1] = base + incl;
-      base += __shfl(incl, 63, 64);
+      total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
     }
-    if (lane == 0) p.ws_prefix[0] = 0;
-  }
-  stamp(8, true);  // the sequence lengths have arrived
-  const int f0 = range_begin(w, p.range_groups, flat, p.num_waves);
-  const int f1 = range_begin(w + 1, p.range_groups, flat, p.num_waves);
-  if (f0 >= f1) return;
-
-  Cursor cur;
-  {
+    const int flat = wave_sum(total) * Hp;
+    if (!CEIL && w == 0) {  // for the reduce: 64-token groups of the sequences before each one
+      int base = 0;
+      for (int k0 = 0; k0 < B; k0 += 64) {
+        const int i = k0 + lane;
+        const int incl = wave_incl_scan((i < B) ? (seq_lens[i] + 63) >> 6 : 0);
+        if (i < B) p.ws_prefix[i + 1] = base + incl;
+        base += lane_value(incl, 63);
+      }
+      if (lane == 0) p.ws_prefix[0] = 0;
+    }
+    stamp(8, true);
+    const Split split = make_split(p.range_groups, flat, p.num_waves);
+    f0 = range_begin(split, w);
+    f1 = range_begin(split, w + 1);
+    if (f0 >= f1) return;
     int base = 0, b0 = 0, before = 0, L0 = 0;
     for (int k0 = 0; k0 < B; k0 += 64) {
       const int i = k0 + lane;
       const int Li = (i < B) ? seq_lens[i] : 0;
-      const int incl = wave_incl_scan((Li + 63) >> 6, lane);
-      const int cnt = __popcll(__ballot((base + incl) * Hp <= f0));  // sequences wholly before f0
-      if (cnt < 64) {
+      const int incl = wave_incl_scan((Li + 63) >> 6);
+      // sequences of this piece wholly before f0 (f0 lies inside the list, so the piece that
+      // holds its sequence is reached)
+      const int cnt = __popcll(__ballot(i < B && (base + incl) * Hp <= f0));
+      if (cnt < 64 && k0 + cnt < B) {
         b0 = k0 + cnt;
-        before = base + (cnt ? __shfl(incl, cnt - 1, 64) : 0);
-        L0 = __shfl(Li, cnt, 64);
+        before = base + (cnt ? lane_value(incl, cnt - 1) : 0);
+        L0 = lane_value(Li, cnt);
         break;
       }
-      base += __shfl(incl, 63, 64);
+      base += lane_value(incl, 63);
     }
-    cur.b = uni(b0);
-    cur.L = uni(L0);
+    cur.b = b0;
+    cur.L = L0;
     cur.ng = (cur.L + 63) >> 6;
-    const int local = f0 - uni(before) * Hp;
+    const int local = f0 - before * Hp;
     cur.pr = local / cur.ng;
     cur.g = local - cur.pr * cur.ng;
   }
@@ -688,68 +755,85 @@ attn_stream_kernel(const AttnArgs p) {
 
 // ---- log-sum-exp merge of a pair's partials: one wavefront per (sequence, query head) and
 // slice of the sequence's query tokens (blockIdx.y; up to 64 slices, so a handful of tokens get
-// a wavefront each), each lane owning D/64 channels.  Where the pair lies in the flat list
-// comes from the prefix sums the streaming kernel's first wavefront left in the workspace (a
-// scan of seq_lens in every one of these wavefronts would cost batch^2 * heads loads); which
-// wavefront ranges cover it is arithmetic; the (max, sum) pairs of up to 64 ranges are fetched
-// by 64 lanes at once, so the chain of dependent memory round trips stays short. ----
+// a wavefront each), each lane owning D/64 channels.  The kernel is a chain of memory round
+// trips behind a launch, so it is written to keep that chain short: where the pair lies in the
+// flat list comes from the prefix sums the streaming kernel's first wavefront left in the
+// workspace (one round trip; a scan of seq_lens in every one of these wavefronts would cost
+// batch^2 * heads loads); which wavefront ranges cover it is 32-bit arithmetic; then the (max,
+// sum) pairs of up to 64 covering ranges, one per lane, and the first eight ranges' accumulator
+// rows are requested together (one more round trip for a pair cut into at most eight pieces);
+// further rows follow eight at a time. ----
 template <int D>
 __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   constexpr int E = D / 64;
+  constexpr int NB = 8;  // accumulator rows requested at once
   typedef float floatE __attribute__((ext_vector_type(E)));
+  typedef float float2v __attribute__((ext_vector_type(2)));
   const int hq = blockIdx.x % p.num_q_heads;
   const int b = blockIdx.x / p.num_q_heads;
   const int lane = threadIdx.x;
   // where the sequence lies in the flat list: the prefix sums the streaming kernel left
-  const int before = p.ws_prefix[b], total = p.ws_prefix[p.batch];
+  const int before = p.ws_prefix[b], next = p.ws_prefix[b + 1], total = p.ws_prefix[p.batch];
   const int Hp = p.pairs_per_seq;
-  const int flat = total * Hp;
+  const Split split = make_split(p.range_groups, total * Hp, p.num_waves);
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
-  const int ng = p.ws_prefix[b + 1] - before;
+  const int ng = next - before;
+  const float* __restrict__ ws_acc = p.ws_acc + lane * E;
+  const float2v* __restrict__ ws_ml = (const float2v*)p.ws_ml;
   for (int j = blockIdx.y; j < p.q_len; j += gridDim.y) {
     const int r = j * p.group + (hq - h * p.group);
     const int rg = r / rt, rl = r - rg * rt;
     const int pr = h * p.num_row_groups + rg;
     const int start = before * Hp + pr * ng;
-    const int w_first = range_of(start, p.range_groups, flat, p.num_waves);
-    const int w_last = range_of(start + ng - 1, p.range_groups, flat, p.num_waves);
+    const int w_first = range_of(split, start);
+    const int w_last = range_of(split, start + ng - 1);
     if (w_first == w_last) continue;  // the streaming kernel already wrote the final rows
     const size_t pair = (size_t)b * Hp + pr;
+    const int n = w_last - w_first + 1;
+    auto row_of = [&](int w) { return ((size_t)w + pair) * rt + rl; };
+    // (max, sum) of range w, or (-inf, 0) for a range that is empty and left no partial
+    auto max_sum = [&](int w) {
+      const bool live = w <= w_last && range_begin(split, w) < range_begin(split, w + 1);
+      return live ? ws_ml[row_of(w)] : float2v{-INFINITY, 0.0f};
+    };
+    auto load_rows = [&](floatE (&a)[NB], int w0, int count) {
+#pragma unroll
+      for (int k = 0; k < NB; ++k)
+        if (k < count) a[k] = *(const floatE*)(ws_acc + row_of(w0 + k) * D);
+    };
+    floatE a_first[NB];
+    load_rows(a_first, w_first, n);
 
     // pass 1: the maximum over all partials
-    float M = -INFINITY;
-    for (int w0 = w_first; w0 <= w_last; w0 += 64) {
-      const int w = w0 + lane;
-      // wavefronts whose range is empty left no partial
-      const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
-                                           range_begin(w + 1, p.range_groups, flat, p.num_waves);
-      const float m = live ? p.ws_ml[(((size_t)w + pair) * rt + rl) * 2] : -INFINITY;
-      M = fmaxf(M, m);
-    }
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) M = fmaxf(M, __shfl_xor(M, s, 64));
+    const float2v ml_first = max_sum(w_first + lane);
+    float M = ml_first[0];
+    for (int w0 = w_first + 64; w0 <= w_last; w0 += 64) M = fmaxf(M, max_sum(w0 + lane)[0]);
+    M = wave_max_f(M);
 
     // pass 2: weights, denominator and the weighted sum of the accumulators
     floatE num = {};
     float den = 0.0f;
     for (int w0 = w_first; w0 <= w_last; w0 += 64) {
-      const int w = w0 + lane;
-      const bool live = w <= w_last && range_begin(w, p.range_groups, flat, p.num_waves) <
-                                           range_begin(w + 1, p.range_groups, flat, p.num_waves);
-      float wgt = 0.0f;
-      if (live) {
-        const size_t row = ((size_t)w + pair) * rt + rl;
-        wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - M);
-        den += wgt * p.ws_ml[row * 2 + 1];
-      }
-      const int n = min(64, w_last - w0 + 1);
-      for (int k = 0; k < n; ++k) {
-        const float wk = __shfl(wgt, k, 64);
-        if (wk == 0.0f) continue;  // empty range (or a partial that carries no weight)
-        const size_t row = ((size_t)(w0 + k) + pair) * rt + rl;
-        const floatE a = *(const floatE*)(p.ws_acc + row * D + lane * E);
-        num += wk * a;
+      const float2v ml = w0 == w_first ? ml_first : max_sum(w0 + lane);
+      const float wgt = __builtin_amdgcn_exp2f(ml[0] - M);  // 0 for an empty range
+      den += wgt * ml[1];
+      const int count = min(64, w_last - w0 + 1);
+      for (int k0 = 0; k0 < count; k0 += NB) {
+        floatE a[NB];
+        if (w0 == w_first && k0 == 0) {
+#pragma unroll
+          for (int k = 0; k < NB; ++k) a[k] = a_first[k];
+        } else {
+          load_rows(a, w0 + k0, count - k0);
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+          if (k0 + k >= count) break;
+          const float wk = lane_value(wgt, k0 + k);
+          // (an empty range's row was never written: it must not enter even with weight 0)
+          if (wk != 0.0f) num += wk * a[k];
+        }
       }
     }
     den = wave_sum_f(den);
