@@ -23,6 +23,12 @@
  *   - Not checked (the caller's contract): block ids and slots in range; no duplicate slot
  *     within one call; no NaN/Inf in k, v, q; |q| <= 65504; q_len <= seq_lens[b] <= max_seq_len;
  *     block-table entries valid for every block below ceil(seq_lens[b] / block_size).
+ *   - With KVQ_DEBUG=1 in the environment (read at every call) kv_quant_write and
+ *     paged_decode_attn first check on the device what they would otherwise follow blindly:
+ *     slots below num_blocks * block_size; q_len <= seq_lens[b] <= max_seq_len; the table
+ *     entries of every block in use inside [0, num_blocks).  A violation returns
+ *     KVQ_E_BAD_INDEX and launches nothing else: no trap, no memory fault.  Such a call waits
+ *     for its stream (it is a debugging aid: slower, and not for use under graph capture).
  */
 #ifndef KVQ_H
 #define KVQ_H
@@ -59,7 +65,8 @@ enum {
   KVQ_E_BAD_MODE = -2,   /* desc->mode is not a kvq_mode_t */
   KVQ_E_BAD_SHAPE = -3,  /* unsupported head_dim / block_size / head counts / lengths */
   KVQ_E_WORKSPACE = -4,  /* workspace_bytes is smaller than paged_decode_attn_workspace_bytes() */
-  KVQ_E_HIP = -5         /* a kernel launch failed (hipGetLastError was not hipSuccess) */
+  KVQ_E_HIP = -5,        /* a kernel launch failed (hipGetLastError was not hipSuccess) */
+  KVQ_E_BAD_INDEX = -6   /* only with KVQ_DEBUG=1: an index read on the device is out of range */
 };
 
 /* Shape of one layer's cache.  K and V of a layer live in one `cache` buffer and one
@@ -152,14 +159,14 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
  *     out = sum_p softmax_p(sm_scale * q . Khat[p]) * Vhat[p],   Xhat = code * scale.
  * Position p lives at block_tables[b][p / block_size], offset p % block_size.
  * seq_lens[b] counts the q_len current tokens, which must already be in the cache.
- *   q             device, bf16 [batch*q_len][num_q_heads][head_dim], read only
+ *   q             device, bf16 [batch*q_len][num_q_heads][head_dim], read only, 16-byte aligned
  *   block_tables  device, int32 [batch][max_blocks_per_seq], read only; entries past a
  *                 sequence's last block are never dereferenced
  *   seq_lens      device, int32 [batch], read only
  *   max_seq_len   host upper bound on seq_lens (sizes the launch grid)
  *   chunk_tokens  split-K granule: tokens of context per wavefront range, a multiple of 64;
  *                 0 = divide the work evenly over the wavefronts the GPU holds at once
- *   out           device, f32 [batch*q_len][num_q_heads][head_dim], written
+ *   out           device, f32 [batch*q_len][num_q_heads][head_dim], written, 16-byte aligned
  *   workspace     device, >= paged_decode_attn_workspace_bytes(...) bytes, 16-byte aligned;
  *                 contents before and after the call are unspecified
  * Split-K: the 64-token groups of all (sequence, kv head) pairs form one flat list that is

@@ -1,6 +1,7 @@
 // extern "C" entry points declared in include/kvq.h: host-side validation first (no HIP call
 // is made for a bad argument), then the kernel launches on the caller's stream.
 #include <math.h>
+#include <stdlib.h>
 
 #include <mutex>
 
@@ -27,10 +28,43 @@ bool desc_ok(const kvq_cache_desc_t* d, int* err) {
     *err = KVQ_E_BAD_SHAPE;
     return false;
   }
+  // a pool beyond 2^46 bytes (64 TiB) is not a real one, and sizes must not wrap
+  const unsigned __int128 bytes = (unsigned __int128)d->num_blocks * 2 * (unsigned)d->num_kv_heads *
+                                  (unsigned)bs * (unsigned)d->head_dim * 2;
+  if (bytes > ((unsigned __int128)1 << 46)) {
+    *err = KVQ_E_BAD_SHAPE;
+    return false;
+  }
   return true;
 }
 
-constexpr int64_t kAutoWaves = 2048;
+// Wavefronts the current GPU holds at once at two per SIMD: compute units x 4 SIMDs x 2 (2048
+// on a whole MI355X; fewer under a partition mode or a CU mask).  Read once per device; where
+// no device can be asked (a machine without a GPU, where only sizes and validation run) the
+// whole chip's figure stands in.
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mutex;
+int g_resident_waves[kMaxDevices] = {};
+
+int64_t auto_waves() {
+  constexpr int64_t kWholeChip = 256 * 4 * 2;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kWholeChip;
+  std::lock_guard<std::mutex> lock(g_device_mutex);
+  if (g_resident_waves[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0 || cus > 4096)
+      return kWholeChip;
+    g_resident_waves[dev] = cus * 4 * 2;
+  }
+  return g_resident_waves[dev];
+}
+
+// the KVQ_DEBUG checks (defined with their kernels further down)
+bool debug_checks();
+int debug_check_slots(const int64_t* slot_mapping, int32_t num_tokens, int64_t num_slots,
+                      hipStream_t stream);
 
 int ilog2(int x) {
   int s = 0;
@@ -49,23 +83,30 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
     return false;
   }
   const int group = num_q_heads / d->num_kv_heads;
-  plan->rows = group * q_len;
-  plan->row_tiles = plan->rows <= 16 ? 1 : 2;
-  plan->num_row_groups = (plan->rows + 16 * plan->row_tiles - 1) / (16 * plan->row_tiles);
-  plan->pairs_per_seq = d->num_kv_heads * plan->num_row_groups;
+  // (every product below is taken in a type that holds it: the arguments are only known to be
+  // non-negative 32-bit numbers at this point)
+  const int64_t rows = (int64_t)group * q_len;
+  const int64_t row_tiles = rows <= 16 ? 1 : 2;
+  const int64_t row_groups = (rows + 16 * row_tiles - 1) / (16 * row_tiles);
+  const int64_t pairs = (int64_t)d->num_kv_heads * row_groups;
   // the flat list of 64-token groups can be no longer than this
-  const int64_t flat_max =
-      (int64_t)batch * ((max_seq_len + 63) / 64) * plan->pairs_per_seq;
-  if (flat_max > 0x7FFFFFFF) {
+  const unsigned __int128 flat_wide =
+      (unsigned __int128)batch * (uint64_t)(((int64_t)max_seq_len + 63) / 64) * (uint64_t)pairs;
+  if (rows > 0x7FFFFFFF || pairs > 0x7FFFFFFF || flat_wide > 0x7FFFFFFF) {
     *err = KVQ_E_BAD_SHAPE;
     return false;
   }
+  const int64_t flat_max = (int64_t)flat_wide;
+  plan->rows = (int32_t)rows;
+  plan->row_tiles = (int32_t)row_tiles;
+  plan->num_row_groups = (int32_t)row_groups;
+  plan->pairs_per_seq = (int32_t)pairs;
   if (chunk_tokens == 0) {
     // even split over as many wavefronts as an MI355X keeps resident at this kernel's
     // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
     // (an unquantized cache needs twice the registers per group: one wavefront per SIMD)
-    const int64_t resident =
-        plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN ? kAutoWaves : kAutoWaves / 2;
+    const int64_t waves = auto_waves();
+    const int64_t resident = plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN ? waves : waves / 2;
     plan->range_groups = 0;
     plan->num_waves = (int32_t)(flat_max < resident ? flat_max : resident);
   } else {
@@ -75,9 +116,9 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   if (plan->num_waves < 1) plan->num_waves = 1;
   // one partial per (wavefront range, pair) crossing: numbered wave + pair index
   const size_t slots = (size_t)plan->num_waves + (size_t)batch * plan->pairs_per_seq;
-  const size_t rows = slots * 16 * plan->row_tiles;
-  plan->acc_floats = rows * d->head_dim;
-  plan->ml_floats = rows * 2;
+  const size_t slot_rows = slots * 16 * plan->row_tiles;
+  plan->acc_floats = slot_rows * d->head_dim;
+  plan->ml_floats = slot_rows * 2;
   plan->prefix_ints = ((size_t)batch + 1 + 3) & ~(size_t)3;
   return true;
 }
@@ -114,6 +155,12 @@ int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
   if (!k || !v || !slot_mapping || !cache) return KVQ_E_NULLPTR;
   if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
   if ((((uintptr_t)k | (uintptr_t)v | (uintptr_t)cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
+  if (debug_checks()) {
+    const int rc = debug_check_slots(slot_mapping, num_tokens,
+                                     (int64_t)desc->num_blocks * desc->block_size,
+                                     (hipStream_t)stream);
+    if (rc != KVQ_OK) return rc;
+  }
   const hipError_t e = kvq::launch_write(k, v, slot_mapping, num_tokens, cache, scales, *desc,
                                          (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
@@ -139,21 +186,96 @@ static __device__ __align__(256) unsigned char scratch[KVQ_STATIC_WORKSPACE_BYTE
 
 namespace {
 
-constexpr int kMaxDevices = 64;
-std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {};  // per device, filled on the first call made there
 
 // Device address of `scratch` on the current device (nullptr if the lookup fails).
 void* scratch_on_current_device() {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  std::lock_guard<std::mutex> lock(g_device_mutex);
   if (!g_scratch_ptr[dev]) {
     void* ptr = nullptr;
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
     g_scratch_ptr[dev] = ptr;
   }
   return g_scratch_ptr[dev];
+}
+
+// ---- KVQ_DEBUG=1 in the environment: the indices the kernels would follow blindly are checked
+// on the device first.  A checking kernel runs ahead of the real one, the call waits for it
+// (so a debug call synchronises with its stream and must not be made under graph capture), and
+// an index out of range becomes KVQ_E_BAD_INDEX instead of a memory fault: nothing is trapped
+// and the real kernel is not launched. ----
+bool debug_checks() {
+  const char* e = getenv("KVQ_DEBUG");
+  return e && e[0] != '\0' && !(e[0] == '0' && e[1] == '\0');
+}
+
+__global__ void check_slots_kernel(const int64_t* __restrict__ slot_mapping, int32_t num_tokens,
+                                   int64_t num_slots, int* __restrict__ word) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= num_tokens) return;
+  if (slot_mapping[t] >= num_slots) {  // (negative = skip the token)
+    atomicOr(&word[0], 1);
+    atomicMin(&word[1], (int)t);
+  }
+}
+
+// entry (b, j): sequence lengths inside [q_len, max_seq_len]; the table entries of every block
+// below ceil(seq_lens[b] / block_size) inside [0, num_blocks)
+__global__ void check_tables_kernel(const int32_t* __restrict__ block_tables,
+                                    const int32_t* __restrict__ seq_lens, int32_t batch,
+                                    int32_t max_blocks_per_seq, int32_t num_blocks,
+                                    int32_t block_size, int32_t q_len, int32_t max_seq_len,
+                                    int* __restrict__ word) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)batch * max_blocks_per_seq) return;
+  const int b = (int)(i / max_blocks_per_seq), j = (int)(i - (int64_t)b * max_blocks_per_seq);
+  const int L = seq_lens[b];
+  if (L < q_len || L > max_seq_len) {
+    if (j == 0) {
+      atomicOr(&word[0], 2);
+      atomicMin(&word[1], b);
+    }
+    return;
+  }
+  if (j >= (L + block_size - 1) / block_size) return;
+  const int e = block_tables[i];
+  if (e < 0 || e >= num_blocks) {
+    atomicOr(&word[0], 4);
+    atomicMin(&word[1], b);
+  }
+}
+
+}  // namespace
+
+static __device__ int debug_word[2];  // [0] what was found (bit set), [1] first token / sequence
+
+namespace {
+
+// Runs `launch_check(word)` on the stream and waits for its verdict.
+template <class F>
+int debug_verdict(hipStream_t stream, F launch_check) {
+  int* word = nullptr;
+  if (hipGetSymbolAddress((void**)&word, HIP_SYMBOL(debug_word)) != hipSuccess) return KVQ_E_HIP;
+  const int init[2] = {0, 0x7FFFFFFF};
+  int found[2] = {0, 0};
+  if (hipMemcpyAsync(word, init, sizeof(init), hipMemcpyHostToDevice, stream) != hipSuccess)
+    return KVQ_E_HIP;
+  launch_check(word);
+  if (hipGetLastError() != hipSuccess) return KVQ_E_HIP;
+  if (hipMemcpyAsync(found, word, sizeof(found), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+      hipStreamSynchronize(stream) != hipSuccess)
+    return KVQ_E_HIP;
+  return found[0] ? KVQ_E_BAD_INDEX : KVQ_OK;
+}
+
+int debug_check_slots(const int64_t* slot_mapping, int32_t num_tokens, int64_t num_slots,
+                      hipStream_t stream) {
+  return debug_verdict(stream, [&](int* word) {
+    hipLaunchKernelGGL(check_slots_kernel, dim3((unsigned)((num_tokens + 255) / 256)), dim3(256), 0,
+                       stream, slot_mapping, num_tokens, num_slots, word);
+  });
 }
 
 // Validation and launch shared by paged_decode_attn and paged_decode_attn_static.  With
@@ -176,6 +298,8 @@ int attn_call(const void* q, const void* cache, const float* scales,
   if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
   if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
   if (!scales && desc->mode != KVQ_BF16_PLAIN) return KVQ_E_NULLPTR;
+  // the kernels read q and the cache and write out in 16-byte pieces
+  if ((((uintptr_t)q | (uintptr_t)cache | (uintptr_t)out) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const size_t need = (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
   if (own_scratch) {
     if (need > (size_t)KVQ_STATIC_WORKSPACE_BYTES) return KVQ_E_WORKSPACE;
@@ -185,6 +309,19 @@ int attn_call(const void* q, const void* cache, const float* scales,
     if (!workspace) return KVQ_E_NULLPTR;
     if (workspace_bytes < need) return KVQ_E_WORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return KVQ_E_BAD_SHAPE;
+  }
+
+  if (debug_checks()) {
+    const int64_t entries = (int64_t)batch * max_blocks_per_seq;
+    if (entries > 0) {
+      const int rc = debug_verdict((hipStream_t)stream, [&](int* word) {
+        hipLaunchKernelGGL(check_tables_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256),
+                           0, (hipStream_t)stream, block_tables, seq_lens, batch,
+                           max_blocks_per_seq, desc->num_blocks, desc->block_size, q_len,
+                           max_seq_len, word);
+      });
+      if (rc != KVQ_OK) return rc;
+    }
   }
 
   kvq::AttnArgs a;
@@ -323,6 +460,7 @@ const char* kvq_strerror(int code) {
     case KVQ_E_BAD_SHAPE: return "unsupported shape or size argument";
     case KVQ_E_WORKSPACE: return "workspace too small";
     case KVQ_E_HIP: return "kernel launch failed";
+    case KVQ_E_BAD_INDEX: return "slot, block-table entry or sequence length out of range (KVQ_DEBUG)";
     default: return "unknown error code";
   }
 }

@@ -429,14 +429,12 @@ attn_stream_kernel(const AttnArgs p) {
       }
   };
 
-  // ---- online softmax of a group: S (logits) -> pb (f16 probabilities x V scale) ----
+  // ---- online softmax of a group: S (logits) -> pb (f16 probabilities x V scale); the body is
+  // online_softmax in kvq_attn_common.h, shared with the many-row kernel.
   // TAIL = some row's causal length ends inside the group: positions past a row's length are
-  // masked and scales of never-written slots are ignored.  The arithmetic on broadcast
-  // operands is kept as separate multiply / add so that the row broadcast rides on the
-  // instruction itself (v_mul_f32_dpp, v_add_f32_dpp) instead of costing moves.
+  // masked and scales of never-written slots are ignored. ----
   auto softmax_impl = [&](auto TAILC, floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
                           Operand (&pb)[NT][2 * EB]) {
-#pragma clang fp contract(off)
     constexpr bool TAIL = decltype(TAILC)::value;
     if constexpr (CEIL) {
       ceil_x ^= __float_as_uint(sk) ^ __float_as_uint(sv);
@@ -452,80 +450,7 @@ attn_stream_kernel(const AttnArgs p) {
       lsv = 0.0f;
       rsv = 0.0f;
     }
-    // logits in base 2, shifted by log2 of the V scale; row maximum
-    float mx[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
-    static_for<16>([&](auto I) {
-      constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        float ze;
-        if constexpr (TOKEN_SCALE) {
-          ze = S[nt][u][i] * row_bcast<tix>(skp);
-          ze = ze + row_bcast<tix>(lsv);
-        } else if constexpr (PLAIN) {
-          ze = S[nt][u][i] * skp;
-        } else {
-          ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
-        }
-        if constexpr (TAIL) ze = (pos0 + 16 * g4 + tix < nrow[nt]) ? ze : -INFINITY;
-        S[nt][u][i] = ze;
-        mx[nt] = fmaxf(mx[nt], ze);
-      }
-    });
-    bool rescale = false;
-    float alpha[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const float m_new = fmaxf(m_run[nt], xor16_max(mx[nt]));
-      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-      alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
-      rescale |= (alpha[nt] != 1.0f);
-      m_run[nt] = m_new;
-      const float msub = m_safe - kPOffset;
-      float lsum = 0.0f;
-      [[maybe_unused]] uint32_t hi_bits[16], lo_bits[16];
-      static_for<16>([&](auto I) {
-        constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
-        const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
-        if constexpr (TOKEN_SCALE) {
-          const float t = pr * row_bcast<tix>(rsv);
-          lsum = lsum + t;
-        } else {
-          lsum = lsum + pr;
-        }
-        if constexpr (PLAIN) {
-          // bf16 keeps 8 bits of a probability: it goes in as two terms, the value cut to
-          // bf16 and the (exactly representable) rest cut to bf16, 16 bits in all
-          hi_bits[tix] = __float_as_uint(pr) & 0xFFFF0000u;
-          lo_bits[tix] = __float_as_uint(pr - __uint_as_float(hi_bits[tix]));
-        } else {
-          pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
-        }
-      });
-      if constexpr (PLAIN) {
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          uintx4 ph, pl;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {  // the upper halves of two tokens' words, packed
-            ph[e] = __builtin_amdgcn_perm(hi_bits[8 * hf + 2 * e + 1], hi_bits[8 * hf + 2 * e], 0x07060302u);
-            pl[e] = __builtin_amdgcn_perm(lo_bits[8 * hf + 2 * e + 1], lo_bits[8 * hf + 2 * e], 0x07060302u);
-          }
-          pb[nt][hf] = __builtin_bit_cast(bf16x8, ph);
-          pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
-        }
-      }
-      if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
-      l_run[nt] = l_run[nt] * alpha[nt] + lsum;
-    }
-    if (__any(rescale)) {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
-    }
+    online_softmax<MODE, NT, DT, TAIL>(S, skp, lsv, rsv, pos0 + 16 * g4, nrow, m_run, l_run, acc, pb);
   };
   auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
                      Operand (&pb)[NT][2 * EB]) {

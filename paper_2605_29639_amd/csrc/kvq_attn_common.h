@@ -92,5 +92,103 @@ __device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
   return r;
 }
 
+// Online softmax of one 64-token group for NT tiles of 16 query rows, shared by the streaming
+// and the many-row kernels.  In: S, the raw contractions K.q in the accumulator layout (lane
+// (row n, sub-block g) holds the 16 tokens of sub-block g); this lane's token's scales as
+// skp = K scale * softmax scale * log2(e), lsv = log2(V scale), rsv = 1 / V scale (per token for
+// the token-scaled formats, the same in every lane otherwise); pos_lane = position of the
+// lane's first token; nrow = causal length of the lane's row per tile.  Out: pb, the
+// probabilities times the V scale as the B operand of P.V (f16 scaled by 2^10, or two bf16
+// terms for an unquantized cache); the running maximum m_run (of logit + lsv, base 2) and sum
+// l_run are updated and acc is rescaled when a maximum moved.
+// TAIL: some row's causal length ends inside the group, so positions are masked.
+// The arithmetic on broadcast operands is kept as separate multiply / add so that the row
+// broadcast rides on the instruction itself (v_mul_f32_dpp, v_add_f32_dpp) instead of costing
+// moves.
+template <int MODE, int NT, int DT, bool TAIL, class Operand, int NP>
+__device__ inline void online_softmax(floatx4 (&S)[NT][4], float skp, float lsv, float rsv,
+                                      int pos_lane, const int (&nrow)[NT], float (&m_run)[NT],
+                                      float (&l_run)[NT], floatx4 (&acc)[NT][DT],
+                                      Operand (&pb)[NT][NP]) {
+#pragma clang fp contract(off)
+  constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;
+  constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
+  constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD || MODE == KVQ_INT4_TOKEN_HEAD;
+  // logits in base 2, shifted by log2 of the V scale; row maximum
+  float mx[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
+  static_for<16>([&](auto I) {
+    constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      float ze;
+      if constexpr (TOKEN_SCALE) {
+        ze = S[nt][u][i] * row_bcast<tix>(skp);
+        ze = ze + row_bcast<tix>(lsv);
+      } else if constexpr (PLAIN) {
+        ze = S[nt][u][i] * skp;
+      } else {
+        ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
+      }
+      if constexpr (TAIL) ze = (pos_lane + tix < nrow[nt]) ? ze : -INFINITY;
+      S[nt][u][i] = ze;
+      mx[nt] = fmaxf(mx[nt], ze);
+    }
+  });
+  bool rescale = false;
+  float alpha[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const float m_new = fmaxf(m_run[nt], xor16_max(mx[nt]));
+    const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+    alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
+    rescale |= (alpha[nt] != 1.0f);
+    m_run[nt] = m_new;
+    const float msub = m_safe - kPOffset;
+    float lsum = 0.0f;
+    [[maybe_unused]] uint32_t hi_bits[16], lo_bits[16];
+    static_for<16>([&](auto I) {
+      constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+      const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
+      if constexpr (TOKEN_SCALE) {
+        const float t = pr * row_bcast<tix>(rsv);
+        lsum = lsum + t;
+      } else {
+        lsum = lsum + pr;
+      }
+      if constexpr (PLAIN) {
+        // bf16 keeps 8 bits of a probability: it goes in as two terms, the value cut to
+        // bf16 and the (exactly representable) rest cut to bf16, 16 bits in all
+        hi_bits[tix] = __float_as_uint(pr) & 0xFFFF0000u;
+        lo_bits[tix] = __float_as_uint(pr - __uint_as_float(hi_bits[tix]));
+      } else {
+        pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
+      }
+    });
+    if constexpr (PLAIN) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        uintx4 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {  // the upper halves of two tokens' words, packed
+          ph[e] = __builtin_amdgcn_perm(hi_bits[8 * hf + 2 * e + 1], hi_bits[8 * hf + 2 * e], 0x07060302u);
+          pl[e] = __builtin_amdgcn_perm(lo_bits[8 * hf + 2 * e + 1], lo_bits[8 * hf + 2 * e], 0x07060302u);
+        }
+        pb[nt][hf] = __builtin_bit_cast(bf16x8, ph);
+        pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
+      }
+    }
+    if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
+    l_run[nt] = l_run[nt] * alpha[nt] + lsum;
+  }
+  if (__any(rescale)) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
+  }
+}
+
 }  // namespace
 }  // namespace kvq

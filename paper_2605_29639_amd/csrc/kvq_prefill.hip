@@ -266,7 +266,6 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     }
   };
   auto softmax_impl = [&](auto TAILC, int g, int half) {
-#pragma clang fp contract(off)
     constexpr bool TAIL = decltype(TAILC)::value;
     const int pos0 = g << 6;
     float skp = p.scale_log2, lsv = 0.0f, rsv = 1.0f;
@@ -276,79 +275,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
       lsv = sc[1];
       rsv = sc[2];
     }
-    float mx[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
-    static_for<16>([&](auto I) {
-      constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        float ze;
-        if constexpr (TOKEN_SCALE) {
-          ze = S[nt][u][i] * row_bcast<tix>(skp);
-          ze = ze + row_bcast<tix>(lsv);
-        } else if constexpr (PLAIN) {
-          ze = S[nt][u][i] * skp;
-        } else {
-          ze = __builtin_fmaf(S[nt][u][i], skp, lsv);
-        }
-        if constexpr (TAIL) ze = (pos0 + 16 * g4 + tix < nrow[nt]) ? ze : -INFINITY;
-        S[nt][u][i] = ze;
-        mx[nt] = fmaxf(mx[nt], ze);
-      }
-    });
-    bool rescale = false;
-    float alpha[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const float m_new = fmaxf(m_run[nt], xor16_max(mx[nt]));
-      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-      alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
-      rescale |= (alpha[nt] != 1.0f);
-      m_run[nt] = m_new;
-      const float msub = m_safe - kPOffset;
-      float lsum = 0.0f;
-      [[maybe_unused]] uint32_t hi_bits[16], lo_bits[16];
-      static_for<16>([&](auto I) {
-        constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
-        const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
-        if constexpr (TOKEN_SCALE) {
-          const float t = pr * row_bcast<tix>(rsv);
-          lsum = lsum + t;
-        } else {
-          lsum = lsum + pr;
-        }
-        if constexpr (PLAIN) {
-          // bf16 keeps 8 bits of a probability: it goes in as two terms, the value cut to
-          // bf16 and the (exactly representable) rest cut to bf16, 16 bits in all
-          hi_bits[tix] = __float_as_uint(pr) & 0xFFFF0000u;
-          lo_bits[tix] = __float_as_uint(pr - __uint_as_float(hi_bits[tix]));
-        } else {
-          pb[nt][tix >> 3][tix & 7] = (_Float16)pr;
-        }
-      });
-      if constexpr (PLAIN) {
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          uintx4 ph, pl;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {  // the upper halves of two tokens' words, packed
-            ph[e] = __builtin_amdgcn_perm(hi_bits[8 * hf + 2 * e + 1], hi_bits[8 * hf + 2 * e], 0x07060302u);
-            pl[e] = __builtin_amdgcn_perm(lo_bits[8 * hf + 2 * e + 1], lo_bits[8 * hf + 2 * e], 0x07060302u);
-          }
-          pb[nt][hf] = __builtin_bit_cast(bf16x8, ph);
-          pb[nt][2 + hf] = __builtin_bit_cast(bf16x8, pl);
-        }
-      }
-      if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
-      l_run[nt] = l_run[nt] * alpha[nt] + lsum;
-    }
-    if (__any(rescale)) {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
-    }
+    online_softmax<MODE, NT, DT, TAIL>(S, skp, lsv, rsv, pos0 + 16 * g4, nrow, m_run, l_run, acc, pb);
   };
   auto pv = [&](int half) {
     // two channel tiles at a time: their four operands are read while the previous pair's

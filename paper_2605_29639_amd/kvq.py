@@ -13,7 +13,7 @@ MODE_BF16 = 2   # KVQ_BF16_PLAIN (unquantized baseline)
 MODE_FP8_TENSOR = 3  # KVQ_FP8E4M3_TENSOR (static per-tensor scales)
 MODE_INT4 = 4    # KVQ_INT4_TOKEN_HEAD (head_dim 128)
 
-OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, -5
+OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP, E_BAD_INDEX = 0, -1, -2, -3, -4, -5, -6
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 
@@ -157,8 +157,34 @@ def alloc_cache(desc, device="cuda", zero=True):
     return cache, scales
 
 
+_pool_sizes = {}   # descriptor fields -> (cache bytes, scales bytes), as the library reports them
+
+
+def _check_pool(cache, scales, desc):
+    """The cache and scales tensors have the sizes the library reports for the descriptor: a
+    smaller buffer would be overrun on the device, which checks nothing."""
+    key = (desc.mode, desc.num_blocks, desc.block_size, desc.num_kv_heads, desc.head_dim)
+    sizes = _pool_sizes.get(key)
+    if sizes is None:
+        sizes = _pool_sizes[key] = (lib().kvq_cache_bytes(desc), lib().kvq_scales_bytes(desc))
+    nbytes, sbytes = sizes
+    if cache is None or cache.numel() * cache.element_size() != nbytes:
+        raise ValueError("cache must hold exactly kvq_cache_bytes(desc) = %d bytes" % nbytes)
+    have = 0 if scales is None else scales.numel() * scales.element_size()
+    if have != sbytes:
+        raise ValueError("scales must hold exactly kvq_scales_bytes(desc) = %d bytes, not %d"
+                         % (sbytes, have))
+
+
 def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None, L=None):
     import torch
+    rows = (k.shape[0], desc.num_kv_heads, desc.head_dim)
+    if tuple(k.shape) != rows or tuple(v.shape) != rows:
+        raise ValueError("k and v must be [num_tokens, %d, %d], not %s and %s"
+                         % (rows[1], rows[2], tuple(k.shape), tuple(v.shape)))
+    if tuple(slot_mapping.shape) != (k.shape[0],):
+        raise ValueError("slot_mapping must be [num_tokens] = [%d]" % k.shape[0])
+    _check_pool(cache, scales, desc)
     rc = (L or lib()).kv_quant_write(_dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
                               _dev(slot_mapping, torch.int64, "slot_mapping"), k.shape[0],
                               _dev(cache, torch.uint8, "cache"),
@@ -166,6 +192,22 @@ def kv_quant_write(k, v, slot_mapping, cache, scales, desc, stream=None, L=None)
                               _stream(stream))
     if rc != OK:
         raise KvqError(rc, "kv_quant_write")
+
+
+def _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, out):
+    """Shapes the device code relies on without checking; returns the batch size."""
+    if seq_lens.dim() != 1:
+        raise ValueError("seq_lens must be [batch]")
+    batch = seq_lens.shape[0]
+    if q.dim() != 3 or q.shape[0] != batch * q_len or q.shape[2] != desc.head_dim:
+        raise ValueError("q must be [batch * q_len, num_q_heads, %d] = [%d, *, %d], not %s"
+                         % (desc.head_dim, batch * q_len, desc.head_dim, tuple(q.shape)))
+    if tuple(out.shape) != tuple(q.shape):
+        raise ValueError("out must have q's shape %s, not %s" % (tuple(q.shape), tuple(out.shape)))
+    if block_tables.dim() != 2 or block_tables.shape[0] != batch:
+        raise ValueError("block_tables must be [batch, max_blocks_per_seq] with batch = %d" % batch)
+    _check_pool(cache, scales, desc)
+    return batch
 
 
 def workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0):
@@ -182,7 +224,10 @@ def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0
 def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max_seq_len,
                       sm_scale, out, workspace, chunk_tokens=0, stream=None, L=None):
     import torch
-    batch = seq_lens.shape[0]
+    batch = _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, out)
+    need = workspace_bytes(desc, batch, q_len, q.shape[1], max_seq_len, chunk_tokens)
+    if batch > 0 and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace holds %d bytes, the call needs %d" % (workspace.numel(), need))
     rc = (L or lib()).paged_decode_attn(
         _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
         _dev(scales, torch.float32, "scales"), C.byref(desc),
@@ -201,7 +246,7 @@ def paged_decode_attn_static(q, cache, scales, desc, block_tables, seq_lens, q_l
                              sm_scale, out, chunk_tokens=0, stream=None):
     """paged_decode_attn on the library's own static scratch buffer (no workspace argument)."""
     import torch
-    batch = seq_lens.shape[0]
+    batch = _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, out)
     rc = lib().paged_decode_attn_static(
         _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
         _dev(scales, torch.float32, "scales"), C.byref(desc),

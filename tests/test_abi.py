@@ -38,7 +38,7 @@ def test_measurement_build_exports_the_library_plus_its_switches_and_the_library
 
 
 def test_strerror_is_static_text_for_any_code():
-    for code in (0, -1, -2, -3, -4, -5, -99, 7):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99, 7):
         assert isinstance(kvq.strerror(code), str) and kvq.strerror(code)
     assert kvq.strerror(0) == "ok"
 
@@ -117,6 +117,8 @@ def test_attn_argument_checks():
     assert attn(L, ok, batch=0) == kvq.OK                  # empty batch: nothing launched
     for name in ("q", "cache", "scales", "tables", "lens", "out"):
         assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
+    for name in ("q", "cache", "out"):                     # read and written in 16-byte pieces
+        assert attn(L, ok, **{name: C.c_void_p(0x1008)}) == kvq.E_BAD_SHAPE
     # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each, and the
     # prefix sums of the sequences' group counts (batch + 1 ints, padded to a multiple of 4)
     need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
@@ -204,3 +206,37 @@ def test_header_is_plain_c(tmp_path):
                            str(exe), "-L", libdir, "-lkvq", "-Wl,-rpath," + libdir])
     out = subprocess.run([str(exe)], stdout=subprocess.PIPE, text=True)
     assert out.returncode == 0 and out.stdout.strip()
+
+
+def test_binding_rejects_shapes_the_device_would_overrun():
+    """The Python binding refuses tensors whose shapes do not fit the descriptor before anything
+    reaches the library (CPU tensors are enough: the checks come first)."""
+    import torch
+    desc = d(nblk=4, bs=16, H=2, D=64)
+    cache = torch.zeros(kvq.lib().kvq_cache_bytes(C.byref(desc)), dtype=torch.uint8)
+    scales = torch.zeros(kvq.lib().kvq_scales_bytes(C.byref(desc)) // 4, dtype=torch.float32)
+    k = torch.zeros((3, 2, 64), dtype=torch.bfloat16)
+    slots = torch.zeros(3, dtype=torch.int64)
+    with pytest.raises(ValueError):
+        kvq.kv_quant_write(k, k[:, :1], slots, cache, scales, desc)          # v: one head short
+    with pytest.raises(ValueError):
+        kvq.kv_quant_write(k, k, slots[:2], cache, scales, desc)             # a slot short
+    with pytest.raises(ValueError):
+        kvq.kv_quant_write(k, k, slots, cache[:-16], scales, desc)           # pool too small
+    with pytest.raises(ValueError):
+        kvq.kv_quant_write(k, k, slots, cache, scales[:-1], desc)
+    q = torch.zeros((2, 4, 64), dtype=torch.bfloat16)
+    out = torch.zeros((2, 4, 64), dtype=torch.float32)
+    bt = torch.zeros((2, 7), dtype=torch.int32)
+    sl = torch.ones(2, dtype=torch.int32)
+    ws = torch.zeros(1 << 16, dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        kvq.paged_decode_attn(q[:1], cache, scales, desc, bt, sl, 1, 100, 0.1, out, ws)
+    with pytest.raises(ValueError):
+        kvq.paged_decode_attn(q, cache, scales, desc, bt, sl, 1, 100, 0.1, out[:, :2], ws)
+    with pytest.raises(ValueError):
+        kvq.paged_decode_attn(q, cache, scales, desc, bt[:1], sl, 1, 100, 0.1, out, ws)
+    with pytest.raises(ValueError):
+        kvq.paged_decode_attn(q, cache, scales, desc, bt, sl, 1, 100, 0.1, out, ws[:64])
+    with pytest.raises(TypeError):                                           # shapes fit: device check
+        kvq.paged_decode_attn(q, cache, scales, desc, bt, sl, 1, 100, 0.1, out, ws)
