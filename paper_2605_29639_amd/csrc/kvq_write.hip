@@ -9,8 +9,10 @@
 //   fp8 per (block, head):  unit = (run, kv head, K|V), a run being the consecutive tokens
 //                           of the call that fall into one cache block;
 //   fp8 under static scales, bf16 rows: as int8 without the scale.
-// Each format has a general routine (any run) and one for whole 16-token sub-blocks, which
-// calls carrying a prompt take (16-byte loads, fp32 rounding with an fp64 decision near ties).
+// Each format has a general routine (any run, one token after another) and one that takes a
+// 16-token sub-block at a time, which calls carrying a prompt use (16-byte loads, fp32 rounding
+// with an fp64 decision near ties; for int8 and fp8 a wavefront does K and V of its window and
+// runs shorter than a sub-block go the same way with the missing rows masked).
 // The decisions that fix an integer (the rounding of x/scale) are taken in fp64: for a bf16
 // x and an fp32 scale the fp64 quotient is either exactly a rounding tie or at least 2^-25
 // (relative 2^-29 for the fp8 midpoints) away from one, so rounding it equals rounding the
@@ -163,68 +165,131 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_kernel(
 // the wavefront fills whole quads; for V the tokens g * (16 / G) + i, so that the lane's bytes
 // of one channel are adjacent in that channel's 16-token row.
 //
-// Rounding x / s: the fp32 product x * rcp(s) is within 2.3e-5 of the exact quotient
-// (|quotient| <= 127, rcp within one ulp, one rounding for the product), so unless it lies
-// within 4e-5 of a half-integer its nearest integer is the exact quotient's; the rare
-// elements that do are decided in fp64 like everywhere else.  The scale is one correctly
-// rounded fp32 division, which equals the fp64 quotient rounded once for every bf16 absmax.
+// Rounding x / s without fp64 and without a branch per element: t = fma(x, rcp(s), 1.5 * 2^23 +
+// 128) is the product rounded once to an integer (the unit in the last place up there is 1,
+// ties go to even) plus 128, so the low byte of t's bit pattern is the stored code.  The
+// product differs from the exact quotient by at most 1.6e-5 (|quotient| <= 127, rcp within one
+// ulp), so t holds the exact quotient's rounding unless the quotient lies within that distance
+// of a half-integer; d = fma(x, rcp(s), -(t - 1.5 * 2^23 - 128)) measures it, and the elements
+// with |d| > 0.5 - 4e-5 (about one in 12 000), like rows whose scale is zero or below the normal
+// fp32 range, are marked in a bit mask and decided in fp64 afterwards, the wavefront skipping
+// every element nobody marked.  The scale is one correctly rounded fp32 division, which equals
+// the fp64 quotient rounded once for every bf16 absmax.
+constexpr float kRoundMagic = 12582912.0f + 128.0f;  // 1.5 * 2^23 + 128
+
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+// largest |bf16| bit pattern among the 8 values of a 16-byte piece
+__device__ inline uint32_t absmax8(const uint4& raw) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  ushort2v m = {0, 0};
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    m = __builtin_elementwise_max(m, __builtin_bit_cast(ushort2v, w[j] & 0x7FFF7FFFu));
+  return m[0] > m[1] ? m[0] : m[1];
+}
+__device__ inline float bf16_of(const uint4& raw, int e) {  // element e of the 8
+  const uint32_t w = e < 2 ? raw.x : e < 4 ? raw.y : e < 6 ? raw.z : raw.w;
+  return (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+}
+// the low bytes of four words, packed in order
+__device__ inline uint32_t low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
+}
+
+// The rows of a sub-block, 16 / G of them per lane (which ones depends on K or V, see above).
+// Rows r_lo .. r_hi - 1 of the sub-block are the run's tokens (all 16 for a whole sub-block);
+// `src` is where row r_lo's token lies; the other rows are not read.
+template <int D>
+__device__ inline void load_subblock(const uint16_t* __restrict__ src, size_t tstride, int kv,
+                                     int lane, int r_lo, int r_hi, uint4 (&raw)[D / 32]) {
+  constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
+  const int c = lane & (CL - 1), g = lane / CL;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int r = kv ? g * NI + i : i * G + g;
+    raw[i] = (r >= r_lo && r < r_hi) ? *(const uint4*)(src + (ptrdiff_t)(r - r_lo) * (ptrdiff_t)tstride + 8 * c)
+                                     : make_uint4(0u, 0u, 0u, 0u);
+  }
+}
 
 template <int D>
-__device__ inline void int8_subblock(const uint16_t* __restrict__ src, size_t tstride,
-                                     uint8_t* __restrict__ tile, float* __restrict__ srow,
-                                     int kv, int off0, int bs, int lane) {
+__device__ inline void int8_subblock(const uint4 (&raw)[D / 32], uint8_t* __restrict__ tile,
+                                     float* __restrict__ srow, int kv, int off0, int bs, int lane,
+                                     int r_lo, int r_hi) {
   constexpr int CL = D / 8;    // lanes per token row
   constexpr int G = 64 / CL;   // lane groups = token rows per load instruction
   constexpr int NI = 16 / G;   // token rows per lane
   const int c = lane & (CL - 1), g = lane / CL;
-  uint4 raw[NI];
   int tok[NI];
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    tok[i] = kv ? g * NI + i : i * G + g;
-    raw[i] = *(const uint4*)(src + (size_t)tok[i] * tstride + 8 * c);
-  }
+  for (int i = 0; i < NI; ++i) tok[i] = kv ? g * NI + i : i * G + g;
   uint32_t vcode[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // V: per channel, this lane's tokens' bytes
+  float mine = 0.0f;  // the scale this lane stores
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
-    uint32_t amax = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
-      amax = amax > lo ? amax : lo;
-      amax = amax > hi ? amax : hi;
-    }
-    amax = row_max_u32<CL>(amax);
-    const float s = int8_scale(amax);
+    const float s = int8_scale(row_max_u32<CL>(absmax8(raw[i])));
     const bool fast = s > 1e-30f;  // rcp of a denormal is not usable
     const float inv = fast ? __builtin_amdgcn_rcpf(s) : 0.0f;
-    uint32_t kcode[2] = {0, 0};
+    uint32_t t[8];  // bit patterns of 1.5 * 2^23 + 128 + code: the low byte is the stored code
+    // lanes whose element e needs the exact decision (wave-wide masks: the comparisons write
+    // them directly and the scalar unit collects them)
+    unsigned long long marked[8], any_marked = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
-                              : __uint_as_float(w[e >> 1] << 16);
-      const float stored = int8_code_f32(x, s, inv, fast) + 128.0f;  // offset-binary, exact
-      if (kv == 0) kcode[e >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(stored, e & 3, kcode[e >> 2]);
-      else vcode[e] = __builtin_amdgcn_cvt_pk_u8_f32(stored, i, vcode[e]);
+      const float x = bf16_of(raw[i], e);
+      const float tf = __builtin_fmaf(x, inv, kRoundMagic);
+      const float d = __builtin_fmaf(x, inv, -(tf - kRoundMagic));
+      t[e] = __float_as_uint(tf);
+      marked[e] = __ballot(!fast || fabsf(d) > 0.5f - 4e-5f);
+      any_marked |= marked[e];
     }
-    if (kv == 0)
-      *(uint2*)(tile + k_elem(off0 + tok[i], 8 * c, bs, D)) = make_uint2(kcode[0], kcode[1]);
-    if (c == 0) srow[tok[i]] = s;
+    if (__builtin_expect(any_marked != 0, 0)) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (marked[e] == 0) continue;  // wave-uniform: nobody asked
+        if ((marked[e] >> lane) & 1)
+          t[e] = s == 0.0f ? 128u : (uint32_t)((int8_t)int8_code(bf16_of(raw[i], e), s) + 128);
+      }
+    }
+    if (kv == 0) {
+      if (tok[i] >= r_lo && tok[i] < r_hi)
+        *(uint2*)(tile + k_elem(off0 + tok[i], 8 * c, bs, D)) =
+            make_uint2(low_bytes(t[0], t[1], t[2], t[3]), low_bytes(t[4], t[5], t[6], t[7]));
+    } else {
+      // the low byte of t[e] becomes byte i of the channel's word
+      constexpr uint32_t kInsert[4] = {0x03020104u, 0x03020400u, 0x03040100u, 0x04020100u};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vcode[e] = __builtin_amdgcn_perm(t[e], vcode[e], kInsert[i]);
+    }
+    mine = c == i ? s : mine;
+  }
+  // the sub-block's 16 scales in one store: lane (c = i, group g) writes its row i's
+  if (c < NI) {
+    const int r = kv ? g * NI + c : c * G + g;
+    if (r >= r_lo && r < r_hi) srow[r] = mine;
   }
   if (kv == 1) {
+    const bool whole = r_lo == 0 && r_hi == 16;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       uint8_t* row = tile + v_elem(off0, 8 * c + e, bs, D) + g * NI;
-      if constexpr (NI == 4) *(uint32_t*)row = vcode[e];
-      else *(uint16_t*)row = (uint16_t)vcode[e];
+      if (whole) {
+        if constexpr (NI == 4) *(uint32_t*)row = vcode[e];
+        else *(uint16_t*)row = (uint16_t)vcode[e];
+      } else {  // a shorter run: byte by byte, the other slots of the row keep their contents
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          if (g * NI + i >= r_lo && g * NI + i < r_hi) row[i] = (uint8_t)(vcode[e] >> (8 * i));
+      }
     }
   }
 }
 
-// unit = (window of 16 consecutive tokens of the call, kv head, K|V): the wavefront handles
-// every run that starts inside its window, so no wavefront is launched only to find that its
-// token is not a run's first.
+// unit = (window of 16 consecutive tokens of the call, kv head): the wavefront handles every run
+// that starts inside its window, so no wavefront is launched only to find that its token is
+// not a run's first, and it handles K and V alike: the slots are worked out once, and the V
+// rows of a whole sub-block are already on their way while the K rows are encoded.
 template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_int8_bulk_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -233,10 +298,9 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_bulk_kernel(
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int windows = (num_tokens + 15) >> 4;
-  if (unit >= (int64_t)windows * H * 2) return;
-  const int kv = (int)(unit & 1);
-  const int h = (int)((unit >> 1) % H);
-  const int w0 = (int)((unit >> 1) / H) * 16;
+  if (unit >= (int64_t)windows * H) return;
+  const int h = (int)(unit % H);
+  const int w0 = (int)(unit / H) * 16;
   // lanes 0..15: is token w0 + lane the first of a run
   bool first = false;
   {
@@ -260,15 +324,19 @@ __global__ __launch_bounds__(kWaves * 64) void write_int8_bulk_kernel(
     const bool cont = lane < 16 - so && t0 + lane < num_tokens && slot_mapping[t0 + lane] == slot0 + lane;
     const uint32_t m = (uint32_t)__ballot(cont);
     const int run = __builtin_ctz(~m);  // lane 0 always continues
-    if (run == 16) {
-      const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
-      const int off0 = (int)(slot0 - blk * bs);
-      int8_subblock<D>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
-                       cache + tile_offset(blk, kv, h, H, bs, D),
-                       scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0, kv, off0, bs, lane);
-    } else {
-      int8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
-    }
+    // rows so .. so + run - 1 of the sub-block that starts at block offset off0
+    const int64_t blk = slot0 >> __builtin_ctz(bs);  // block sizes are powers of two
+    const int off0 = (int)(slot0 - blk * bs) - so;
+    const size_t row0 = ((size_t)t0 * H + h) * D;
+    uint4 k_rows[D / 32], v_rows[D / 32];
+    load_subblock<D>(k + row0, tstride, 0, lane, so, so + run, k_rows);
+    load_subblock<D>(v + row0, tstride, 1, lane, so, so + run, v_rows);
+    int8_subblock<D>(k_rows, cache + tile_offset(blk, 0, h, H, bs, D),
+                     scales + (((size_t)blk * 2 + 0) * H + h) * bs + off0, 0, off0, bs, lane, so,
+                     so + run);
+    int8_subblock<D>(v_rows, cache + tile_offset(blk, 1, h, H, bs, D),
+                     scales + (((size_t)blk * 2 + 1) * H + h) * bs + off0, 1, off0, bs, lane, so,
+                     so + run);
   }
 }
 
@@ -378,92 +446,166 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
 // ---- fp8, many tokens per call (prefill) ---------------------------------------------------
 // A run made of whole 16-token sub-blocks whose block scale does not force a re-encode of
 // earlier codes (always so when a block is written at once) is handled with 16-byte loads, a
-// lane owning 8 channels of 16 / G tokens as in the int8 prefill kernel: one pass for the
-// run's absmax, a second (the rows now come from the cache) for the codes.
+// lane owning 8 channels of 16 / G tokens as in the int8 prefill kernel.  The rows of up to four
+// sub-blocks (blocks of up to 64 tokens) stay in registers between the pass that finds the
+// run's absmax and the pass that encodes; longer runs are read a second time.
 //
-// Rounding x / s to E4M3: with q = x * rcp(s) in fp32 (relative error below 1.8e-7) and
-// t = |q| / 2^(e-3), e = max(floor(log2 |q|), -6), the code's mantissa is the nearest integer
-// to t in [0, 16]; t is within 3e-6 of the exact value, so unless it lies within 1e-5 of a
-// half-integer its nearest integer is the exact one's.  (Just below a power of two the fast
-// exponent may come out one higher than the exact one; t is then 8 and the code the same.)
-// The rare elements near a half-integer are decided in fp64.
-__device__ inline uint32_t fp8_code_fast(float x, float inv, float s, bool usable) {
-  const float q = x * inv;
-  const float a = fminf(fabsf(q), 448.0f);
-  int e = (int)(__float_as_uint(a) >> 23) - 127;
-  e = e < -6 ? -6 : e;
-  const float t = __builtin_ldexpf(a, 3 - e);
-  const float r = __builtin_rintf(t);
-  if (__builtin_expect(!usable || fabsf(t - r) > 0.5f - 1e-5f, 0))
-    return fp8_code((double)x / (double)s);
-  return ((__float_as_uint(q) >> 24) & 0x80u) | (uint32_t)(((e + 7) << 3) + (int)r - 8);
-}
-
+// Rounding x / s to E4M3 with the hardware conversion (v_cvt_pk_fp8_f32: nearest, ties to even,
+// exact for every |value| <= 448 including the subnormals and the sign of zero; above 464 it
+// gives NaN, so values are first limited to +-448): q = x * rcp(s) is within 1.8e-7 (relative)
+// of the exact quotient, and the conversion is monotonic, so if q (1 + 2^-21) and q (1 - 2^-21)
+// convert to the same code, that is the exact quotient's code.  The rare elements where they
+// differ (a code boundary lies in between: about one in 60 000), and runs whose scale is below
+// the normal fp32 range, are decided in fp64.
+// One run (the call's consecutive tokens that fall into one block: any start o_min, any length),
+// K and V.  `done` comes back false, and nothing is written, if a block scale grows over older
+// codes: they have to be re-expressed, which the general routine does.
 template <int D>
-__device__ inline void fp8_subblocks(const uint16_t* __restrict__ src, size_t tstride,
-                                     uint8_t* __restrict__ tile, float* __restrict__ sp, int kv,
-                                     int o_min, int run, int bs, int lane, bool tensor_scale,
-                                     bool& done) {
+__device__ inline void fp8_run_fast(const uint16_t* __restrict__ k_src,
+                                    const uint16_t* __restrict__ v_src, size_t tstride,
+                                    uint8_t* __restrict__ k_tile, uint8_t* __restrict__ v_tile,
+                                    float* __restrict__ k_sp, float* __restrict__ v_sp, int o_min,
+                                    int run, int bs, int lane, bool tensor_scale, bool& done) {
   constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
   const int c = lane & (CL - 1), g = lane / CL;
-  int tok[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) tok[i] = kv ? g * NI + i : i * G + g;
-  uint32_t amax = 0;
+  const int base0 = o_min & ~15;                       // block offset of the first sub-block touched
+  const int nsb = ((o_min + run + 15) >> 4) - (o_min >> 4);
+  // sub-block j of the run: its valid rows and where its first valid row's token lies
+  auto rows_of = [&](int j, int& r_lo, int& r_hi, ptrdiff_t& first_token) {
+    const int base = base0 + 16 * j;
+    r_lo = max(o_min - base, 0);
+    r_hi = min(o_min + run - base, 16);
+    first_token = (ptrdiff_t)(base + r_lo - o_min);
+  };
+  // the first sub-block's rows stay in registers from the absmax pass to the encoding pass (a
+  // block of 16 tokens is read once); further sub-blocks of the run are read again
+  uint4 k_first[NI], v_first[NI];
+  {
+    int r_lo, r_hi;
+    ptrdiff_t ft;
+    rows_of(0, r_lo, r_hi, ft);
+    load_subblock<D>(k_src + ft * (ptrdiff_t)tstride, tstride, 0, lane, r_lo, r_hi, k_first);
+    load_subblock<D>(v_src + ft * (ptrdiff_t)tstride, tstride, 1, lane, r_lo, r_hi, v_first);
+  }
+  uint32_t amax[2] = {0, 0};
   if (!tensor_scale) {
-    for (int sb = 0; sb < run; sb += 16) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      amax[0] = max(amax[0], absmax8(k_first[i]));
+      amax[1] = max(amax[1], absmax8(v_first[i]));
+    }
+    for (int j = 1; j < nsb; ++j) {
+      int r_lo, r_hi;
+      ptrdiff_t ft;
+      rows_of(j, r_lo, r_hi, ft);
+      uint4 a[NI], b[NI];
+      load_subblock<D>(k_src + ft * (ptrdiff_t)tstride, tstride, 0, lane, r_lo, r_hi, a);
+      load_subblock<D>(v_src + ft * (ptrdiff_t)tstride, tstride, 1, lane, r_lo, r_hi, b);
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        amax[0] = max(amax[0], absmax8(a[i]));
+        amax[1] = max(amax[1], absmax8(b[i]));
+      }
+    }
+    amax[0] = wave_max_u32(amax[0]);
+    amax[1] = wave_max_u32(amax[1]);
+  }
+  float s_new[2];
+  done = true;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t lo = w[j] & 0x7FFFu, hi = (w[j] >> 16) & 0x7FFFu;
-          amax = amax > lo ? amax : lo;
-          amax = amax > hi ? amax : hi;
+  for (int kv = 0; kv < 2; ++kv) {
+    const float* sp = kv ? v_sp : k_sp;
+    const float s_prev = (tensor_scale || o_min > 0) ? *sp : 0.0f;
+    const float s_cand = (amax[kv] == 0) ? 0.0f : __fdiv_rn(bf16_bits_to_float(amax[kv]), 448.0f);
+    s_new[kv] = s_prev > s_cand ? s_prev : s_cand;
+    if (o_min > 0 && s_new[kv] > s_prev && s_prev > 0.0f) done = false;
+  }
+  if (!done) return;
+  constexpr float kUp = 1.0f + 4.76837158203125e-07f, kDown = 1.0f - 4.76837158203125e-07f;  // 2^-21
+
+  auto encode = [&](const uint4 (&raw)[NI], int kv, int j) {
+    const float s = s_new[kv];
+    const bool usable = s > 1e-30f;  // rcp of a denormal is not usable
+    const float inv = usable ? __builtin_amdgcn_rcpf(s) : 0.0f;
+    uint8_t* tile = kv ? v_tile : k_tile;
+    int r_lo, r_hi;
+    ptrdiff_t ft;
+    rows_of(j, r_lo, r_hi, ft);
+    const int base = base0 + 16 * j;
+    // four values (element e4[n] of row r4[n]) -> four code bytes in that order
+    auto codes4 = [&](const int (&r4)[4], const int (&e4)[4], int n) -> uint32_t {
+      if (!(s > 0.0f)) return 0u;  // an all-zero run under a zero scale: codes 0x00
+      float q[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+        q[x] = x < n ? __builtin_amdgcn_fmed3f(bf16_of(raw[r4[x]], e4[x]) * inv, -448.0f, 448.0f) : 0.0f;
+      int up = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kUp, q[1] * kUp, 0, false);
+      int down = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kDown, q[1] * kDown, 0, false);
+      if (n > 2) {
+        up = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kUp, q[3] * kUp, up, true);
+        down = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kDown, q[3] * kDown, down, true);
+      }
+      uint32_t word = (uint32_t)up;
+      const uint32_t diff = usable ? word ^ (uint32_t)down : ~0u;
+      if (__builtin_expect(__any(diff != 0), 0)) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          if (x >= n) break;
+          const bool bad = ((diff >> (8 * x)) & 0xFFu) != 0;
+          if (!__any(bad)) continue;  // wave-uniform: nobody asked
+          if (bad) {
+            const uint32_t code = fp8_code((double)bf16_of(raw[r4[x]], e4[x]) / (double)s);
+            word = (word & ~(0xFFu << (8 * x))) | (code << (8 * x));
+          }
+        }
+      }
+      return word;
+    };
+    if (kv == 0) {  // a row's 8 codes are two words of the quad order
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int r = i * G + g;
+        const int r4[4] = {i, i, i, i}, lo[4] = {0, 1, 2, 3}, hi[4] = {4, 5, 6, 7};
+        const uint2 words = make_uint2(codes4(r4, lo, 4), codes4(r4, hi, 4));
+        if (r >= r_lo && r < r_hi) *(uint2*)(tile + k_elem(base + r, 8 * c, bs, D)) = words;
+      }
+    } else {  // a channel's NI tokens are adjacent bytes of its 16-token row
+      const bool whole = r_lo == 0 && r_hi == 16;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int r4[4] = {0, 1 % NI, 2 % NI, 3 % NI}, e4[4] = {e, e, e, e};
+        const uint32_t word = codes4(r4, e4, NI);
+        uint8_t* row = tile + v_elem(base, 8 * c + e, bs, D) + g * NI;
+        if (whole) {
+          if constexpr (NI == 4) *(uint32_t*)row = word;
+          else *(uint16_t*)row = (uint16_t)word;
+        } else {  // byte by byte: the other slots of the row keep their contents
+#pragma unroll
+          for (int i = 0; i < NI; ++i)
+            if (g * NI + i >= r_lo && g * NI + i < r_hi) row[i] = (uint8_t)(word >> (8 * i));
         }
       }
     }
-    amax = wave_max_u32(amax);
+  };
+  encode(k_first, 0, 0);
+  encode(v_first, 1, 0);
+  for (int j = 1; j < nsb; ++j) {
+    int r_lo, r_hi;
+    ptrdiff_t ft;
+    rows_of(j, r_lo, r_hi, ft);
+    uint4 a[NI], b[NI];
+    load_subblock<D>(k_src + ft * (ptrdiff_t)tstride, tstride, 0, lane, r_lo, r_hi, a);
+    load_subblock<D>(v_src + ft * (ptrdiff_t)tstride, tstride, 1, lane, r_lo, r_hi, b);
+    encode(a, 0, j);
+    encode(b, 1, j);
   }
-  const float s_prev = (tensor_scale || o_min > 0) ? *sp : 0.0f;
-  const float s_cand = (amax == 0) ? 0.0f : __fdiv_rn(bf16_bits_to_float(amax), 448.0f);
-  const float s_new = s_prev > s_cand ? s_prev : s_cand;
-  done = !(o_min > 0 && s_new > s_prev && s_prev > 0.0f);
-  if (!done) return;  // earlier codes must be re-expressed: the general routine does the run
-  const bool usable = s_new > 1e-30f;  // rcp of a denormal is not usable
-  const float inv = usable ? __builtin_amdgcn_rcpf(s_new) : 0.0f;
-  for (int sb = 0; sb < run; sb += 16) {
-    uint32_t vcode[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const uint4 raw = *(const uint4*)(src + (size_t)(sb + tok[i]) * tstride + 8 * c);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-      uint32_t kcode[2] = {0, 0};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float x = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u)
-                                : __uint_as_float(w[e >> 1] << 16);
-        const uint32_t code = (s_new > 0.0f) ? fp8_code_fast(x, inv, s_new, usable) : 0u;
-        if (kv == 0) kcode[e >> 2] |= code << (8 * (e & 3));
-        else vcode[e] |= code << (8 * i);
-      }
-      if (kv == 0)
-        *(uint2*)(tile + k_elem(o_min + sb + tok[i], 8 * c, bs, D)) = make_uint2(kcode[0], kcode[1]);
-    }
-    if (kv == 1) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        uint8_t* row = tile + v_elem(o_min + sb, 8 * c + e, bs, D) + g * NI;
-        if constexpr (NI == 4) *(uint32_t*)row = vcode[e];
-        else *(uint16_t*)row = (uint16_t)vcode[e];
-      }
-    }
+  if (lane == 0 && !tensor_scale) {
+    *k_sp = s_new[0];
+    *v_sp = s_new[1];
   }
-  if (lane == 0 && !tensor_scale) *sp = s_new;
 }
 
-// unit = (window of 16 consecutive tokens of the call, kv head, K|V), as for int8
+// unit = (window of 16 consecutive tokens of the call, kv head): K and V, as for int8
 template <int D>
 __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -472,17 +614,19 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
   const int lane = threadIdx.x & 63;
   const int64_t unit = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int windows = (num_tokens + 15) >> 4;
-  if (unit >= (int64_t)windows * H * 2) return;
-  const int kv = (int)(unit & 1);
-  const int h = (int)((unit >> 1) % H);
-  const int w0 = (int)((unit >> 1) / H) * 16;
+  if (unit >= (int64_t)windows * H) return;
+  const int h = (int)(unit % H);
+  const int w0 = (int)(unit / H) * 16;
+  // a run ends with its block, whose tokens share a scale; under static scales nothing ties a
+  // block's sub-blocks together, so runs end with the sub-block and spread over more wavefronts
+  const int span = tensor_scale ? 16 : bs;
   bool first = false;
   {
     const int t = w0 + lane;
     if (lane < 16 && t < num_tokens) {
       const int64_t slot = slot_mapping[t];
       if (slot >= 0)
-        first = !(t > 0 && (slot & (bs - 1)) > 0 && slot_mapping[t - 1] == slot - 1);
+        first = !(t > 0 && (slot & (span - 1)) > 0 && slot_mapping[t - 1] == slot - 1);
     }
   }
   uint32_t starts = (uint32_t)__ballot(first);
@@ -492,25 +636,28 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
     starts &= starts - 1;
     const int64_t slot0 = slot_mapping[t0];
     const int o_min = (int)(slot0 & (bs - 1));
+    const int room = span - (int)(slot0 & (span - 1));  // slots left in the block / sub-block
     int run = 0;
-    for (int base = 0; base < bs - o_min; base += 64) {  // block sizes reach 256
+    for (int base = 0; base < room; base += 64) {  // block sizes reach 256
       const int j = base + lane;
-      const bool cont = j < bs - o_min && t0 + j < num_tokens && slot_mapping[t0 + j] == slot0 + j;
+      const bool cont = j < room && t0 + j < num_tokens && slot_mapping[t0 + j] == slot0 + j;
       const unsigned long long m = __ballot(cont);
       const int n = m == ~0ull ? 64 : __builtin_ctzll(~m);
       run += n;
       if (n < 64) break;
     }
+    const int64_t blk = slot0 >> __builtin_ctz(bs);
+    const size_t row0 = ((size_t)t0 * H + h) * D;
     bool done = false;
-    if (((o_min | run) & 15) == 0) {
-      const int64_t blk = slot0 >> __builtin_ctz(bs);
-      fp8_subblocks<D>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
-                       cache + tile_offset(blk, kv, h, H, bs, D),
-                       tensor_scale ? scales + kv : scales + ((size_t)blk * 2 + kv) * H + h, kv,
-                       o_min, run, bs, lane, tensor_scale != 0, done);
+    fp8_run_fast<D>(k + row0, v + row0, tstride, cache + tile_offset(blk, 0, h, H, bs, D),
+                    cache + tile_offset(blk, 1, h, H, bs, D),
+                    tensor_scale ? scales + 0 : scales + ((size_t)blk * 2 + 0) * H + h,
+                    tensor_scale ? scales + 1 : scales + ((size_t)blk * 2 + 1) * H + h, o_min, run,
+                    bs, lane, tensor_scale != 0, done);
+    if (!done) {
+      fp8_run<D>(k, v, cache, scales, H, bs, 0, h, t0, slot0, run, lane, tensor_scale != 0);
+      fp8_run<D>(k, v, cache, scales, H, bs, 1, h, t0, slot0, run, lane, tensor_scale != 0);
     }
-    if (!done)
-      fp8_run<D>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane, tensor_scale != 0);
   }
 }
 
@@ -771,11 +918,23 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
       hipLaunchKernelGGL((write_plain_kernel<64>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
                          num_tokens, (uint16_t*)cache, desc.num_kv_heads, desc.block_size);
   } else if (bulk && desc.mode == KVQ_INT8_TOKEN_HEAD) {
-    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 128);
-    else KVQ_LAUNCH_WRITE(write_int8_bulk_kernel, 64);
+    // (a wavefront of this kernel handles K and V: half the units)
+    const unsigned g = (unsigned)((units / 2 + kWaves - 1) / kWaves);
+    if (desc.head_dim == 128)
+      hipLaunchKernelGGL((write_int8_bulk_kernel<128>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+    else
+      hipLaunchKernelGGL((write_int8_bulk_kernel<64>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
   } else if (bulk) {
-    if (desc.head_dim == 128) KVQ_LAUNCH_WRITE_FP8(write_fp8_bulk_kernel, 128);
-    else KVQ_LAUNCH_WRITE_FP8(write_fp8_bulk_kernel, 64);
+    const unsigned g = (unsigned)((units / 2 + kWaves - 1) / kWaves);  // K and V per wavefront
+    const int32_t ts = desc.mode == KVQ_FP8E4M3_TENSOR;
+    if (desc.head_dim == 128)
+      hipLaunchKernelGGL((write_fp8_bulk_kernel<128>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size, ts);
+    else
+      hipLaunchKernelGGL((write_fp8_bulk_kernel<64>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size, ts);
   } else if (desc.mode == KVQ_INT8_TOKEN_HEAD) {
     if (desc.head_dim == 128) KVQ_LAUNCH_WRITE(write_int8_kernel, 128);
     else KVQ_LAUNCH_WRITE(write_int8_kernel, 64);
