@@ -146,7 +146,8 @@ class Layers:
         cache, scales = self.caches[i % self.n]
         kvq.paged_decode_attn(self.q, cache, scales, self.desc, self.bt, self.sl, wl.q_len,
                               wl.max_seq_len, wl.sm_scale, self.out, self.ws,
-                              chunk_tokens=self.chunk, stream=self.stream, L=L)
+                              chunk_tokens=self.chunk, stream=self.stream, L=L,
+                              shared_prefix_tokens=wl.shared_prefix)
 
     def step(self, i, L=None):
         self.write(i, L)

@@ -189,6 +189,23 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       int32_t chunk_tokens, float* out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* paged_decode_attn for a batch whose sequences begin with the same blocks: a prompt prefix
+ * served from the prefix cache, whose full blocks are shared by the requests that reuse it
+ * (Section 1, "Intelligent KV Cache Management"; Section 5.2.3).  shared_prefix_tokens says
+ * that the positions below it are read by other sequences of this batch as well (their
+ * block-table entries name the same physical blocks).  It is a hint about traffic, never about
+ * the result, which is paged_decode_attn's whatever its value: the kernels load those positions
+ * through the L2 cache instead of streaming past it, so that a prefix leaves HBM once per L2
+ * (there are eight) instead of once per sequence.  Honoured for KVQ_INT8_TOKEN_HEAD and
+ * KVQ_FP8E4M3_BLOCK_HEAD with fewer than 128 query rows per kv head, in units of 64 tokens
+ * (rounded down); ignored otherwise.  shared_prefix_tokens < 0 is KVQ_E_BAD_SHAPE. */
+int paged_decode_attn_prefix(const void* q, const void* cache, const float* scales,
+                             const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                             int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                             int32_t q_len, int32_t num_q_heads, int32_t max_seq_len,
+                             float sm_scale, int32_t chunk_tokens, int32_t shared_prefix_tokens,
+                             float* out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, serving loops
  * and harnesses that forbid allocation): paged_decode_attn with the library's own scratch buffer
  * in place of the caller's workspace.  Same arguments otherwise, same kernels, same results.

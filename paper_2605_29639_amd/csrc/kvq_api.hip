@@ -285,8 +285,8 @@ int attn_call(const void* q, const void* cache, const float* scales,
               const kvq_cache_desc_t* desc, const int32_t* block_tables,
               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch, int32_t q_len,
               int32_t num_q_heads, int32_t max_seq_len, float sm_scale, int32_t chunk_tokens,
-              float* out, void* workspace, size_t workspace_bytes, bool own_scratch,
-              void* stream) {
+              int32_t shared_prefix_tokens, float* out, void* workspace, size_t workspace_bytes,
+              bool own_scratch, void* stream) {
   kvq::AttnPlan plan;
   int err;
   if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
@@ -294,6 +294,7 @@ int attn_call(const void* q, const void* cache, const float* scales,
   if (max_blocks_per_seq < 0 ||
       (int64_t)max_blocks_per_seq * desc->block_size < (int64_t)max_seq_len)
     return KVQ_E_BAD_SHAPE;
+  if (shared_prefix_tokens < 0) return KVQ_E_BAD_SHAPE;
   if (batch == 0) return KVQ_OK;
   if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
   if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
@@ -352,6 +353,7 @@ int attn_call(const void* q, const void* cache, const float* scales,
   a.num_waves = plan.num_waves;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   a.wave_clock = nullptr;
+  a.shared_groups = shared_prefix_tokens / 64;
   const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
@@ -367,8 +369,19 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
                       int32_t chunk_tokens, float* out, void* workspace,
                       size_t workspace_bytes, void* stream) {
   return attn_call(q, cache, scales, desc, block_tables, max_blocks_per_seq, seq_lens, batch,
-                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, out, workspace,
+                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, 0, out, workspace,
                    workspace_bytes, false, stream);
+}
+
+int paged_decode_attn_prefix(const void* q, const void* cache, const float* scales,
+                             const kvq_cache_desc_t* desc, const int32_t* block_tables,
+                             int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,
+                             int32_t q_len, int32_t num_q_heads, int32_t max_seq_len,
+                             float sm_scale, int32_t chunk_tokens, int32_t shared_prefix_tokens,
+                             float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_call(q, cache, scales, desc, block_tables, max_blocks_per_seq, seq_lens, batch,
+                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, shared_prefix_tokens,
+                   out, workspace, workspace_bytes, false, stream);
 }
 
 int paged_decode_attn_static(const void* q, const void* cache, const float* scales,
@@ -377,8 +390,8 @@ int paged_decode_attn_static(const void* q, const void* cache, const float* scal
                              int32_t q_len, int32_t num_q_heads, int32_t max_seq_len,
                              float sm_scale, int32_t chunk_tokens, float* out, void* stream) {
   return attn_call(q, cache, scales, desc, block_tables, max_blocks_per_seq, seq_lens, batch,
-                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, out, nullptr, 0, true,
-                   stream);
+                   q_len, num_q_heads, max_seq_len, sm_scale, chunk_tokens, 0, out, nullptr, 0,
+                   true, stream);
 }
 
 int kvq_cache_to_canonical(const void* cache, void* canonical, const kvq_cache_desc_t* desc,

@@ -127,7 +127,10 @@ __device__ inline int range_of(const Split& s, int f) {
 // (The second launch bound, two wavefronts per SIMD, for the quantized one-tile kernels: they
 // fit either way, but told so the compiler keeps everything in 200-224 VGPRs instead of parking
 // values in AGPRs and copying them back, 1-2 % faster.)
-template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK>
+//   SHARED = true (instantiated for the int8 and block-scaled fp8 caches): the groups below
+//   p.shared_groups are loaded through the caches rather than past them, because the caller
+//   said that other sequences of the batch read the same blocks (a common prefix).
+template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK, bool SHARED = false>
 __global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN) ? 2 : 1) void
 attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
@@ -285,29 +288,49 @@ attn_stream_kernel(const AttnArgs p) {
     const uint8_t* kbase =
         cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * RB + k_lane);
     vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * RB);
+    const uint32_t s_lane = TOKEN_SCALE                    ? h * bs + m16 + off_v
+                            : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
+                                                           : h;
+    const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
+    if (SHARED && c.g < p.shared_groups) {  // blocks other sequences read too: keep them cached
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int j = 0; j < KJ; ++j)
-        kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
+        for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * (4 * RB) + 256 * j);
+      if constexpr (!PLAIN) {
+        sk = *sp;
+        sv = sp[s_kv];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+          kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
+      if constexpr (!PLAIN) {
+        sk = __builtin_nontemporal_load(sp);
+        sv = __builtin_nontemporal_load(sp + s_kv);
+      }
+    }
     if constexpr (PLAIN) {
       sk = 1.0f;
       sv = 1.0f;
-    } else {
-      const uint32_t s_lane = TOKEN_SCALE                    ? h * bs + m16 + off_v
-                              : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
-                                                             : h;
-      const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
-      sk = __builtin_nontemporal_load(sp);
-      sv = __builtin_nontemporal_load(sp + s_kv);
     }
   };
   // (unquantized: piece 2 tt + half is channel tile tt, tokens 8 half .. 8 half + 7)
-  auto load_v = [&](uintx4 (&vt)[VW], const uint8_t* vbase) {
+  auto load_v = [&](uintx4 (&vt)[VW], const uint8_t* vbase, const Cursor& c) {
+    if (SHARED && c.g < p.shared_groups) {
 #pragma unroll
-    for (int x = 0; x < VW; ++x) {
-      const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
-      vt[x] = __builtin_nontemporal_load((const uintx4*)(vbase + at));
+      for (int x = 0; x < VW; ++x) {
+        const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
+        vt[x] = *(const uintx4*)(vbase + at);
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < VW; ++x) {
+        const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
+        vt[x] = __builtin_nontemporal_load((const uintx4*)(vbase + at));
+      }
     }
   };
 
@@ -568,7 +591,7 @@ attn_stream_kernel(const AttnArgs p) {
       __builtin_amdgcn_sched_barrier(0);
       stamp(10, true);  // the first table entries (and q) have arrived
       load_k(kt, sk, sv, vbase, cur, bk0, bv0);
-      load_v(vt, vbase);
+      load_v(vt, vbase, cur);
     }
     stamp(2);
     // Two wavefronts share a SIMD and the hardware serves the older one first, so left alone
@@ -588,7 +611,7 @@ attn_stream_kernel(const AttnArgs p) {
       fetch_entries(nn, blk_k, blk_v);
       softmax(S, sk_cur, sv_cur, cur, pb);
       pv(vt, pb, cur);
-      load_v(vt, vbase);
+      load_v(vt, vbase, nxt);
       if (nxt.g == 0) {  // the next group opens another pair
         end_pair(cur, from_start);
         begin_pair(nxt);
@@ -621,7 +644,7 @@ attn_stream_kernel(const AttnArgs p) {
     begin_pair(cur);
     __builtin_amdgcn_sched_barrier(0);
     load_k(kta, ska, sva, vbase, cur, tk0, tv0);
-    load_v(vta, vbase);
+    load_v(vta, vbase, cur);
     auto leave = [&](const Cursor& next) {  // after a group: does the next one open another pair
       if (next.g == 0) {
         end_pair(cur, from_start);
@@ -635,7 +658,7 @@ attn_stream_kernel(const AttnArgs p) {
       // buffer a holds group i; tk1/tv1 are the entries of group i+1
       fetch_entries(c2, tk0, tv0);
       load_k(ktb, skb, svb, vbase, c1, tk1, tv1);
-      load_v(vtb, vbase);
+      load_v(vtb, vbase, c1);
       qk(kta, S);
       softmax(S, ska, sva, cur, pb);
       pv(vta, pb, cur);
@@ -643,7 +666,7 @@ attn_stream_kernel(const AttnArgs p) {
       // buffer b holds group i+1; tk0/tv0 are the entries of group i+2
       fetch_entries(c3, tk1, tv1);
       load_k(kta, ska, sva, vbase, c2, tk0, tv0);
-      load_v(vta, vbase);
+      load_v(vta, vbase, c2);
       qk(ktb, S);
       softmax(S, skb, svb, cur, pb);
       pv(vtb, pb, cur);
@@ -656,7 +679,7 @@ attn_stream_kernel(const AttnArgs p) {
     // one or two groups are left; buffer a holds group i
     if (i + 1 < count) {
       load_k(ktb, skb, svb, vbase, c1, tk1, tv1);
-      load_v(vtb, vbase);
+      load_v(vtb, vbase, c1);
       qk(kta, S);
       softmax(S, ska, sva, cur, pb);
       pv(vta, pb, cur);
@@ -784,6 +807,18 @@ unsigned long long* g_wave_clock = nullptr;
 template <int MODE, int D, bool CEIL, bool CLOCK>
 void launch_variant(const AttnArgs& a, hipStream_t stream) {
   constexpr int kDepth = MODE == KVQ_BF16_PLAIN ? 1 : 2;
+  // the variant that keeps a shared prefix cached exists for the two benchmark formats
+  constexpr bool kHasShared =
+      !CEIL && !CLOCK && (MODE == KVQ_INT8_TOKEN_HEAD || MODE == KVQ_FP8E4M3_BLOCK_HEAD);
+  if constexpr (kHasShared) {
+    if (a.shared_groups > 0) {
+      if (a.row_tiles == 1)
+        hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1, false, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
+      else
+        hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, kDepth, false, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
+      return;
+    }
+  }
   if (a.row_tiles == 1)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, CEIL, 1, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
   else

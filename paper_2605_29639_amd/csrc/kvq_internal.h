@@ -91,6 +91,7 @@ struct AttnArgs {
   int32_t block_size, bs_shift, head_dim, mode;
   int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;
   float scale_log2;  // sm_scale * log2(e)
+  int32_t shared_groups;  // leading 64-token groups of every sequence that other sequences read too
   unsigned long long* wave_clock;  // measurement build: 8 clock readings per wavefront; else null
 };
 

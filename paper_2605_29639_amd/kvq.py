@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
            "paged_decode_attn_workspace_bytes",
-           "paged_decode_attn", "paged_decode_attn_static", "kvq_cache_to_canonical", "kvq_cache_from_canonical",
+           "paged_decode_attn", "paged_decode_attn_prefix", "paged_decode_attn_static",
+           "kvq_cache_to_canonical", "kvq_cache_from_canonical",
            "kvq_blocks_export", "kvq_blocks_import",
            "kvq_strerror")
 # what the measurement build (libkvq_prof.so, include/kvq_prof.h) exports on top
@@ -74,6 +75,9 @@ def _load(path, prof):
     L.paged_decode_attn.restype = C.c_int
     L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
                                     I32, P, P, SZ, P]
+    L.paged_decode_attn_prefix.restype = C.c_int
+    L.paged_decode_attn_prefix.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
+                                           I32, I32, P, P, SZ, P]
     L.paged_decode_attn_static.restype = C.c_int
     L.paged_decode_attn_static.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
                                            I32, P, P]
@@ -222,12 +226,26 @@ def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0
 
 
 def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max_seq_len,
-                      sm_scale, out, workspace, chunk_tokens=0, stream=None, L=None):
+                      sm_scale, out, workspace, chunk_tokens=0, stream=None, L=None,
+                      shared_prefix_tokens=0):
+    """paged_decode_attn, or paged_decode_attn_prefix when shared_prefix_tokens is given."""
     import torch
     batch = _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, out)
     need = workspace_bytes(desc, batch, q_len, q.shape[1], max_seq_len, chunk_tokens)
     if batch > 0 and workspace.numel() * workspace.element_size() < need:
         raise ValueError("workspace holds %d bytes, the call needs %d" % (workspace.numel(), need))
+    if shared_prefix_tokens:
+        rc = (L or lib()).paged_decode_attn_prefix(
+            _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
+            _dev(scales, torch.float32, "scales"), C.byref(desc),
+            _dev(block_tables, torch.int32, "block_tables"), block_tables.shape[1],
+            _dev(seq_lens, torch.int32, "seq_lens"), batch, q_len, q.shape[1], max_seq_len,
+            float(sm_scale), chunk_tokens, int(shared_prefix_tokens),
+            _dev(out, torch.float32, "out"), _dev(workspace, torch.uint8, "workspace"),
+            workspace.numel(), _stream(stream))
+        if rc != OK:
+            raise KvqError(rc, "paged_decode_attn_prefix")
+        return
     rc = (L or lib()).paged_decode_attn(
         _dev(q, torch.bfloat16, "q"), _dev(cache, torch.uint8, "cache"),
         _dev(scales, torch.float32, "scales"), C.byref(desc),

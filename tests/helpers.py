@@ -37,7 +37,7 @@ from paper_2605_29639_amd.fill import attn_err, bits_to_bf16_tensor, gpu_desc, g
 
 
 def gpu_attention(wl, cache, scales, desc, chunk_tokens=None, seq_lens=None, q=None, q_len=None,
-                  L=None):
+                  L=None, shared_prefix_tokens=0):
     """Run the library's paged_decode_attn on a device cache; returns float32 numpy out."""
     import torch
     from paper_2605_29639_amd import kvq
@@ -54,7 +54,7 @@ def gpu_attention(wl, cache, scales, desc, chunk_tokens=None, seq_lens=None, q=N
     ws = kvq.alloc_workspace(desc, len(seq_lens), q_len, qbits.shape[1], max_len, chunk)
     ws.fill_(0xFF)  # NaN patterns: the kernels must not depend on workspace contents
     kvq.paged_decode_attn(qd, cache, scales, desc, bt, sl, q_len, max_len, wl.sm_scale, out, ws,
-                          chunk_tokens=chunk, L=L)
+                          chunk_tokens=chunk, L=L, shared_prefix_tokens=shared_prefix_tokens)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 

@@ -155,6 +155,17 @@ def test_static_scratch_rejects_what_does_not_fit():
                                       Hq, max_len, 0.1, 0, fake, None) == kvq.E_NULLPTR
 
 
+def test_prefix_entry_point_validates_like_the_plain_one():
+    L = kvq.lib()
+    ok = d()
+    args = [FAKE, FAKE, FAKE, C.byref(ok), FAKE, 8, FAKE, 2, 1, 4, 100, 0.125, 0]
+    tail = [FAKE, FAKE, 1 << 30, None]
+    assert L.paged_decode_attn_prefix(*args, -64, *tail) == kvq.E_BAD_SHAPE
+    assert L.paged_decode_attn_prefix(*args[:7], 0, *args[8:], 64, *tail) == kvq.OK   # empty batch
+    assert L.paged_decode_attn_prefix(None, *args[1:], 64, *tail) == kvq.E_NULLPTR
+    assert L.paged_decode_attn_prefix(*args[:9], 3, *args[10:], 64, *tail) == kvq.E_BAD_SHAPE
+
+
 def test_repack_argument_checks():
     L = kvq.lib()
     assert L.kvq_cache_to_canonical(None, FAKE, C.byref(d()), None) == kvq.E_NULLPTR

@@ -227,3 +227,23 @@ def test_many_query_rows_through_both_kernels(mode):
         prof.kvq_profile_prefill_kernel(1)
     assert attn_err(shared, want) <= TOL and attn_err(streamed, want) <= TOL
     assert attn_err(shared, streamed.astype(np.float64)) <= 2e-4
+
+
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("q_len", [1, 4])
+def test_shared_prefix_hint_changes_traffic_not_results(mode, q_len):
+    """paged_decode_attn_prefix: sequences that begin with the same physical blocks; the hint
+    only chooses how those blocks are loaded, so the output is paged_decode_attn's bit for bit
+    (also where the hint overstates the sharing or is not a multiple of 64, and for a format
+    that ignores it), and within the bound of the checker."""
+    wl = W.custom("prefix", mode, [700, 256 + q_len, 1500, 333, 257], q_len, 8, 2, 128, 16,
+                  seed=90 + mode + q_len, shared_prefix=256)
+    assert (wl.block_tables[:, :16] == wl.block_tables[0, :16]).all()
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    plain = gpu_attention(wl, cache, scales, desc)
+    assert attn_err(plain, want) <= TOL
+    for hint in (256, 200, 64, 4096):
+        hinted = gpu_attention(wl, cache, scales, desc, shared_prefix_tokens=hint)
+        assert np.array_equal(hinted.view(np.uint32), plain.view(np.uint32)), hint
