@@ -27,6 +27,8 @@ MODE_FP8 = 1
 MODE_BF16 = 2
 MODE_FP8_TENSOR = 3
 MODE_INT4 = 4
+MODE_INT4_GROUP = 5   # int4 codes, one scale per (token, kv head, 32 adjacent channels)
+INT4_MODES = (MODE_INT4, MODE_INT4_GROUP)
 
 _lib = None
 
@@ -161,7 +163,7 @@ def unpack_int4(cache):
 
 
 def head_dim_of(cache, mode):
-    return cache.shape[-1] * (2 if mode == MODE_INT4 else 1)
+    return cache.shape[-1] * (2 if mode in INT4_MODES else 1)
 
 
 def scale(absmax, qmax):
@@ -171,7 +173,7 @@ def scale(absmax, qmax):
 def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
     """Zero-filled canonical cache and scales."""
     cache = np.zeros((num_blocks, 2, num_kv_heads, block_size,
-                      head_dim // 2 if mode == MODE_INT4 else head_dim),
+                      head_dim // 2 if mode in INT4_MODES else head_dim),
                      dtype=np.uint16 if mode == MODE_BF16 else np.uint8)
     if mode == MODE_BF16:
         scales = np.zeros((0,), dtype=np.float32)
@@ -179,6 +181,8 @@ def alloc_cache(mode, num_blocks, block_size, num_kv_heads, head_dim):
         scales = np.zeros((2,), dtype=np.float32)
     elif mode in (MODE_INT8, MODE_INT4):
         scales = np.zeros((num_blocks, 2, num_kv_heads, block_size), dtype=np.float32)
+    elif mode == MODE_INT4_GROUP:
+        scales = np.zeros((num_blocks, 2, num_kv_heads, block_size, head_dim // 32), dtype=np.float32)
     else:
         scales = np.zeros((num_blocks, 2, num_kv_heads), dtype=np.float32)
     return cache, scales
@@ -191,7 +195,8 @@ def _chk_cache(cache, scales, mode):
     assert two == 2
     assert scales.shape == {MODE_INT8: (nblk, 2, H, bs), MODE_FP8: (nblk, 2, H),
                             MODE_BF16: (0,), MODE_FP8_TENSOR: (2,),
-                            MODE_INT4: (nblk, 2, H, bs)}[mode]
+                            MODE_INT4: (nblk, 2, H, bs),
+                            MODE_INT4_GROUP: (nblk, 2, H, bs, D // 16)}[mode]
 
 
 def kv_quant_write(k, v, slot_mapping, cache, scales, mode):
@@ -217,6 +222,8 @@ def dequant(cache, scales, mode):
         return bf16_to_f64(cache)
     if mode == MODE_INT4:
         return unpack_int4(cache).astype(np.float64) * scales.astype(np.float64)[..., None]
+    if mode == MODE_INT4_GROUP:
+        return unpack_int4(cache).astype(np.float64) * np.repeat(scales.astype(np.float64), 32, axis=-1)
     if mode == MODE_INT8:
         return cache.view(np.int8).astype(np.float64) * scales.astype(np.float64)[..., None]
     table = fp8_decode(np.arange(256, dtype=np.uint8))
@@ -284,7 +291,7 @@ def blocks_export(cache, scales, mode, block_ids):
     _chk_cache(cache, scales, mode)
     ids = np.asarray(block_ids, dtype=np.int64)
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
-    per_block = mode in (MODE_INT8, MODE_FP8, MODE_INT4)  # else the scales are not part of a block
+    per_block = mode in (MODE_INT8, MODE_FP8, MODE_INT4, MODE_INT4_GROUP)  # else the scales are not part of a block
     packed_scales = scales[ids].copy() if per_block else scales.copy()
     return cache[ids].copy(), packed_scales
 
@@ -298,7 +305,7 @@ def blocks_import(packed_cache, packed_scales, mode, block_ids, cache, scales):
     assert ids.size == 0 or (ids.min() >= 0 and ids.max() < cache.shape[0])
     for i, blk in enumerate(ids):
         cache[blk] = packed_cache[i]
-        if mode in (MODE_INT8, MODE_FP8, MODE_INT4):
+        if mode in (MODE_INT8, MODE_FP8, MODE_INT4, MODE_INT4_GROUP):
             scales[blk] = packed_scales[i]
 
 

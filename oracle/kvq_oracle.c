@@ -24,6 +24,8 @@
  *           f32 [2] (K, V), an input                           (mode 3)
  *           as mode 0                                          (mode 4; cache rows are
  *           head_dim / 2 bytes)
+ *           f32 [num_blocks][2][num_kv_heads][block_size][head_dim / 32]  (mode 5; cache as
+ *           mode 4)
  *   k, v, q : bf16 bit patterns (uint16), [tokens][heads][head_dim]
  *   out     : f64 [batch*q_len][num_q_heads][head_dim]
  *
@@ -51,6 +53,13 @@
  * row holds channel 2j in its low nibble and channel 2j+1 in its high nibble, each a 4-bit
  * two's complement number.  The cache's last dimension is head_dim / 2 bytes. */
 #define ORACLE_MODE_INT4 4
+/* INT4 under "per-block dynamic scaling" (Section 7.2.2) with the block read as a group of
+ * channels, the form int4 formats commonly take: one fp32 scale per (token, kv head, group of
+ * 32 adjacent channels) = fp32 nearest to that group's absmax / 7; codes, nibble order and
+ * cache shape as mode 4; scales f32 [num_blocks][2][num_kv_heads][block_size][head_dim / 32].
+ * A channel with outliers then costs the resolution of its own group only. */
+#define ORACLE_MODE_INT4_GROUP 5
+#define ORACLE_INT4_GROUP 32
 
 /* ---- O1: a bf16 bit pattern is the top half of an fp32; widening is exact ---- */
 double oracle_bf16_to_f64(uint16_t bits) {
@@ -214,6 +223,38 @@ int oracle_kv_quant_write(const uint16_t* k, const uint16_t* v, const int64_t* s
     }
     return 0;
   }
+  if (mode == ORACLE_MODE_INT4_GROUP) {
+    const int Db = D / 2, NG = D / ORACLE_INT4_GROUP;
+    for (int32_t t = 0; t < num_tokens; ++t) {
+      int64_t slot = slot_mapping[t];
+      if (slot < 0) continue;
+      int64_t blk = slot / bs;
+      int off = (int)(slot % bs);
+      for (int kv = 0; kv < 2; ++kv) {
+        for (int h = 0; h < H; ++h) {
+          const uint16_t* row = (kv ? v : k) + ((size_t)t * H + h) * D;
+          uint8_t* dst = cache + tile_index(blk, kv, h, H, bs, Db) + (size_t)off * Db;
+          float* sdst = scales + ((((size_t)blk * 2 + kv) * H + h) * bs + off) * NG;
+          for (int g = 0; g < NG; ++g) {
+            const uint16_t* grp = row + g * ORACLE_INT4_GROUP;
+            double m = 0.0;
+            for (int d = 0; d < ORACLE_INT4_GROUP; ++d) {
+              double a = fabs(oracle_bf16_to_f64(grp[d]));
+              if (a > m) m = a;
+            }
+            float s = (m == 0.0) ? 0.0f : oracle_scale(m, 7.0);
+            sdst[g] = s;
+            for (int j = 0; j < ORACLE_INT4_GROUP / 2; ++j) {
+              int lo = oracle_int4_encode(oracle_bf16_to_f64(grp[2 * j]), s);
+              int hi = oracle_int4_encode(oracle_bf16_to_f64(grp[2 * j + 1]), s);
+              dst[g * (ORACLE_INT4_GROUP / 2) + j] = (uint8_t)((lo & 15) | ((hi & 15) << 4));
+            }
+          }
+        }
+      }
+    }
+    return 0;
+  }
   if (mode == ORACLE_MODE_FP8_TENSOR) {
     for (int32_t t = 0; t < num_tokens; ++t) {
       int64_t slot = slot_mapping[t];
@@ -302,11 +343,14 @@ double oracle_dequant_at(const uint8_t* cache, const float* scales, int32_t mode
                          int kv, int h, int off, int d, int32_t block_size,
                          int32_t num_kv_heads, int32_t head_dim) {
   const int H = num_kv_heads, D = head_dim, bs = block_size;
-  if (mode == ORACLE_MODE_INT4) {
+  if (mode == ORACLE_MODE_INT4 || mode == ORACLE_MODE_INT4_GROUP) {
     uint8_t byte = cache[tile_index(blk, kv, h, H, bs, D / 2) + (size_t)off * (D / 2) + d / 2];
     int nib = (d & 1) ? (byte >> 4) : (byte & 15);
     int code = (nib ^ 8) - 8; /* 4-bit two's complement */
-    return (double)code * (double)scales[(((size_t)blk * 2 + kv) * H + h) * bs + off];
+    size_t token = (((size_t)blk * 2 + kv) * H + h) * bs + off;
+    if (mode == ORACLE_MODE_INT4) return (double)code * (double)scales[token];
+    return (double)code *
+           (double)scales[token * (D / ORACLE_INT4_GROUP) + d / ORACLE_INT4_GROUP];
   }
   if (mode == ORACLE_MODE_BF16)
     return oracle_bf16_to_f64(

@@ -19,6 +19,7 @@ MODE_FP8 = 1   # fp8-e4m3 codes, one fp32 scale per (block, kv head)
 MODE_BF16 = 2  # the unquantized baseline: bf16 rows stored as they are, no scales
 MODE_FP8_TENSOR = 3  # fp8-e4m3 codes, static scales: one for a layer's K, one for its V
 MODE_INT4 = 4  # int4 codes in [-7, 7], two per byte, one fp32 scale per (token, kv head)
+MODE_INT4_GROUP = 5  # int4 codes, one fp32 scale per (token, kv head, 32 adjacent channels)
 
 # Static scales for the generators' data: |K| reaches about 20 * 4.6 in the outlier channels and
 # |V| about 6 (N(0,1) over ~1e9 draws), against the format's 448; a few V values saturate.
@@ -125,6 +126,8 @@ class Workload:
             per_token_head = 2.0 * D
         elif self.mode == MODE_INT4:
             per_token_head = 2.0 * (D / 2 + 4)
+        elif self.mode == MODE_INT4_GROUP:
+            per_token_head = 2.0 * (D / 2 + 4 * (D / 32))
         else:
             per_token_head = 2.0 * D + 8.0 / bs
         kv = self.unique_tokens() * H * per_token_head

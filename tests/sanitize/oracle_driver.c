@@ -30,11 +30,12 @@ int main(void) {
   const int32_t lens[B] = {37, 19};
   const int32_t tables[B][MAXB] = {{4, 1, 5}, {2, 0, -1}};
   double checksum = 0.0;
-  for (int mode = 0; mode <= 4; ++mode) {
-    const size_t row = mode == 4 ? D / 2 : D, esz = mode == 2 ? 2 : 1;
+  for (int mode = 0; mode <= 5; ++mode) {
+    const size_t row = mode >= 4 ? D / 2 : D, esz = mode == 2 ? 2 : 1;
     const size_t cache_bytes = (size_t)NBLK * 2 * H * BS * row * esz;
     const size_t nscales = mode == 2 ? 0 : mode == 3 ? 2 : mode == 1 ? (size_t)NBLK * 2 * H
-                                                                   : (size_t)NBLK * 2 * H * BS;
+                           : mode == 5 ? (size_t)NBLK * 2 * H * BS * (D / 32)
+                                       : (size_t)NBLK * 2 * H * BS;
     uint8_t* cache = calloc(cache_bytes, 1);
     float* scales = calloc(nscales ? nscales : 1, sizeof(float));
     if (mode == 3) { scales[0] = 0.05f; scales[1] = 0.02f; }

@@ -26,7 +26,8 @@ def run(wl, cache, scales):
                                     wl.q_len, wl.sm_scale)
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4,
+                                  W.MODE_INT4_GROUP])
 def test_tiny_config_equals_dense_brute_force(mode):
     wl = W.tiny(mode)
     cache, scales = oracle_fill(wl)
@@ -44,7 +45,7 @@ def test_tiny_config_equals_dense_brute_force(mode):
     K = oracle.gather_dequant(cache, scales, mode, wl.block_tables[1], 100, 0, 1)
     x = oracle.bf16_to_f64(k[:, 1])
     rel = np.abs(K - x).max() / np.abs(x).max()
-    assert rel < {W.MODE_INT8: 0.005, W.MODE_INT4: 0.08}.get(mode, 0.07)
+    assert rel < {W.MODE_INT8: 0.005, W.MODE_INT4: 0.08, W.MODE_INT4_GROUP: 0.08}.get(mode, 0.07)
 
 
 def test_unquantized_mode_is_attention_over_the_original_rows():

@@ -32,6 +32,14 @@ MUTANTS = [
      "int nib = (d & 1) ? (byte >> 4) : (byte & 15);", "int nib = (d & 1) ? (byte & 15) : (byte >> 4);"),
     ("int4_scale_divides_by_8",
      "oracle_scale(m, 7.0)", "oracle_scale(m, 8.0)"),
+    ("int4_group_scale_taken_over_64_channels",
+     "#define ORACLE_INT4_GROUP 32", "#define ORACLE_INT4_GROUP 64"),
+    ("int4_group_dequant_uses_the_first_group_scale",
+     "(double)scales[token * (D / ORACLE_INT4_GROUP) + d / ORACLE_INT4_GROUP]",
+     "(double)scales[token * (D / ORACLE_INT4_GROUP)]"),
+    ("int4_group_codes_written_to_the_first_group",
+     "dst[g * (ORACLE_INT4_GROUP / 2) + j] = (uint8_t)((lo & 15) | ((hi & 15) << 4));",
+     "dst[j] = (uint8_t)((lo & 15) | ((hi & 15) << 4));"),
     ("fp8_ties_go_to_the_odd_code",
      "(err == best_err && (c & 1) == 0)", "(err == best_err && (c & 1) == 1)"),
     ("fp8_exponent_bias_8",

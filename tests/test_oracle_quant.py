@@ -418,7 +418,8 @@ def test_footprint_is_half_of_bf16():
         assert 0.5 <= ratio <= 0.52
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4,
+                                  W.MODE_INT4_GROUP])
 def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
     """The tiered cache's block moves are index copies: checked element by element against
     explicit loops, as a round trip, and for leaving every other block alone."""
@@ -427,7 +428,7 @@ def test_block_export_and_import_move_whole_blocks_and_nothing_else(mode):
     cache, scales = oracle.alloc_cache(mode, nblk, bs, H, D)
     cache[:] = rng.integers(0, 1 << (8 * cache.itemsize), size=cache.shape, dtype=np.uint32).astype(cache.dtype)
     scales[...] = rng.random(scales.shape, dtype=np.float32)
-    per_block_scales = mode in (W.MODE_INT8, W.MODE_FP8, W.MODE_INT4)
+    per_block_scales = mode in (W.MODE_INT8, W.MODE_FP8, W.MODE_INT4, W.MODE_INT4_GROUP)
     ids = np.array([7, 0, 3], dtype=np.int32)
     pc, ps = oracle.blocks_export(cache, scales, mode, ids)
     assert pc.shape == (3,) + cache.shape[1:]
@@ -586,6 +587,97 @@ def test_int4_scale_is_correctly_rounded_and_zero_rows():
     codes, sc, cache, _ = write_rows_int4(row)
     assert sc[0] == 0 and not cache[0, 0, 0, 0].any()
     assert sc[1] == np.float32(2.0 / 7) and codes[1, 3] == -7 and np.count_nonzero(codes[1]) == 1
+
+
+# ---------------------------------------------------------------------------- int4, group scales
+
+def write_rows_int4_group(rows):
+    """Write T rows (values exact in bf16) for 1 head into a fresh pool of the group-scaled int4
+    format; returns (codes int8 [T, D], scales [T, D / 32], cache, scales array)."""
+    rows = np.asarray(rows, dtype=np.float32)
+    T, D = rows.shape
+    kb = f32_bits_of(rows).reshape(T, 1, D)
+    bs = 16
+    nblk = (T + bs - 1) // bs
+    cache, scales = oracle.alloc_cache(oracle.MODE_INT4_GROUP, nblk, bs, 1, D)
+    assert scales.shape == (nblk, 2, 1, bs, D // 32)
+    oracle.kv_quant_write(kb, kb.copy(), np.arange(T, dtype=np.int64), cache, scales,
+                          oracle.MODE_INT4_GROUP)
+    raw = cache[:, 0, 0].reshape(nblk * bs, D // 2)[:T]
+    codes = np.empty((T, D), dtype=np.int8)     # unpacked by hand, not with the checker's helper
+    codes[:, 0::2] = ((raw & 15).astype(np.int16) ^ 8) - 8
+    codes[:, 1::2] = ((raw >> 4).astype(np.int16) ^ 8) - 8
+    return codes, scales[:, 0, 0].reshape(nblk * bs, D // 32)[:T], cache, scales
+
+
+def test_int4_group_scales_hand_computed_ties_per_group(golden_dir):
+    """The tie table of the per-token format inside one group (absmax 7: scale 1), next to a
+    group whose absmax is 14 (scale 2: 3 -> 1.5 -> 2, 5 -> 2.5 -> 2, -1 -> -0.5 -> 0), an
+    all-zero group and a group of small values (scale 2^-10) that keeps its own resolution."""
+    rows = read_table(os.path.join(golden_dir, "int4_ties.txt"))
+    xs = [float(r[0]) for r in rows]
+    want = [int(r[1]) for r in rows]
+    assert len(xs) <= 32
+    row = np.zeros(128, dtype=np.float32)
+    row[32:32 + len(xs)] = xs                       # group 1: the tie table, scale 1
+    row[0:6] = [14.0, 3.0, 5.0, -1.0, -14.0, 7.0]   # group 0: scale 2
+    row[96:100] = np.array([7.0, -3.5, 1.75, 2.5]) * 2.0 ** -10    # group 3: absmax 7 * 2^-10
+    codes, sc, cache, _ = write_rows_int4_group(row[None, :])
+    assert sc[0].tolist() == [2.0, 1.0, 0.0, 2.0 ** -10]
+    assert codes[0, 32:32 + len(xs)].tolist() == want
+    assert codes[0, 0:6].tolist() == [7, 2, 2, 0, -7, 4]        # 7 / 2 = 3.5 -> 4 (even)
+    assert not codes[0, 64:96].any()
+    assert codes[0, 96:100].tolist() == [7, -4, 2, 2]           # -3.5 -> -4 and 2.5 -> 2 (even)
+    # byte 0 holds channel 0 (7 -> 0x7) low and channel 1 (2) high
+    assert cache[0, 0, 0, 0, 0] == 0x27 and cache.shape[-1] == 64
+
+
+def test_int4_group_codes_equal_exact_rational_rounding_group_by_group():
+    rng = np.random.default_rng(73)
+    T, D = 300, 128
+    x = rng.standard_normal((T, D), dtype=np.float32)
+    x[:, 5] *= 20.0                                  # an outlier channel in group 0
+    xv = W.bf16_bits_to_f32(f32_bits_of(x))
+    codes, sc, cache, scales = write_rows_int4_group(xv)
+    for t in range(T):
+        for g in range(D // 32):
+            grp = xv[t, 32 * g:32 * g + 32]
+            m = Fraction(float(np.abs(grp).max()))
+            assert sc[t, g] == nearest_f32(m / 7), (t, g)
+            s = Fraction(float(sc[t, g]))
+            want = [max(-7, min(7, rne_fraction(Fraction(float(v)) / s))) for v in grp]
+            assert codes[t, 32 * g:32 * g + 32].tolist() == want, (t, g)
+    assert codes.min() == -7 and codes.max() == 7
+    # every group reaches +-7 and the round trip stays within half of the group's own step
+    assert np.all(np.abs(codes.astype(np.int32)).reshape(T, D // 32, 32).max(axis=2) == 7)
+    s64 = np.repeat(sc.astype(np.float64), 32, axis=1)
+    assert np.all(np.abs(xv.astype(np.float64) - codes * s64) <= s64 / 2 * (1 + 1e-12))
+    dq = oracle.dequant(cache, scales, oracle.MODE_INT4_GROUP)
+    assert np.array_equal(dq[:, 0, 0].reshape(-1, D)[:T], codes * s64)
+    # the outlier costs its own group's resolution only: the other groups' steps stay small
+    assert np.median(sc[:, 0]) > 4 * np.median(sc[:, 1:])
+
+
+def test_int4_group_scales_groups_are_independent_and_reduce_to_the_per_token_format():
+    rng = np.random.default_rng(74)
+    T, D = 40, 128
+    x = W.bf16_bits_to_f32(f32_bits_of(rng.standard_normal((T, D), dtype=np.float32)))
+    codes, sc, _, _ = write_rows_int4_group(x)
+    y = x.copy()
+    y[:, 32:64] *= np.float32(64.0)                  # only group 1 changes
+    codes2, sc2, _, _ = write_rows_int4_group(y)
+    keep = np.r_[0:32, 64:128]
+    assert np.array_equal(codes2[:, keep], codes[:, keep])
+    assert np.array_equal(sc2[:, [0, 2, 3]], sc[:, [0, 2, 3]])
+    assert np.array_equal(sc2[:, 1], sc[:, 1] * np.float32(64.0))      # a power of two: same codes
+    assert np.array_equal(codes2[:, 32:64], codes[:, 32:64])
+    # with the same absmax in every group the format is the per-token one
+    z = np.clip(x, -3.0, 3.0)
+    z[:, [0, 32, 64, 96]] = np.float32(3.5)
+    cg, sg, _, _ = write_rows_int4_group(z)
+    ct, st, _, _ = write_rows_int4(z)
+    assert np.array_equal(cg, ct)
+    assert np.array_equal(sg, np.repeat(st[:, None], 4, axis=1))
 
 
 def test_encoders_clamp_symmetrically_whatever_the_scale():
