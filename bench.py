@@ -31,9 +31,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
-MODE_NAMES = {0: "int8", 1: "fp8", 2: "bf16", 3: "fp8_tensor", 4: "int4"}
+MODE_NAMES = {0: "int8", 1: "fp8", 2: "bf16", 3: "fp8_tensor", 4: "int4", 5: "int4_group"}
 MODE_LONG = {0: "int8_token_head", 1: "fp8e4m3_block_head", 2: "bf16_unquantized",
-             3: "fp8e4m3_static_tensor_scales", 4: "int4_token_head"}
+             3: "fp8e4m3_static_tensor_scales", 4: "int4_token_head",
+             5: "int4_scale_per_32_channels"}
 
 
 class HipEvents:
@@ -84,7 +85,8 @@ def make_workload(name, mode):
     kw = {} if mode is None else {"mode": {"int8": W.MODE_INT8, "fp8": W.MODE_FP8,
                                            "bf16": W.MODE_BF16,
                                            "fp8_tensor": W.MODE_FP8_TENSOR,
-                                           "int4": W.MODE_INT4}[mode]}
+                                           "int4": W.MODE_INT4,
+                                           "int4_group": W.MODE_INT4_GROUP}[mode]}
     makers = {"llama8b": W.llama8b, "fp8_append": W.fp8_append, "long_gqa": W.long_gqa,
               "verify_prefix": W.verify_prefix}
     if name not in makers:
@@ -355,7 +357,8 @@ def extras(res, lay, out_main, args, ev, prof):
     for i in range(3):
         bulk(i)
     bulk_us = bracket_us(ev, bulk, 10)
-    per_row = 2 * D + {0: D + 4, 1: D + 4.0 / wl.block_size, 2: 2 * D, 3: D, 4: D / 2 + 4}[wl.mode]
+    per_row = 2 * D + {0: D + 4, 1: D + 4.0 / wl.block_size, 2: 2 * D, 3: D, 4: D / 2 + 4,
+                       5: D / 2 + D / 8}[wl.mode]
     bulk_bytes = n_tok * wl.num_kv_heads * 2 * per_row
     res["prefill_write"] = {"tokens": n_tok, "sequences": n_seq, "us": bulk_us,
                             "bytes": bulk_bytes, "GB/s": bulk_bytes / bulk_us / 1e3,
@@ -479,7 +482,7 @@ def main():
                     help="seconds of untimed load before the warmup steps")
     ap.add_argument("--workload", default="llama8b",
                     help="the headline workload: llama8b, fp8_append, long_gqa or verify_prefix")
-    ap.add_argument("--mode", default=None, choices=["int8", "fp8", "bf16", "fp8_tensor", "int4"],
+    ap.add_argument("--mode", default=None, choices=["int8", "fp8", "bf16", "fp8_tensor", "int4", "int4_group"],
                     help="override the headline workload's cache mode (bf16 = the unquantized baseline)")
     ap.add_argument("--configs", default=None, choices=["all", "none"],
                     help="also measure the other benchmark configurations (default: all when "
@@ -535,7 +538,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.mode == 2 else "f16",   # the matrix instructions' operand type
         "dtype_detail": ("bf16 rows, bf16 MFMA operands, f32 accumulate and softmax" if wl.mode == 2 else
-                         "u4 codes, f16 MFMA operands, f32 accumulate and softmax" if wl.mode == 4 else
+                         "u4 codes, f16 MFMA operands, f32 accumulate and softmax" if wl.mode in (4, 5) else
                          "u8 codes, f16 MFMA operands, f32 accumulate and softmax"),
         "data": "synthetic" if not args.alias_blocks else "INVALID: aliased block tables (diagnostic)",
     }

@@ -55,8 +55,11 @@ typedef enum {
   KVQ_FP8E4M3_TENSOR = 3,     /* E4M3 codes with static per-tensor scales: one fp32 scale for
                                  all of the layer's K, one for all of its V, chosen by the
                                  caller beforehand and only read by the library */
-  KVQ_INT4_TOKEN_HEAD = 4     /* int4 codes in [-7,7], two per byte, one fp32 scale per
+  KVQ_INT4_TOKEN_HEAD = 4,    /* int4 codes in [-7,7], two per byte, one fp32 scale per
                                  (token, kv head); head_dim 128 only */
+  KVQ_INT4_GROUP32 = 5        /* the same codes and cache, one fp32 scale per (token, kv head,
+                                 group of 32 adjacent channels): "per-block dynamic scaling"
+                                 with a block of channels; head_dim 128 only */
 } kvq_mode_t;
 
 enum {
@@ -101,6 +104,8 @@ enum {
  *         e = off % 8
  * scales as for KVQ_INT8_TOKEN_HEAD.  The canonical form packs channel 2j (low nibble) and
  * 2j+1 (high nibble) of a token in byte j, 4-bit two's complement, rows of head_dim/2 bytes.
+ * KVQ_INT4_GROUP32: the cache of KVQ_INT4_TOKEN_HEAD; scales
+ *         f32 [num_blocks][2][num_kv_heads][block_size][head_dim / 32].
  * scales: f32 [num_blocks][2][num_kv_heads][block_size]   for KVQ_INT8_TOKEN_HEAD
  *         f32 [num_blocks][2][num_kv_heads]               for KVQ_FP8E4M3_BLOCK_HEAD
  * Supported: head_dim 64 or 128; block_size a power of two in [16, 256]. */
@@ -128,6 +133,8 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc);
  *   absmax/127 (0 for an all-zero row, whose codes are 0); code = round-half-even of the
  *   exact x/scale, clamped to [-127, 127].
  * KVQ_INT4_TOKEN_HEAD: as KVQ_INT8_TOKEN_HEAD with 7 in place of 127.
+ * KVQ_INT4_GROUP32: the same per group of 32 adjacent channels: each group has its own absmax,
+ *   scale and rounding.
  * KVQ_BF16_PLAIN: the rows are copied to their slots unchanged.
  * KVQ_FP8E4M3_TENSOR: code = encode(x / scales[kv]) (0x00 when the scale is 0), saturating at
  *   +-448; the scales are not modified.

@@ -16,7 +16,7 @@ bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   if (!d) { *err = KVQ_E_NULLPTR; return false; }
   if (d->mode != KVQ_INT8_TOKEN_HEAD && d->mode != KVQ_FP8E4M3_BLOCK_HEAD &&
       d->mode != KVQ_BF16_PLAIN && d->mode != KVQ_FP8E4M3_TENSOR &&
-      d->mode != KVQ_INT4_TOKEN_HEAD) {
+      d->mode != KVQ_INT4_TOKEN_HEAD && d->mode != KVQ_INT4_GROUP32) {
     *err = KVQ_E_BAD_MODE;
     return false;
   }
@@ -24,7 +24,7 @@ bool desc_ok(const kvq_cache_desc_t* d, int* err) {
   const bool bs_ok = bs >= 16 && bs <= 256 && (bs & (bs - 1)) == 0;
   if (d->num_blocks < 0 || !bs_ok || d->num_kv_heads <= 0 ||
       (d->head_dim != 64 && d->head_dim != 128) ||
-      (d->mode == KVQ_INT4_TOKEN_HEAD && d->head_dim != 128)) {
+      (kvq::is_int4(d->mode) && d->head_dim != 128)) {
     *err = KVQ_E_BAD_SHAPE;
     return false;
   }
@@ -86,7 +86,8 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   // (every product below is taken in a type that holds it: the arguments are only known to be
   // non-negative 32-bit numbers at this point)
   const int64_t rows = (int64_t)group * q_len;
-  const int64_t row_tiles = rows <= 16 ? 1 : 2;
+  // (the group-scaled int4 kernels hold one accumulator per channel group: one row tile)
+  const int64_t row_tiles = rows <= 16 || d->mode == KVQ_INT4_GROUP32 ? 1 : 2;
   const int64_t row_groups = (rows + 16 * row_tiles - 1) / (16 * row_tiles);
   const int64_t pairs = (int64_t)d->num_kv_heads * row_groups;
   // the flat list of 64-token groups can be no longer than this
@@ -106,7 +107,11 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
     // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
     // (an unquantized cache needs twice the registers per group: one wavefront per SIMD)
     const int64_t waves = auto_waves();
-    const int64_t resident = plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN ? waves : waves / 2;
+    // (so does the group-scaled int4 cache, for its four accumulators per logit)
+    const int64_t resident = plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN &&
+                                     d->mode != KVQ_INT4_GROUP32
+                                 ? waves
+                                 : waves / 2;
     plan->range_groups = 0;
     plan->num_waves = (int32_t)(flat_max < resident ? flat_max : resident);
   } else {
@@ -138,9 +143,8 @@ size_t kvq_scales_bytes(const kvq_cache_desc_t* desc) {
   int err;
   if (!desc_ok(desc, &err) || desc->mode == KVQ_BF16_PLAIN) return 0;
   if (desc->mode == KVQ_FP8E4M3_TENSOR) return 2 * sizeof(float);
-  const size_t per_block = (size_t)2 * desc->num_kv_heads *
-                           (desc->mode == KVQ_FP8E4M3_BLOCK_HEAD ? 1 : desc->block_size);
-  return (size_t)desc->num_blocks * per_block * sizeof(float);
+  return (size_t)desc->num_blocks * sizeof(float) *
+         kvq::block_scale_floats(desc->mode, desc->num_kv_heads, desc->block_size, desc->head_dim);
 }
 
 int kv_quant_write(const void* k, const void* v, const int64_t* slot_mapping,
@@ -428,9 +432,8 @@ static int block_copy(const void* pool_cache, const float* pool_scales,
     return KVQ_E_BAD_SHAPE;
   if (num == 0) return KVQ_OK;
   if (!pool_cache || !block_ids || !packed_cache) return KVQ_E_NULLPTR;
-  const bool block_scales = desc->mode == KVQ_INT8_TOKEN_HEAD ||
-                            desc->mode == KVQ_FP8E4M3_BLOCK_HEAD ||
-                            desc->mode == KVQ_INT4_TOKEN_HEAD;
+  const bool block_scales = kvq::block_scale_floats(desc->mode, desc->num_kv_heads,
+                                                    desc->block_size, desc->head_dim) != 0;
   if (block_scales && (!pool_scales || !packed_scales)) return KVQ_E_NULLPTR;
   if ((((uintptr_t)pool_cache | (uintptr_t)packed_cache) & 15) != 0) return KVQ_E_BAD_SHAPE;
   const hipError_t e = kvq::launch_block_copy(pool_cache, pool_scales, *desc, block_ids, num,

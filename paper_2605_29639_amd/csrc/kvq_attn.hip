@@ -131,14 +131,22 @@ __device__ inline int range_of(const Split& s, int f) {
 //   p.shared_groups are loaded through the caches rather than past them, because the caller
 //   said that other sequences of the batch read the same blocks (a common prefix).
 template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK, bool SHARED = false>
-__global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN) ? 2 : 1) void
+__global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN && MODE != KVQ_INT4_GROUP32) ? 2 : 1) void
 attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
   // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
-  constexpr bool INT4 = MODE == KVQ_INT4_TOKEN_HEAD;  // two codes per byte (head_dim 128)
-  // one fp32 scale per token and head, K and V
+  // int4 with one scale per (token, head, 32 channels): a matrix instruction contracts over
+  // exactly one group of channels, so QK^T keeps one accumulator per group and the logit is
+  // their sum weighted by the token's four K scales; P.V takes the probabilities times the V
+  // scale of the group the channel tile belongs to (four versions of the B operand)
+  constexpr bool GROUPED = MODE == KVQ_INT4_GROUP32;
+  constexpr bool INT4 = MODE == KVQ_INT4_TOKEN_HEAD || GROUPED;  // two codes per byte (head_dim 128)
+  // fp32 scales per token and head, K and V
   constexpr bool TOKEN_SCALE = MODE == KVQ_INT8_TOKEN_HEAD || INT4;
+  static_assert(!GROUPED || (NT == 1 && D == 128), "group scales: one row tile, head_dim 128");
+  constexpr int NG = GROUPED ? 4 : 1;  // scale groups per token
+  using ScaleT = std::conditional_t<GROUPED, floatx4, float>;  // a token's K (or V) scales
   constexpr int EB = PLAIN ? 2 : 1;                // bytes per cache element
   constexpr int RB = INT4 ? D / 2 : D * EB;        // bytes per token row in a tile
   constexpr int DT = D / 16;
@@ -263,10 +271,10 @@ attn_stream_kernel(const AttnArgs p) {
   const uint32_t block_stride = 2u * (uint32_t)H * tile_bytes;  // bytes per cache block
   const uint32_t k_lane = 64u * g4 + 16u * (m16 & 3);  // inside a 4-token quad
   const uint32_t v_lane = (uint32_t)H * tile_bytes + 16u * m16;  // inside a 16-token sub-block
-  const uint32_t s_block_stride = TOKEN_SCALE                    ? 2u * H * bs
+  const uint32_t s_block_stride = TOKEN_SCALE                    ? 2u * H * bs * NG
                                   : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
                                                                  : 2u * H;
-  const uint32_t s_kv = TOKEN_SCALE                    ? (uint32_t)H * bs
+  const uint32_t s_kv = TOKEN_SCALE                    ? (uint32_t)H * bs * NG
                         : (MODE == KVQ_FP8E4M3_TENSOR) ? 1u
                                                        : (uint32_t)H;
 
@@ -279,7 +287,7 @@ attn_stream_kernel(const AttnArgs p) {
   };
 
   // K codes and both scales of a group; also works out where the group's V codes are
-  auto load_k = [&](uintx4 (&kt)[4][KJ], float& sk, float& sv, const uint8_t*& vbase,
+  auto load_k = [&](uintx4 (&kt)[4][KJ], ScaleT& sk, ScaleT& sv, const uint8_t*& vbase,
                     const Cursor& c, int blk_k, int blk_v) {
     const int pos0 = c.g << 6, last_sb = ((c.L - 1) >> 4) << 4;
     const uint32_t h = (uint32_t)(c.pr / NRG);
@@ -288,10 +296,11 @@ attn_stream_kernel(const AttnArgs p) {
     const uint8_t* kbase =
         cache + (size_t)blk_k * block_stride + (h * tile_bytes + off_k * RB + k_lane);
     vbase = cache + (size_t)blk_v * block_stride + (h * tile_bytes + v_lane + off_v * RB);
-    const uint32_t s_lane = TOKEN_SCALE                    ? h * bs + m16 + off_v
+    const uint32_t s_lane = TOKEN_SCALE                    ? (h * bs + m16 + off_v) * NG
                             : (MODE == KVQ_FP8E4M3_TENSOR) ? 0u
                                                            : h;
-    const float* sp = scales + (size_t)blk_v * s_block_stride + s_lane;
+    const ScaleT* sp = (const ScaleT*)(scales + (size_t)blk_v * s_block_stride + s_lane);
+    constexpr uint32_t kSkip = GROUPED ? 4 : 1;  // floats per ScaleT
     if (SHARED && c.g < p.shared_groups) {  // blocks other sequences read too: keep them cached
 #pragma unroll
       for (int u = 0; u < 4; ++u)
@@ -299,7 +308,7 @@ attn_stream_kernel(const AttnArgs p) {
         for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * (4 * RB) + 256 * j);
       if constexpr (!PLAIN) {
         sk = *sp;
-        sv = sp[s_kv];
+        sv = sp[s_kv / kSkip];
       }
     } else {
 #pragma unroll
@@ -309,7 +318,7 @@ attn_stream_kernel(const AttnArgs p) {
           kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
       if constexpr (!PLAIN) {
         sk = __builtin_nontemporal_load(sp);
-        sv = __builtin_nontemporal_load(sp + s_kv);
+        sv = __builtin_nontemporal_load(sp + s_kv / kSkip);
       }
     }
     if constexpr (PLAIN) {
@@ -337,6 +346,8 @@ attn_stream_kernel(const AttnArgs p) {
   // ---- per-pair state: q as the B operand of QK^T, each row's causal length, the running
   // maximum / sum / accumulator ----
   Operand qb[NT][KS];
+  [[maybe_unused]] floatx4 SG[GROUPED ? 3 : 1][4];  // group scales: contractions of groups 1..3
+  [[maybe_unused]] half8 pbg[GROUPED ? 4 : 1][2];   // group scales: p x V scale, per group
   int nrow[NT];
   floatx4 acc[NT][DT];
   float m_run[NT], l_run[NT];
@@ -422,6 +433,12 @@ attn_stream_kernel(const AttnArgs p) {
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int u = 0; u < 4; ++u) S[nt][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (GROUPED) {
+#pragma unroll
+      for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) SG[g][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -436,9 +453,14 @@ attn_stream_kernel(const AttnArgs p) {
 #pragma unroll
           for (int st = 0; st < 4; ++st) {
             const half8 a = cvt_int4(raw[st]);
+            if constexpr (GROUPED) {  // step st = channel group st: its own accumulator
+              floatx4& dst = st == 0 ? S[0][u] : SG[st == 0 ? 0 : st - 1][u];
+              dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qb[0][st], dst, 0, 0, 0);
+            } else {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qb[nt][4 * j + st], S[nt][u], 0, 0, 0);
+              for (int nt = 0; nt < NT; ++nt)
+                S[nt][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qb[nt][4 * j + st], S[nt][u], 0, 0, 0);
+            }
           }
         } else {
           const half8 a0 = cvt8<MODE>(raw[0], raw[1]);
@@ -456,26 +478,58 @@ attn_stream_kernel(const AttnArgs p) {
   // online_softmax in kvq_attn_common.h, shared with the many-row kernel.
   // TAIL = some row's causal length ends inside the group: positions past a row's length are
   // masked and scales of never-written slots are ignored. ----
-  auto softmax_impl = [&](auto TAILC, floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
+  auto softmax_impl = [&](auto TAILC, floatx4 (&S)[NT][4], ScaleT sk, ScaleT sv, const Cursor& c,
                           Operand (&pb)[NT][2 * EB]) {
     constexpr bool TAIL = decltype(TAILC)::value;
     if constexpr (CEIL) {
-      ceil_x ^= __float_as_uint(sk) ^ __float_as_uint(sv);
+      if constexpr (GROUPED) ceil_x ^= __float_as_uint(sk[0] + sk[1] + sk[2] + sk[3] + sv[0] + sv[1] + sv[2] + sv[3]);
+      else ceil_x ^= __float_as_uint(sk) ^ __float_as_uint(sv);
       return;
     }
     const int pos0 = c.g << 6, L = c.L;
-    // this lane's scales: logit factor, log2 of the V scale and its inverse
-    float skp = sk * p.scale_log2;
-    float lsv = PLAIN ? 0.0f : __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
-    float rsv = PLAIN ? 1.0f : __builtin_amdgcn_exp2f(-lsv);
-    if (TOKEN_SCALE && TAIL && pos0 + 16 * g4 + m16 >= L) {
-      skp = 0.0f;  // a slot that was never written: its scales are not data
-      lsv = 0.0f;
-      rsv = 0.0f;
+    if constexpr (GROUPED) {
+#pragma clang fp contract(off)
+      // a slot that was never written: its scales are not data
+      const bool dead = TAIL && pos0 + 16 * g4 + m16 >= L;
+      float skp[4], ratio[4];
+      const float sv_max = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+      const float lsv = dead ? 0.0f : __builtin_amdgcn_logf(fmaxf(sv_max, kMinVScale));
+      const float rsv = dead ? 0.0f : __builtin_amdgcn_exp2f(-lsv);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        skp[g] = dead ? 0.0f : sk[g] * p.scale_log2;
+        ratio[g] = dead ? 0.0f : sv[g] * rsv;  // this group's V scale relative to the token's largest
+      }
+      // the logit: the four groups' contractions weighted by the token's four K scales
+      static_for<16>([&](auto I) {
+        constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+        float z = S[0][u][i] * row_bcast<tix>(skp[0]);
+#pragma unroll
+        for (int g = 1; g < 4; ++g) z = z + SG[g - 1][u][i] * row_bcast<tix>(skp[g]);
+        S[0][u][i] = z;
+      });
+      online_softmax<MODE, NT, DT, TAIL>(S, 1.0f, lsv, rsv, pos0 + 16 * g4, nrow, m_run, l_run, acc, pb);
+      // S now holds the probabilities times the largest V scale: one B operand per group
+      static_for<16>([&](auto I) {
+        constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          pbg[g][tix >> 3][tix & 7] = (_Float16)(S[0][u][i] * row_bcast<tix>(ratio[g]));
+      });
+    } else {
+      // this lane's scales: logit factor, log2 of the V scale and its inverse
+      float skp = sk * p.scale_log2;
+      float lsv = PLAIN ? 0.0f : __builtin_amdgcn_logf(fmaxf(sv, kMinVScale));
+      float rsv = PLAIN ? 1.0f : __builtin_amdgcn_exp2f(-lsv);
+      if (TOKEN_SCALE && TAIL && pos0 + 16 * g4 + m16 >= L) {
+        skp = 0.0f;  // a slot that was never written: its scales are not data
+        lsv = 0.0f;
+        rsv = 0.0f;
+      }
+      online_softmax<MODE, NT, DT, TAIL>(S, skp, lsv, rsv, pos0 + 16 * g4, nrow, m_run, l_run, acc, pb);
     }
-    online_softmax<MODE, NT, DT, TAIL>(S, skp, lsv, rsv, pos0 + 16 * g4, nrow, m_run, l_run, acc, pb);
   };
-  auto softmax = [&](floatx4 (&S)[NT][4], float sk, float sv, const Cursor& c,
+  auto softmax = [&](floatx4 (&S)[NT][4], ScaleT sk, ScaleT sv, const Cursor& c,
                      Operand (&pb)[NT][2 * EB]) {
     if ((c.g << 6) + 64 > c.L - p.q_len + 1)
       softmax_impl(std::true_type{}, S, sk, sv, c, pb);
@@ -527,10 +581,15 @@ attn_stream_kernel(const AttnArgs p) {
         for (int par = 0; par < 2; ++par) {
           const half8 a0 = cvt_int4(vt[x][2 * par]);
           const half8 a1 = cvt_int4(vt[x][2 * par + 1]);
+          if constexpr (GROUPED) {  // piece x = channels 32 x .. 32 x + 31 = group x
+            acc[0][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, pbg[x][0], acc[0][2 * x + par], 0, 0, 0);
+            acc[0][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, pbg[x][1], acc[0][2 * x + par], 0, 0, 0);
+          } else {
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, pb[nt][0], acc[nt][2 * x + par], 0, 0, 0);
-            acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, pb[nt][1], acc[nt][2 * x + par], 0, 0, 0);
+            for (int nt = 0; nt < NT; ++nt) {
+              acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, pb[nt][0], acc[nt][2 * x + par], 0, 0, 0);
+              acc[nt][2 * x + par] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, pb[nt][1], acc[nt][2 * x + par], 0, 0, 0);
+            }
           }
         }
       return;
@@ -581,7 +640,7 @@ attn_stream_kernel(const AttnArgs p) {
   bool from_start = cur.g == 0;  // did this wave see the current pair from its first group
   if constexpr (DEPTH == 1) {
     uintx4 kt[4][KJ], vt[VW];
-    float sk, sv;
+    ScaleT sk, sv;
     const uint8_t* vbase;
     {
       int bk0, bv0;
@@ -605,7 +664,7 @@ attn_stream_kernel(const AttnArgs p) {
       if (i == q2) __builtin_amdgcn_s_setprio(1);
       if (i == q3) __builtin_amdgcn_s_setprio(0);
       qk(kt, S);
-      const float sk_cur = sk, sv_cur = sv;
+      const ScaleT sk_cur = sk, sv_cur = sv;
       load_k(kt, sk, sv, vbase, nxt, blk_k, blk_v);
       if (i + 2 < count) advance(nn);
       fetch_entries(nn, blk_k, blk_v);
@@ -632,7 +691,7 @@ attn_stream_kernel(const AttnArgs p) {
     // copies, and every load in it is unconditional (a load under a usually-true condition
     // would make the compiler's wait counts as strict as if the load were never issued).
     uintx4 kta[4][KJ], vta[VW], ktb[4][KJ], vtb[VW];
-    float ska, sva, skb, svb;
+    ScaleT ska, sva, skb, svb;
     const uint8_t* vbase;
     int tk0, tv0, tk1, tv1;  // table entries of the group after the one being loaded
     Cursor c1 = nxt, c2 = nxt, c3 = nxt;  // groups i+1, i+2, i+3 (clamped to the range's last)
@@ -819,10 +878,14 @@ void launch_variant(const AttnArgs& a, hipStream_t stream) {
       return;
     }
   }
-  if (a.row_tiles == 1)
+  if constexpr (MODE == KVQ_INT4_GROUP32) {  // (the plan gives this format one row tile always)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, CEIL, 1, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
-  else
-    hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, CEIL, kDepth, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  } else {
+    if (a.row_tiles == 1)
+      hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, CEIL, 1, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
+    else
+      hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, CEIL, kDepth, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
+  }
 }
 
 template <int MODE, int D>
@@ -879,6 +942,8 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
                           : launch_stream<KVQ_FP8E4M3_TENSOR, 64>(a, stream);
   else if (a.mode == KVQ_INT4_TOKEN_HEAD)
     e = launch_stream<KVQ_INT4_TOKEN_HEAD, 128>(a, stream);  // (the only head_dim it takes)
+  else if (a.mode == KVQ_INT4_GROUP32)
+    e = launch_stream<KVQ_INT4_GROUP32, 128>(a, stream);
   else
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);

@@ -39,9 +39,21 @@ __host__ __device__ inline int v_elem16(int off, int d, int head_dim) {
   return (off >> 4) * (16 * head_dim) + ((off >> 3) & 1) * (8 * head_dim) + d * 8 + (off & 7);
 }
 __host__ __device__ inline int elem_bytes(int mode) { return mode == KVQ_BF16_PLAIN ? 2 : 1; }
+__host__ __device__ inline bool is_int4(int mode) {
+  return mode == KVQ_INT4_TOKEN_HEAD || mode == KVQ_INT4_GROUP32;
+}
 // bytes one token's head_dim values take in the cache
 __host__ __device__ inline int row_bytes(int mode, int head_dim) {
-  return mode == KVQ_BF16_PLAIN ? 2 * head_dim : mode == KVQ_INT4_TOKEN_HEAD ? head_dim / 2 : head_dim;
+  return mode == KVQ_BF16_PLAIN ? 2 * head_dim : is_int4(mode) ? head_dim / 2 : head_dim;
+}
+// fp32 scales that belong to one block of the pool (0: the format's scales are not per block)
+__host__ __device__ inline size_t block_scale_floats(int mode, int num_kv_heads, int block_size,
+                                                     int head_dim) {
+  const size_t token_heads = (size_t)2 * num_kv_heads * block_size;
+  return mode == KVQ_INT8_TOKEN_HEAD || mode == KVQ_INT4_TOKEN_HEAD ? token_heads
+         : mode == KVQ_INT4_GROUP32      ? token_heads * (head_dim / 32)
+         : mode == KVQ_FP8E4M3_BLOCK_HEAD ? (size_t)2 * num_kv_heads
+                                          : 0;
 }
 
 // int4 (head_dim 128): byte offset, inside a tile, of the 32-bit word that holds logical element

@@ -355,7 +355,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 }  // namespace
 
 bool prefill_applies(const AttnArgs& a) {
-  return a.rows >= kRowsPerWorkgroup;
+  // (the group-scaled int4 format has no many-row kernel: its row groups go through the
+  // streaming kernel)
+  return a.rows >= kRowsPerWorkgroup && a.mode != KVQ_INT4_GROUP32;
 }
 
 hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {

@@ -39,13 +39,14 @@ __device__ inline float int8_code_f32(float x, float s, float inv, bool fast) {
   return r;
 }
 
-// Maximum over the CL (8 or 16) adjacent lanes that share a row of 16.
+// Maximum over the CL (4, 8 or 16) adjacent lanes that share a row of 16.
 template <int CL>
 __device__ inline uint32_t row_max_u32(uint32_t v) {
   auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
   v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
   v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  if constexpr (CL >= 8)
+    v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
   if constexpr (CL == 16)
     v = mx(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
   return v;

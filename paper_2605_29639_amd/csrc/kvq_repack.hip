@@ -133,11 +133,8 @@ hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
                              hipStream_t stream) {
   const uint32_t block_bytes =
       2u * desc.num_kv_heads * desc.block_size * row_bytes(desc.mode, desc.head_dim);
-  const uint32_t scale_floats =
-      desc.mode == KVQ_INT8_TOKEN_HEAD || desc.mode == KVQ_INT4_TOKEN_HEAD
-          ? 2u * desc.num_kv_heads * desc.block_size
-      : desc.mode == KVQ_FP8E4M3_BLOCK_HEAD ? 2u * desc.num_kv_heads
-                                            : 0u;  // no per-block scales
+  const uint32_t scale_floats = (uint32_t)block_scale_floats(desc.mode, desc.num_kv_heads,
+                                                             desc.block_size, desc.head_dim);
   const uint32_t pieces = (block_bytes + 4095u) / 4096u;
   hipLaunchKernelGGL(block_copy_kernel, dim3((unsigned)num * pieces), dim3(256), 0, stream,
                      (uint8_t*)pool_cache, (float*)pool_scales, (uint8_t*)packed_cache,
@@ -148,11 +145,11 @@ hipError_t launch_block_copy(const void* pool_cache, const float* pool_scales,
 hipError_t launch_repack(const void* src, void* dst, const kvq_cache_desc_t& desc,
                          bool to_canonical, hipStream_t stream) {
   const size_t total = (size_t)desc.num_blocks * 2 * desc.num_kv_heads * desc.block_size *
-                       (desc.mode == KVQ_INT4_TOKEN_HEAD ? desc.head_dim / 2 : desc.head_dim);
+                       (is_int4(desc.mode) ? desc.head_dim / 2 : desc.head_dim);
   if (total == 0) return hipSuccess;
   size_t blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
-  if (desc.mode == KVQ_INT4_TOKEN_HEAD) {
+  if (is_int4(desc.mode)) {
     hipLaunchKernelGGL(repack_int4_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                        (const uint8_t*)src, (uint8_t*)dst, total, desc.num_kv_heads,
                        desc.block_size, to_canonical);

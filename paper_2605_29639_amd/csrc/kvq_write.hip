@@ -680,15 +680,18 @@ __device__ inline uint32_t int4_nib(float x, float s) {  // stored nibble of x /
 // the same call (a skipped token in mid sub-block, tokens not in slot order) are handled by
 // other wavefronts and share those words.  The nibbles of different tokens are disjoint, so the
 // result does not depend on the order in which the wavefronts arrive.
+// GROUPED: one scale per 32 adjacent channels (the 16 lanes of a row own them) instead of one
+// per token and head; the scales of a token are then 4 adjacent floats.
+template <bool GROUPED>
 __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                 uint8_t* __restrict__ cache, float* __restrict__ scales, int H,
                                 int bs, int kv, int h, int t0, int64_t slot0, int run, int lane) {
-  constexpr int D = 128;
+  constexpr int D = 128, NG = GROUPED ? 4 : 1;
   const int64_t blk = slot0 >> __builtin_ctz(bs);
   const int off0 = (int)(slot0 - blk * bs);
   const int so = off0 & 15;
   uint8_t* tile = cache + (size_t)tile_offset(blk, kv, h, H, bs, D / 2);
-  float* srow = scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0;
+  float* srow = scales + ((((size_t)blk * 2 + kv) * H + h) * bs + off0) * NG;
   const uint16_t* src = (kv ? v : k) + ((size_t)t0 * H + h) * D + lane * 2;
   const size_t tstride = (size_t)H * D;
   unsigned long long img[2] = {0, 0}, mask = 0;  // V rows of the lane's two channels
@@ -696,7 +699,7 @@ __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* 
     const uint32_t w = *(const uint32_t*)(src + i * tstride);
     const uint32_t b0 = w & 0xFFFFu, b1 = w >> 16;
     uint32_t amax = (b0 & 0x7FFFu) > (b1 & 0x7FFFu) ? (b0 & 0x7FFFu) : (b1 & 0x7FFFu);
-    amax = wave_max_u32(amax);
+    amax = GROUPED ? row_max_u32<16>(amax) : wave_max_u32(amax);
     const float s = (amax == 0) ? 0.0f : (float)((double)bf16_bits_to_float(amax) / 7.0);
     const uint32_t n0 = (amax == 0) ? 8u : int4_nib(bf16_bits_to_float(b0), s);
     const uint32_t n1 = (amax == 0) ? 8u : int4_nib(bf16_bits_to_float(b1), s);
@@ -713,7 +716,7 @@ __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* 
       img[1] |= (unsigned long long)n1 << sh;
       mask |= 15ull << sh;
     }
-    if (lane == 0) srow[i] = s;
+    if (GROUPED ? (lane & 15) == 0 : lane == 0) srow[i * NG + (GROUPED ? lane >> 4 : 0)] = s;
   }
   if (kv == 1) {
 #pragma unroll
@@ -735,6 +738,7 @@ __device__ inline void int4_run(const uint16_t* __restrict__ k, const uint16_t* 
   }
 }
 
+template <bool GROUPED>
 __global__ __launch_bounds__(kWaves * 64) void write_int4_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
@@ -751,16 +755,18 @@ __global__ __launch_bounds__(kWaves * 64) void write_int4_kernel(
   if (t0 > 0 && so > 0 && slot_mapping[t0 - 1] == slot0 - 1) return;  // not a run's first token
   int run = 1;
   while (run < 16 - so && t0 + run < num_tokens && slot_mapping[t0 + run] == slot0 + run) ++run;
-  int4_run(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+  int4_run<GROUPED>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
 }
 
 // A whole sub-block with 16-byte loads, as for int8: a lane owns 8 channels (8 c .. 8 c + 7,
 // c = lane % 16) of 4 tokens.  K (tokens 4 i + g): the lane's eight codes of a token are one
 // whole word.  V (tokens 4 g + i): the lane's four tokens of a channel are the nibbles
 // 2a, 2a+1 (one byte) and 2a+4, 2a+5 (another byte) of the channel's word g / 2, a = g % 2.
+template <bool GROUPED>
 __device__ inline void int4_subblock(const uint16_t* __restrict__ src, size_t tstride,
                                      uint8_t* __restrict__ tile, float* __restrict__ srow,
                                      int kv, int off0, int lane) {
+  constexpr int NG = GROUPED ? 4 : 1;  // scales per token; a group of 32 channels = 4 lanes
   const int c = lane & 15, g = lane >> 4;
   uint4 raw[4];
   int tok[4];
@@ -780,7 +786,7 @@ __device__ inline void int4_subblock(const uint16_t* __restrict__ src, size_t ts
       amax = amax > lo ? amax : lo;
       amax = amax > hi ? amax : hi;
     }
-    amax = row_max_u32<16>(amax);
+    amax = GROUPED ? row_max_u32<4>(amax) : row_max_u32<16>(amax);
     const float a = bf16_bits_to_float(amax);
     const float s = (amax == 0) ? 0.0f : __fdiv_rn(a, 7.0f);
     const bool fast = s > 1e-30f;
@@ -799,7 +805,7 @@ __device__ inline void int4_subblock(const uint16_t* __restrict__ src, size_t ts
       else vnib[e][i] = nib;
     }
     if (kv == 0) *(uint32_t*)(tile + int4_k_word(off0 + tok[i], 8 * c)) = kword;
-    if (c == 0) srow[tok[i]] = s;
+    if (GROUPED ? (c & 3) == 0 : c == 0) srow[tok[i] * NG + (GROUPED ? c >> 2 : 0)] = s;
   }
   if (kv == 1) {
     const int a = g & 1;
@@ -812,6 +818,7 @@ __device__ inline void int4_subblock(const uint16_t* __restrict__ src, size_t ts
   }
 }
 
+template <bool GROUPED>
 __global__ __launch_bounds__(kWaves * 64) void write_int4_bulk_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
@@ -844,11 +851,12 @@ __global__ __launch_bounds__(kWaves * 64) void write_int4_bulk_kernel(
     if (run == 16) {
       const int64_t blk = slot0 >> __builtin_ctz(bs);
       const int off0 = (int)(slot0 - blk * bs);
-      int4_subblock((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
-                    cache + (size_t)tile_offset(blk, kv, h, H, bs, D / 2),
-                    scales + (((size_t)blk * 2 + kv) * H + h) * bs + off0, kv, off0, lane);
+      int4_subblock<GROUPED>((kv ? v : k) + ((size_t)t0 * H + h) * D, tstride,
+                             cache + (size_t)tile_offset(blk, kv, h, H, bs, D / 2),
+                             scales + ((((size_t)blk * 2 + kv) * H + h) * bs + off0) * (GROUPED ? 4 : 1),
+                             kv, off0, lane);
     } else {
-      int4_run(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
+      int4_run<GROUPED>(k, v, cache, scales, H, bs, kv, h, t0, slot0, run, lane);
     }
   }
 }
@@ -902,12 +910,19 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
   hipLaunchKernelGGL((KERNEL<DD>), dim3(grid), block, 0, stream, kk, vv, slot_mapping,        \
                      num_tokens, c, scales, desc.num_kv_heads, desc.block_size,               \
                      (int32_t)(desc.mode == KVQ_FP8E4M3_TENSOR))
-  if (desc.mode == KVQ_INT4_TOKEN_HEAD) {
-    if (bulk)
-      hipLaunchKernelGGL(write_int4_bulk_kernel, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+  if (is_int4(desc.mode)) {
+    const bool grouped = desc.mode == KVQ_INT4_GROUP32;
+    if (bulk && grouped)
+      hipLaunchKernelGGL(write_int4_bulk_kernel<true>, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+    else if (bulk)
+      hipLaunchKernelGGL(write_int4_bulk_kernel<false>, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+    else if (grouped)
+      hipLaunchKernelGGL(write_int4_kernel<true>, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
                          num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
     else
-      hipLaunchKernelGGL(write_int4_kernel, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
+      hipLaunchKernelGGL(write_int4_kernel<false>, dim3(grid), block, 0, stream, kk, vv, slot_mapping,
                          num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
   } else if (desc.mode == KVQ_BF16_PLAIN) {
     const unsigned g = (unsigned)(((int64_t)num_tokens * desc.num_kv_heads * 2 + kWaves - 1) / kWaves);

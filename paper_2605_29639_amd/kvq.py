@@ -12,6 +12,7 @@ MODE_FP8 = 1    # KVQ_FP8E4M3_BLOCK_HEAD
 MODE_BF16 = 2   # KVQ_BF16_PLAIN (unquantized baseline)
 MODE_FP8_TENSOR = 3  # KVQ_FP8E4M3_TENSOR (static per-tensor scales)
 MODE_INT4 = 4    # KVQ_INT4_TOKEN_HEAD (head_dim 128)
+MODE_INT4_GROUP = 5   # KVQ_INT4_GROUP32 (head_dim 128; one scale per 32 channels)
 
 OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP, E_BAD_INDEX = 0, -1, -2, -3, -4, -5, -6
 
@@ -36,11 +37,13 @@ class CacheDesc(C.Structure):
 
     def cache_shape(self):
         return (self.num_blocks, 2, self.num_kv_heads, self.block_size,
-                self.head_dim // 2 if self.mode == MODE_INT4 else self.head_dim)
+                self.head_dim // 2 if self.mode in (MODE_INT4, MODE_INT4_GROUP) else self.head_dim)
 
     def scales_shape(self):
         if self.mode in (MODE_INT8, MODE_INT4):
             return (self.num_blocks, 2, self.num_kv_heads, self.block_size)
+        if self.mode == MODE_INT4_GROUP:
+            return (self.num_blocks, 2, self.num_kv_heads, self.block_size, self.head_dim // 32)
         if self.mode == MODE_BF16:
             return (0,)
         if self.mode == MODE_FP8_TENSOR:
@@ -155,7 +158,7 @@ def alloc_cache(desc, device="cuda", zero=True):
     cache = make(nbytes, dtype=torch.uint8, device=device)
     if zero and desc.mode == MODE_INT8:
         cache.fill_(0x80)
-    if zero and desc.mode == MODE_INT4:
+    if zero and desc.mode in (MODE_INT4, MODE_INT4_GROUP):
         cache.fill_(0x88)  # nibbles are stored as code + 8
     scales = make(sbytes // 4, dtype=torch.float32, device=device).view(desc.scales_shape())
     return cache, scales
@@ -289,7 +292,7 @@ def _any(t, dtype, name):
 def packed_sizes(desc, num):
     """(cache bytes, scale floats) of `num` packed blocks."""
     nb = max(desc.num_blocks, 1)
-    per_block_scales = desc.mode in (MODE_INT8, MODE_FP8, MODE_INT4)
+    per_block_scales = desc.mode in (MODE_INT8, MODE_FP8, MODE_INT4, MODE_INT4_GROUP)
     return (num * (lib().kvq_cache_bytes(desc) // nb),
             num * (lib().kvq_scales_bytes(desc) // nb // 4) if per_block_scales else 0)
 

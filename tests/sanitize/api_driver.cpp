@@ -27,7 +27,7 @@ hipError_t launch_repack(const void*, void*, const kvq_cache_desc_t&, bool, hipS
 
 int main() {
   void* fake = (void*)0x1000;
-  const int modes[5] = {0, 1, 2, 3, 4};
+  const int modes[6] = {0, 1, 2, 3, 4, 5};
   for (int mode : modes) {
     for (int bs = 16; bs <= 256; bs *= 2) {
       kvq_cache_desc_t d = {mode, 1000, bs, 8, 128};
@@ -49,6 +49,7 @@ int main() {
           EXPECT((char*)a.ws_acc == ws && (char*)a.ws_ml > ws && (char*)a.ws_prefix > (char*)a.ws_ml);
           EXPECT((char*)(a.ws_prefix + batch + 1) <= ws + need);
           EXPECT(a.num_waves >= 1 && a.pairs_per_seq == 8 * a.num_row_groups);
+          EXPECT(mode != 5 || a.row_tiles == 1);
           EXPECT(paged_decode_attn(fake, fake, (const float*)fake, &d, (const int32_t*)fake, max_blocks,
                                    (const int32_t*)fake, batch, q_len, Hq, max_len, 0.1f, chunk,
                                    (float*)fake, ws, need - 1, nullptr) == KVQ_E_WORKSPACE);

@@ -59,6 +59,9 @@ def test_sizes():
     assert L.kvq_cache_bytes(C.byref(d(mode=4, D=128))) == 8 * 2 * 2 * 16 * 64    # int4: two codes a byte
     assert L.kvq_scales_bytes(C.byref(d(mode=4, D=128))) == 8 * 2 * 2 * 16 * 4
     assert L.kvq_cache_bytes(C.byref(d(mode=4, D=64))) == 0                       # head_dim 128 only
+    assert L.kvq_cache_bytes(C.byref(d(mode=5, D=128))) == 8 * 2 * 2 * 16 * 64    # int4, group scales:
+    assert L.kvq_scales_bytes(C.byref(d(mode=5, D=128))) == 8 * 2 * 2 * 16 * 4 * 4  # four per token-head
+    assert L.kvq_cache_bytes(C.byref(d(mode=5, D=64))) == 0
     assert L.kvq_cache_bytes(C.byref(d(D=96))) == 0
     assert L.kvq_cache_bytes(None) == 0
 
@@ -133,6 +136,10 @@ def test_attn_argument_checks():
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
         (2048 + 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
+    # the group-scaled int4 format: one row tile whatever the row count, one wavefront per SIMD
+    g4 = kvq.make_desc(5, 1000, 16, 8, 128)
+    assert L.paged_decode_attn_workspace_bytes(C.byref(g4), 128, 4, 64, 16384, 0) == \
+        (1024 + 128 * 8 * 2) * 16 * (128 + 2) * 4 + 132 * 4
     # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
         (1024 + 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4

@@ -34,11 +34,11 @@ def check(wl, chunks=(0,), tol=TOL):
     return errs
 
 
-MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4]
+MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4, W.MODE_INT4_GROUP]
 
 
 def skip_unsupported(mode, D):
-    if mode == W.MODE_INT4 and D != 128:
+    if mode in (W.MODE_INT4, W.MODE_INT4_GROUP) and D != 128:
         pytest.skip("int4 takes head_dim 128 only")
 
 
@@ -110,7 +110,7 @@ def test_stale_bytes_after_the_last_position_are_never_used(mode, q_len):
     """Unwritten slots hold NaN codes / NaN or huge scales; block-table entries past the last
     block are -1.  The output must not change and must stay finite."""
     import torch
-    D = 128 if mode == W.MODE_INT4 else 64
+    D = 128 if mode in (W.MODE_INT4, W.MODE_INT4_GROUP) else 64
     lens = [max(l, q_len) for l in (37, 100, 64, 3)]
     wl = W.custom("stale", mode, lens, q_len, 4 if q_len == 1 else 8, 2, D, 16, seed=8)
     oc, osc = oracle_fill(wl)
@@ -125,7 +125,7 @@ def test_stale_bytes_after_the_last_position_are_never_used(mode, q_len):
             dirty_c[blk, :, :, off, :] = 0x7FC0 if (blk + off) % 2 else 0xFF80
         else:
             dirty_c[blk, :, :, off, :] = 0x80 if mode == W.MODE_INT8 else 0x7F
-        if mode in (W.MODE_INT8, W.MODE_INT4):
+        if mode in (W.MODE_INT8, W.MODE_INT4, W.MODE_INT4_GROUP):
             dirty_s[blk, :, :, off] = np.nan if (blk + off) % 2 else 3e38
     if mode == W.MODE_FP8:
         dead_blocks = ~live.any(axis=1)
@@ -193,7 +193,7 @@ def test_random_shapes(seed):
     size, cache mode and split granule all drawn from a seeded generator."""
     rng = np.random.default_rng(7000 + seed)
     D = int(rng.choice([64, 128]))
-    modes = [m for m in MODES if not (m == W.MODE_INT4 and D != 128)]
+    modes = [m for m in MODES if not (m in (W.MODE_INT4, W.MODE_INT4_GROUP) and D != 128)]
     mode = int(rng.choice(modes))
     bs = int(rng.choice([16, 32, 64, 128]))
     Hkv = int(rng.choice([1, 2, 3]))

@@ -18,12 +18,12 @@ def canon(t, desc):
 
 @pytest.mark.parametrize("host", [False, True], ids=["device", "pinned_host"])
 @pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR,
-                                  W.MODE_INT4])
+                                  W.MODE_INT4, W.MODE_INT4_GROUP])
 @pytest.mark.parametrize("bs,D,H", [(16, 128, 8), (64, 64, 3)])
 def test_export_then_import_elsewhere(mode, host, bs, D, H):
     import torch
     from paper_2605_29639_amd import kvq
-    if mode == W.MODE_INT4 and D != 128:
+    if mode in (W.MODE_INT4, W.MODE_INT4_GROUP) and D != 128:
         pytest.skip("int4 takes head_dim 128 only")
     wl = W.custom("blocks", mode, [300, 77, 150], 1, H, H, D, bs, seed=5 + bs + mode)
     oc, osc = oracle_fill(wl)
@@ -41,7 +41,7 @@ def test_export_then_import_elsewhere(mode, host, bs, D, H):
     want_c, want_s = oracle.blocks_export(oc, osc, mode, ids)
     pdesc = kvq.make_desc(mode, n, bs, H, D)          # the packed area is a pool of n blocks
     assert np.array_equal(canon(pc.cuda(), pdesc), want_c)
-    if mode in (W.MODE_INT8, W.MODE_FP8, W.MODE_INT4):
+    if mode in (W.MODE_INT8, W.MODE_FP8, W.MODE_INT4, W.MODE_INT4_GROUP):
         assert np.array_equal(ps.cpu().numpy().view(np.uint32).reshape(want_s.shape),
                               want_s.view(np.uint32))
     # import into a second pool at other places

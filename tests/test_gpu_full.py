@@ -99,7 +99,7 @@ def test_unquantized_baseline_full_size():
     compare_on_sample(wl, chunks=(0,), seqs=sample_sequences(wl, extra=0))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT4, W.MODE_FP8_TENSOR])
+@pytest.mark.parametrize("mode", [W.MODE_INT4, W.MODE_INT4_GROUP, W.MODE_FP8_TENSOR])
 def test_other_formats_full_size(mode):
     """Configuration 2's shapes with int4 per token-head codes and with e4m3 codes under static
     per-tensor scales."""

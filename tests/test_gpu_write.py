@@ -10,11 +10,11 @@ from paper_2605_29639_amd import workloads as W
 from helpers import bits_to_bf16_tensor, gpu_desc, gpu_fill, oracle_fill
 
 
-ALL_MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4]
+ALL_MODES = [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4, W.MODE_INT4_GROUP]
 
 
 def skip_unsupported(mode, D):
-    if mode == W.MODE_INT4 and D != 128:
+    if mode in (W.MODE_INT4, W.MODE_INT4_GROUP) and D != 128:
         pytest.skip("int4 takes head_dim 128 only")
 
 
@@ -66,7 +66,8 @@ def test_ragged_shapes_bulk_write(mode, shape):
     assert_pool_equal(wl, fetch(cache, scales, desc), oracle_fill(wl))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4,
+                                  W.MODE_INT4_GROUP])
 @pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1)])
 def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     """Thousands of tokens in one call (the prefill kernels): ragged sequences back to back, so
@@ -95,7 +96,7 @@ def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
         k, v = wl.kv_rows(b, lo, L)
         kf, vf = W.bf16_bits_to_f32(k), W.bf16_bits_to_f32(v)
         if b == 0:
-            qmax = {W.MODE_INT8: 127.0, W.MODE_INT4: 7.0}.get(mode, 448.0)
+            qmax = {W.MODE_INT8: 127.0, W.MODE_INT4: 7.0, W.MODE_INT4_GROUP: 7.0}.get(mode, 448.0)
             vf[64:128] = np.round(vf[64:128] * 16) / 2   # half-integers ...
             vf[64:128, :, 0] = qmax                      # ... at scale exactly 1: ties
             kf[128:160] *= np.float32(2.0 ** -120)       # scales below the normal fp32 range
@@ -164,11 +165,11 @@ def test_chunked_prefill_then_appends(mode):
     assert_pool_equal(wl, fetch(cache, scales, desc), (oc, osc))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_INT4])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_INT4, W.MODE_INT4_GROUP])
 def test_zero_rows_negative_zero_skipped_tokens_and_stale_pool(mode):
     import torch
     from paper_2605_29639_amd import kvq
-    D = 128 if mode == W.MODE_INT4 else 64
+    D = 128 if mode in (W.MODE_INT4, W.MODE_INT4_GROUP) else 64
     wl = W.custom("edge", mode, [48], 1, 2, 2, D, 16, seed=3)
     k, v = wl.kv_rows(0, 0, 48)
     k[3] = 0                     # all-zero K row (both heads)
@@ -311,7 +312,8 @@ def test_random_slot_patterns(mode, num_tokens, bs):
     assert_pool_equal(None, fetch(cache, scales, desc), (oc, osc))
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_BF16, W.MODE_FP8_TENSOR, W.MODE_INT4,
+                                  W.MODE_INT4_GROUP])
 @pytest.mark.parametrize("num_tokens", [150, 1500])      # per-run kernels, prefill kernels
 @pytest.mark.parametrize("bs", [16, 64])
 def test_tokens_in_any_order_with_skips_anywhere(mode, num_tokens, bs):
