@@ -99,9 +99,9 @@ __device__ inline half8 cvt8(uint32_t x0, uint32_t x1) {
 // the token-scaled formats, the same in every lane otherwise); pos_lane = position of the
 // lane's first token; nrow = causal length of the lane's row per tile.  Out: pb, the
 // probabilities times the V scale as the B operand of P.V (f16 scaled by 2^10, or two bf16
-// terms for an unquantized cache); S is left holding those probabilities in fp32; the running
-// maximum m_run (of logit + lsv, base 2) and sum l_run are updated and acc is rescaled when a
-// maximum moved.
+// terms for an unquantized cache) (for the group-scaled int4 format S is left holding those
+// probabilities in fp32 instead); the running maximum m_run (of logit + lsv, base 2) and sum
+// l_run are updated and acc is rescaled when a maximum moved.
 // TAIL: some row's causal length ends inside the group, so positions are masked.
 // The arithmetic on broadcast operands is kept as separate multiply / add so that the row
 // broadcast rides on the instruction itself (v_mul_f32_dpp, v_add_f32_dpp) instead of costing
@@ -153,7 +153,7 @@ __device__ inline void online_softmax(floatx4 (&S)[NT][4], float skp, float lsv,
     static_for<16>([&](auto I) {
       constexpr int tix = decltype(I)::value, u = tix >> 2, i = tix & 3;
       const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
-      S[nt][u][i] = pr;  // left for a caller that scales the probabilities once more
+      if constexpr (MODE == KVQ_INT4_GROUP32) S[nt][u][i] = pr;  // its caller scales them once more
       if constexpr (TOKEN_SCALE) {
         const float t = pr * row_bcast<tix>(rsv);
         lsum = lsum + t;
