@@ -119,12 +119,13 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
     plan->num_waves = (int32_t)((flat_max + plan->range_groups - 1) / plan->range_groups);
   }
   if (plan->num_waves < 1) plan->num_waves = 1;
-  // one partial per (wavefront range, pair) crossing: numbered wave + pair index
-  const size_t slots = (size_t)plan->num_waves + (size_t)batch * plan->pairs_per_seq;
+  // one partial per (wavefront range, pair) crossing, numbered wave + pair index; twice the
+  // pairs, since a shared prefix splits every pair's groups into two parts of the list
+  const size_t slots = (size_t)plan->num_waves + 2 * (size_t)batch * plan->pairs_per_seq;
   const size_t slot_rows = slots * 16 * plan->row_tiles;
   plan->acc_floats = slot_rows * d->head_dim;
   plan->ml_floats = slot_rows * 2;
-  plan->prefix_ints = ((size_t)batch + 1 + 3) & ~(size_t)3;
+  plan->prefix_ints = ((size_t)batch + 2 + 3) & ~(size_t)3;  // prefix sums, prefix length
   return true;
 }
 

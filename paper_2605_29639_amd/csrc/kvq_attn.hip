@@ -40,8 +40,11 @@ namespace {
 
 // Position in the flat list of groups: sequence b, pair pr inside the sequence
 // (pr = kv head * row groups + row group), group g of ng, sequence length L.  Wave-uniform.
+// part / end: with a shared prefix of P groups the list is all pairs' first P groups (part 0,
+// g runs over [0, P)) followed by all pairs' remaining groups (part 1, g over [P, ng)); without
+// one there is a single part with g over [0, ng).  `end` is where g stops in the current part.
 struct Cursor {
-  int b, pr, g, ng, L;
+  int b, pr, g, ng, L, part, end;
 };
 
 // Cross-lane scans and reductions on the DPP network (no LDS round trips): Hillis-Steele
@@ -71,6 +74,9 @@ __device__ inline float lane_value(float v, int lane_index) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane_index));
 }
 __device__ inline int wave_sum(int v) { return lane_value(wave_incl_scan(v), 63); }
+__device__ inline int wave_min(int v) {
+  return lane_value(dpp_scan_bits(v, 0x7FFFFFFF, [](int a, int b) { return a < b ? a : b; }), 63);
+}
 __device__ inline float wave_sum_f(float v) {
   const int r = dpp_scan_bits(__float_as_int(v), 0, [](int a, int b) {
     return __float_as_int(__int_as_float(a) + __int_as_float(b));
@@ -175,39 +181,84 @@ attn_stream_kernel(const AttnArgs p) {
   const int32_t* __restrict__ seq_lens = p.seq_lens;
 
   // ---- this wave's range [f0, f1) of the flat list, and where it starts ----
+  // With the shared-prefix variant and a prefix of P groups that every sequence has, the list
+  // is cut in two parts: first every pair's P prefix groups, then every pair's other groups.
+  // The wavefronts then all work on the prefix at the same time, at the start of the kernel,
+  // each on its own pairs' queries but on the same few blocks, which therefore leave HBM once
+  // per L2 instead of once per sequence.  (Each pair then has a partial result per part.)
   Cursor cur;
   int f0, f1;
+  int P = 0;
+  auto place = [&](int f, int incl_chunk_base, int Li, int incl, int k0, bool& found) {
+    // f lies in part 1 (or the only part): among the sequences k0 + lane of this piece find
+    // the one that holds it; incl = groups of this part up to and including the lane's sequence
+    const int i = k0 + lane;
+    const int cnt = __popcll(__ballot(i < B && (incl_chunk_base + incl) * Hp <= f));
+    found = cnt < 64 && k0 + cnt < B;
+    if (!found) return;
+    const int before = incl_chunk_base + (cnt ? lane_value(incl, cnt - 1) : 0);
+    cur.b = k0 + cnt;
+    cur.L = lane_value(Li, cnt);
+    cur.ng = (cur.L + 63) >> 6;
+    cur.end = cur.ng;
+    const int len = cur.ng - P;  // the pair's groups in this part
+    const int local = f - before * Hp;
+    cur.pr = local / len;
+    cur.g = P + (local - cur.pr * len);
+  };
+  auto place_prefix = [&](int f) {  // f lies in part 0: uniform arithmetic
+    const int pair = f / P;
+    cur.g = f - pair * P;
+    cur.b = pair / Hp;
+    cur.pr = pair - cur.b * Hp;
+    cur.L = seq_lens[cur.b];
+    cur.ng = (cur.L + 63) >> 6;
+    cur.part = 0;
+    cur.end = P;
+  };
+  cur.part = 0;
   if (B <= 64) {
     // lane i holds sequence i: one load and one scan give the list's length, the prefix sums
     // the reduce wants and, by a ballot, the sequence this wave's range starts in
     const int Li = lane < B ? seq_lens[lane] : 0;
-    const int incl = wave_incl_scan((Li + 63) >> 6);
+    const int ngi = (Li + 63) >> 6;
+    const int incl = wave_incl_scan(ngi);
     const int flat = lane_value(incl, 63) * Hp;
+    if constexpr (SHARED) {
+      if (p.shared_groups <= wave_min(lane < B ? ngi : 0x7FFFFFFF)) P = p.shared_groups;
+    }
     if (!CEIL && w == 0) {
       if (lane < B) p.ws_prefix[lane + 1] = incl;
-      if (lane == 0) p.ws_prefix[0] = 0;
+      if (lane == 0) {
+        p.ws_prefix[0] = 0;
+        p.ws_prefix[B + 1] = P;
+      }
     }
     stamp(8, true);  // the sequence lengths have arrived
     const Split split = make_split(p.range_groups, flat, p.num_waves);
     f0 = range_begin(split, w);
     f1 = range_begin(split, w + 1);
     if (f0 >= f1) return;
-    // sequences wholly before f0 (lanes past the batch hold the total: never counted)
-    const int cnt = __popcll(__ballot(incl * Hp <= f0));
-    const int before = cnt ? lane_value(incl, cnt - 1) : 0;
-    cur.b = cnt;
-    cur.L = lane_value(Li, cnt);
-    cur.ng = (cur.L + 63) >> 6;
-    const int local = f0 - before * Hp;
-    cur.pr = local / cur.ng;
-    cur.g = local - cur.pr * cur.ng;
+    const int flat_prefix = B * Hp * P;
+    if (f0 < flat_prefix) {
+      place_prefix(f0);
+    } else {
+      cur.part = P > 0;
+      bool found;
+      place(f0 - flat_prefix, 0, Li, incl - (lane + 1) * P, 0, found);
+    }
   } else {
-    int total = 0;
+    int total = 0, min_ng = 0x7FFFFFFF;
     for (int k0 = 0; k0 < B; k0 += 64) {
       const int i = k0 + lane;
-      total += (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
+      const int ngi = (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
+      total += ngi;
+      if (i < B) min_ng = min(min_ng, ngi);
     }
     const int flat = wave_sum(total) * Hp;
+    if constexpr (SHARED) {
+      if (p.shared_groups <= wave_min(min_ng)) P = p.shared_groups;
+    }
     if (!CEIL && w == 0) {  // for the reduce: 64-token groups of the sequences before each one
       int base = 0;
       for (int k0 = 0; k0 < B; k0 += 64) {
@@ -216,47 +267,67 @@ attn_stream_kernel(const AttnArgs p) {
         if (i < B) p.ws_prefix[i + 1] = base + incl;
         base += lane_value(incl, 63);
       }
-      if (lane == 0) p.ws_prefix[0] = 0;
+      if (lane == 0) {
+        p.ws_prefix[0] = 0;
+        p.ws_prefix[B + 1] = P;
+      }
     }
     stamp(8, true);
     const Split split = make_split(p.range_groups, flat, p.num_waves);
     f0 = range_begin(split, w);
     f1 = range_begin(split, w + 1);
     if (f0 >= f1) return;
-    int base = 0, b0 = 0, before = 0, L0 = 0;
-    for (int k0 = 0; k0 < B; k0 += 64) {
-      const int i = k0 + lane;
-      const int Li = (i < B) ? seq_lens[i] : 0;
-      const int incl = wave_incl_scan((Li + 63) >> 6);
-      // sequences of this piece wholly before f0 (f0 lies inside the list, so the piece that
-      // holds its sequence is reached)
-      const int cnt = __popcll(__ballot(i < B && (base + incl) * Hp <= f0));
-      if (cnt < 64 && k0 + cnt < B) {
-        b0 = k0 + cnt;
-        before = base + (cnt ? lane_value(incl, cnt - 1) : 0);
-        L0 = lane_value(Li, cnt);
-        break;
+    const int flat_prefix = B * Hp * P;
+    if (f0 < flat_prefix) {
+      place_prefix(f0);
+    } else {
+      cur.part = P > 0;
+      int base = 0;
+      for (int k0 = 0; k0 < B; k0 += 64) {
+        const int i = k0 + lane;
+        const int Li = (i < B) ? seq_lens[i] : 0;
+        // this part's groups, sequence by sequence (f0 lies inside the list, so the piece that
+        // holds its sequence is reached)
+        const int incl = wave_incl_scan(i < B ? ((Li + 63) >> 6) - P : 0);
+        bool found;
+        place(f0 - flat_prefix, base, Li, incl, k0, found);
+        if (found) break;
+        base += lane_value(incl, 63);
       }
-      base += lane_value(incl, 63);
     }
-    cur.b = b0;
-    cur.L = L0;
-    cur.ng = (cur.L + 63) >> 6;
-    const int local = f0 - before * Hp;
-    cur.pr = local / cur.ng;
-    cur.g = local - cur.pr * cur.ng;
   }
   stamp(9);  // the range and its first group are known
+  // the next group of the list; true if it belongs to another pair or part than the last one
   auto advance = [&](Cursor& c) {
-    if (++c.g < c.ng) return;
-    c.g = 0;
-    if (++c.pr < Hp) return;
+    if (++c.g < c.end) return;
+    if (++c.pr < Hp) {
+      c.g = c.part ? P : 0;
+      return;
+    }
     c.pr = 0;
-    do {
+    for (;;) {
       ++c.b;
-      c.L = (c.b < B) ? seq_lens[c.b] : 64;
+      if (c.b >= B) {
+        if (c.part == 0 && P > 0) {  // the prefix part is done: on to the pairs' other groups
+          c.part = 1;
+          c.b = 0;
+        } else {  // past the end of the list (never computed on): a harmless stand-in
+          c.L = 64;
+          c.ng = 1;
+          c.g = 0;
+          c.end = 1;
+          return;
+        }
+      }
+      c.L = seq_lens[c.b];
       c.ng = (c.L + 63) >> 6;
-    } while (c.b < B && c.ng == 0);
+      c.end = c.part == 0 && P > 0 ? P : c.ng;
+      c.g = c.part ? P : 0;
+      if (c.g < c.end) return;  // (a sequence that is all prefix has nothing in the second part)
+    }
+  };
+  auto same_pair = [](const Cursor& a, const Cursor& b) {
+    return a.b == b.b && a.pr == b.pr && a.part == b.part;
   };
 
   if (CLOCK && lane == 0)  // slot 1: where the wavefront runs (XCC_ID << 32 | HW_ID)
@@ -389,11 +460,13 @@ attn_stream_kernel(const AttnArgs p) {
     }
   };
 
-  // leave a pair: final rows if this wave saw all of it, else a partial
+  // leave a pair: final rows if this wave saw all of it, else a partial (numbered so that no
+  // two (wavefront, part, pair) share one: wavefront + position of (part, pair) in list order)
   auto end_pair = [&](const Cursor& c, bool whole) {
     if constexpr (CEIL) return;
     const int h = c.pr / NRG, rg = c.pr - h * NRG;
-    const size_t slot = (size_t)w + (size_t)c.b * Hp + c.pr;
+    const size_t slot = (size_t)w + (size_t)(c.part * B + c.b) * Hp + c.pr;
+    if (P > 0) whole = false;  // the pair's other part is another partial
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const float l = xor16_sum(l_run[nt]);
@@ -637,7 +710,8 @@ attn_stream_kernel(const AttnArgs p) {
   Cursor nxt = cur;
   if (count > 1) advance(nxt);
   Cursor nn = nxt;
-  bool from_start = cur.g == 0;  // did this wave see the current pair from its first group
+  // did this wave see the current pair (its share of the current part) from the first group
+  bool from_start = cur.g == (cur.part ? P : 0);
   if constexpr (DEPTH == 1) {
     uintx4 kt[4][KJ], vt[VW];
     ScaleT sk, sv;
@@ -671,7 +745,7 @@ attn_stream_kernel(const AttnArgs p) {
       softmax(S, sk_cur, sv_cur, cur, pb);
       pv(vt, pb, cur);
       load_v(vt, vbase, nxt);
-      if (nxt.g == 0) {  // the next group opens another pair
+      if (!same_pair(cur, nxt)) {  // the next group opens another pair
         end_pair(cur, from_start);
         begin_pair(nxt);
         from_start = true;
@@ -705,7 +779,7 @@ attn_stream_kernel(const AttnArgs p) {
     load_k(kta, ska, sva, vbase, cur, tk0, tv0);
     load_v(vta, vbase, cur);
     auto leave = [&](const Cursor& next) {  // after a group: does the next one open another pair
-      if (next.g == 0) {
+      if (!same_pair(cur, next)) {
         end_pair(cur, from_start);
         begin_pair(next);
         from_start = true;
@@ -752,7 +826,7 @@ attn_stream_kernel(const AttnArgs p) {
       pv(vta, pb, cur);
     }
   }
-  end_pair(cur, from_start && cur.g == cur.ng - 1);
+  end_pair(cur, from_start && cur.g == cur.end - 1);
   stamp(5);
   stamp(7);
   // (one dword per lane into the accumulator area, which holds at least 16 * D floats per
@@ -779,9 +853,12 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   const int hq = blockIdx.x % p.num_q_heads;
   const int b = blockIdx.x / p.num_q_heads;
   const int lane = threadIdx.x;
-  // where the sequence lies in the flat list: the prefix sums the streaming kernel left
+  // where the sequence lies in the flat list: the prefix sums the streaming kernel left, and
+  // the length P (in groups) of the shared prefix it split off (0: one part)
   const int before = p.ws_prefix[b], next = p.ws_prefix[b + 1], total = p.ws_prefix[p.batch];
+  const int P = p.ws_prefix[p.batch + 1];
   const int Hp = p.pairs_per_seq;
+  const int all_pairs = p.batch * Hp;
   const Split split = make_split(p.range_groups, total * Hp, p.num_waves);
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
@@ -792,47 +869,62 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
     const int r = j * p.group + (hq - h * p.group);
     const int rg = r / rt, rl = r - rg * rt;
     const int pr = h * p.num_row_groups + rg;
-    const int start = before * Hp + pr * ng;
-    const int w_first = range_of(split, start);
-    const int w_last = range_of(split, start + ng - 1);
-    if (w_first == w_last) continue;  // the streaming kernel already wrote the final rows
-    const size_t pair = (size_t)b * Hp + pr;
-    const int n = w_last - w_first + 1;
-    auto row_of = [&](int w) { return ((size_t)w + pair) * rt + rl; };
-    // (max, sum) of range w, or (-inf, 0) for a range that is empty and left no partial
-    auto max_sum = [&](int w) {
-      const bool live = w <= w_last && range_begin(split, w) < range_begin(split, w + 1);
-      return live ? ws_ml[row_of(w)] : float2v{-INFINITY, 0.0f};
+    const int pair = b * Hp + pr;
+    // the wavefront ranges that cover the pair's groups: those of its prefix part, then those
+    // of the rest (with one part: only the latter)
+    int wa = 0, na = 0, wb = 0, nb = 0;
+    if (P > 0) {
+      wa = range_of(split, pair * P);
+      na = range_of(split, pair * P + P - 1) - wa + 1;
+    }
+    if (ng > P) {
+      const int start = all_pairs * P + (before - b * P) * Hp + pr * (ng - P);
+      wb = range_of(split, start);
+      nb = range_of(split, start + (ng - P) - 1) - wb + 1;
+    }
+    if (P == 0 && nb == 1) continue;  // the streaming kernel already wrote the final rows
+    const int n = na + nb;
+    // the e-th partial of the pair: its wavefront and its row in the workspace
+    auto wave_of = [&](int e) { return e < na ? wa + e : wb + (e - na); };
+    auto row_of = [&](int e) {
+      return ((size_t)wave_of(e) + (e < na ? 0 : (P > 0 ? all_pairs : 0)) + pair) * rt + rl;
     };
-    auto load_rows = [&](floatE (&a)[NB], int w0, int count) {
+    // its (max, sum), or (-inf, 0) past the last one and for a range that is empty and left
+    // no partial
+    auto max_sum = [&](int e) {
+      const int w = wave_of(e);
+      const bool live = e < n && range_begin(split, w) < range_begin(split, w + 1);
+      return live ? ws_ml[row_of(e)] : float2v{-INFINITY, 0.0f};
+    };
+    auto load_rows = [&](floatE (&a)[NB], int e0, int count) {
 #pragma unroll
       for (int k = 0; k < NB; ++k)
-        if (k < count) a[k] = *(const floatE*)(ws_acc + row_of(w0 + k) * D);
+        if (k < count) a[k] = *(const floatE*)(ws_acc + row_of(e0 + k) * D);
     };
     floatE a_first[NB];
-    load_rows(a_first, w_first, n);
+    load_rows(a_first, 0, n);
 
     // pass 1: the maximum over all partials
-    const float2v ml_first = max_sum(w_first + lane);
+    const float2v ml_first = max_sum(lane);
     float M = ml_first[0];
-    for (int w0 = w_first + 64; w0 <= w_last; w0 += 64) M = fmaxf(M, max_sum(w0 + lane)[0]);
+    for (int e0 = 64; e0 < n; e0 += 64) M = fmaxf(M, max_sum(e0 + lane)[0]);
     M = wave_max_f(M);
 
     // pass 2: weights, denominator and the weighted sum of the accumulators
     floatE num = {};
     float den = 0.0f;
-    for (int w0 = w_first; w0 <= w_last; w0 += 64) {
-      const float2v ml = w0 == w_first ? ml_first : max_sum(w0 + lane);
+    for (int e0 = 0; e0 < n; e0 += 64) {
+      const float2v ml = e0 == 0 ? ml_first : max_sum(e0 + lane);
       const float wgt = __builtin_amdgcn_exp2f(ml[0] - M);  // 0 for an empty range
       den += wgt * ml[1];
-      const int count = min(64, w_last - w0 + 1);
+      const int count = min(64, n - e0);
       for (int k0 = 0; k0 < count; k0 += NB) {
         floatE a[NB];
-        if (w0 == w_first && k0 == 0) {
+        if (e0 == 0 && k0 == 0) {
 #pragma unroll
           for (int k = 0; k < NB; ++k) a[k] = a_first[k];
         } else {
-          load_rows(a, w0 + k0, count - k0);
+          load_rows(a, e0 + k0, count - k0);
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) {

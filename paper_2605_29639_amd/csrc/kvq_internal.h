@@ -85,7 +85,7 @@ struct AttnPlan {
   int32_t num_waves;       // wavefronts launched (= grid size)
   size_t acc_floats;       // workspace: accumulators
   size_t ml_floats;        // workspace: (max, sum) pairs
-  size_t prefix_ints;      // workspace: groups before each sequence (batch + 1, padded to 4)
+  size_t prefix_ints;      // workspace: groups before each sequence and the prefix length (batch + 2, padded to 4)
 };
 
 struct AttnArgs {
@@ -97,8 +97,9 @@ struct AttnArgs {
   float* out;
   float* ws_acc;
   float* ws_ml;
-  int32_t* ws_prefix;  // [batch + 1] 64-token groups of the sequences before b (written by the
-                       // streaming kernel's first wavefront, read by the reduce)
+  int32_t* ws_prefix;  // [batch + 1] 64-token groups of the sequences before b, then the shared
+                       // prefix length in groups that the streaming kernel split off (written
+                       // by its first wavefront, read by the reduce)
   int32_t max_blocks_per_seq, batch, q_len, num_q_heads, num_kv_heads, group, rows;
   int32_t block_size, bs_shift, head_dim, mode;
   int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;

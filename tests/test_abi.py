@@ -122,11 +122,12 @@ def test_attn_argument_checks():
         assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
     for name in ("q", "cache", "out"):                     # read and written in 16-byte pieces
         assert attn(L, ok, **{name: C.c_void_p(0x1008)}) == kvq.E_BAD_SHAPE
-    # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each, and the
-    # prefix sums of the sequences' group counts (batch + 1 ints, padded to a multiple of 4)
+    # workspace: one partial slot per (wavefront range, part, pair) crossing (a shared prefix
+    # makes two parts), 16 rows each, and the prefix sums of the sequences' group counts with the
+    # prefix length behind them (batch + 2 ints, padded to a multiple of 4)
     need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
     flat_max = 2 * 2 * 2                                   # batch * ceil(100/64) * kv heads
-    assert need == (flat_max + 2 * 2) * 16 * (64 + 2) * 4 + 4 * 4
+    assert need == (flat_max + 2 * 2 * 2) * 16 * (64 + 2) * 4 + 4 * 4
     assert attn(L, ok, chunk=64, ws=None) == kvq.E_NULLPTR
     assert attn(L, ok, chunk=64, ws_bytes=need - 1) == kvq.E_WORKSPACE
     assert attn(L, ok, chunk=64, ws=C.c_void_p(0x1004), ws_bytes=need) == kvq.E_BAD_SHAPE
@@ -134,15 +135,15 @@ def test_attn_argument_checks():
     assert auto == need                                    # fewer groups than resident waves
     big = kvq.make_desc(0, 1000, 16, 8, 128)
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
-        (2048 + 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
+        (2048 + 2 * 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
     # the group-scaled int4 format: one row tile whatever the row count, one wavefront per SIMD
     g4 = kvq.make_desc(5, 1000, 16, 8, 128)
     assert L.paged_decode_attn_workspace_bytes(C.byref(g4), 128, 4, 64, 16384, 0) == \
-        (1024 + 128 * 8 * 2) * 16 * (128 + 2) * 4 + 132 * 4
+        (1024 + 2 * 128 * 8 * 2) * 16 * (128 + 2) * 4 + 132 * 4
     # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
-        (1024 + 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
+        (1024 + 2 * 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
 
 
 def test_static_scratch_rejects_what_does_not_fit():
@@ -247,7 +248,7 @@ def test_binding_rejects_shapes_the_device_would_overrun():
     out = torch.zeros((2, 4, 64), dtype=torch.float32)
     bt = torch.zeros((2, 7), dtype=torch.int32)
     sl = torch.ones(2, dtype=torch.int32)
-    ws = torch.zeros(1 << 16, dtype=torch.uint8)
+    ws = torch.zeros(1 << 17, dtype=torch.uint8)
     with pytest.raises(ValueError):
         kvq.paged_decode_attn(q[:1], cache, scales, desc, bt, sl, 1, 100, 0.1, out, ws)
     with pytest.raises(ValueError):
