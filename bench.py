@@ -125,7 +125,8 @@ class Layers:
         self.sl = torch.from_numpy(wl.seq_lens).cuda()
         self.out = torch.empty((B * wl.q_len, wl.num_q_heads, wl.head_dim), dtype=torch.float32,
                                device="cuda")
-        self.ws = kvq.alloc_workspace(self.desc, B, wl.q_len, wl.num_q_heads, wl.max_seq_len, chunk)
+        self.ws = kvq.alloc_workspace(self.desc, B, wl.q_len, wl.num_q_heads, wl.max_seq_len, chunk,
+                                      shared_prefix_tokens=wl.shared_prefix)
         # the newest token(s) of every sequence: what a decode step appends before attending
         self.newest = [wl.kv_rows(b, int(wl.seq_lens[b]) - wl.q_len, int(wl.seq_lens[b]))
                        for b in range(B)]

@@ -198,14 +198,30 @@ int paged_decode_attn(const void* q, const void* cache, const float* scales,
 
 /* paged_decode_attn for a batch whose sequences begin with the same blocks: a prompt prefix
  * served from the prefix cache, whose full blocks are shared by the requests that reuse it
- * (Section 1, "Intelligent KV Cache Management"; Section 5.2.3).  shared_prefix_tokens says
- * that the positions below it are read by other sequences of this batch as well (their
- * block-table entries name the same physical blocks).  It is a hint about traffic, never about
- * the result, which is paged_decode_attn's whatever its value: the kernels load those positions
- * through the L2 cache instead of streaming past it, so that a prefix leaves HBM once per L2
- * (there are eight) instead of once per sequence.  Honoured for KVQ_INT8_TOKEN_HEAD and
- * KVQ_FP8E4M3_BLOCK_HEAD with fewer than 128 query rows per kv head, in units of 64 tokens
- * (rounded down); ignored otherwise.  shared_prefix_tokens < 0 is KVQ_E_BAD_SHAPE. */
+ * (Section 1, "Intelligent KV Cache Management"; Section 5.2.3).
+ *
+ * shared_prefix_tokens is a promise: every block that holds a position below it is the same
+ * physical block in every sequence's table (block_tables[b][i] == block_tables[0][i] for
+ * those i).  The positions below floor(shared_prefix_tokens / 64) * 64 are then read once for
+ * many sequences instead of once per sequence: a first kernel stacks the query rows of all
+ * sequences, 128 to a workgroup, over the shared blocks (the many-row kernel of
+ * paged_decode_attn, each K/V tile dequantized once per 128 rows) and leaves partials; the
+ * streaming kernel covers the rest of each sequence; the reduce merges both.  The result is
+ * paged_decode_attn's up to the order of the fp32 merges.  If the promise does not hold the
+ * result is wrong, not undefined (every address still comes from a valid table entry); with
+ * KVQ_DEBUG=1 it is checked and KVQ_E_BAD_INDEX returned.
+ *
+ * The prefix is used when every sequence has at least that many tokens (decided on the device
+ * from seq_lens), for every format but KVQ_INT4_GROUP32, with batch >= 2 and fewer than 128
+ * query rows per kv head; otherwise, and with shared_prefix_tokens < 64, the call is
+ * paged_decode_attn.  shared_prefix_tokens < 0 is KVQ_E_BAD_SHAPE.
+ *
+ * workspace_bytes must be at least paged_decode_attn_prefix_workspace_bytes() for the same
+ * arguments (more than paged_decode_attn needs: room for the first kernel's partials). */
+size_t paged_decode_attn_prefix_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
+                                                int32_t q_len, int32_t num_q_heads,
+                                                int32_t max_seq_len, int32_t chunk_tokens,
+                                                int32_t shared_prefix_tokens);
 int paged_decode_attn_prefix(const void* q, const void* cache, const float* scales,
                              const kvq_cache_desc_t* desc, const int32_t* block_tables,
                              int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t batch,

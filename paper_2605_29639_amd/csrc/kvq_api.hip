@@ -74,11 +74,12 @@ int ilog2(int x) {
 
 // Everything the launch needs that depends only on host-side arguments.
 bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t num_q_heads,
-               int32_t max_seq_len, int32_t chunk_tokens, kvq::AttnPlan* plan, int* err) {
+               int32_t max_seq_len, int32_t chunk_tokens, int32_t shared_prefix_tokens,
+               kvq::AttnPlan* plan, int* err) {
   if (!desc_ok(d, err)) return false;
   if (batch < 0 || q_len < 1 || q_len > KVQ_MAX_Q_LEN || num_q_heads <= 0 ||
       num_q_heads % d->num_kv_heads != 0 || max_seq_len < 0 || chunk_tokens < 0 ||
-      chunk_tokens % 64 != 0) {
+      chunk_tokens % 64 != 0 || shared_prefix_tokens < 0) {
     *err = KVQ_E_BAD_SHAPE;
     return false;
   }
@@ -119,9 +120,27 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
     plan->num_waves = (int32_t)((flat_max + plan->range_groups - 1) / plan->range_groups);
   }
   if (plan->num_waves < 1) plan->num_waves = 1;
-  // one partial per (wavefront range, pair) crossing, numbered wave + pair index; twice the
-  // pairs, since a shared prefix splits every pair's groups into two parts of the list
-  const size_t slots = (size_t)plan->num_waves + 2 * (size_t)batch * plan->pairs_per_seq;
+  // A shared prefix goes to the many-row kernel with all sequences' rows stacked, where that
+  // kernel exists for the format, the call is not already its own (128 rows and more per kv
+  // head), there is a second sequence to share with and the prefix fits the declared lengths.
+  // It is cut into pieces so that about two workgroups per compute unit come about.
+  plan->shared_groups = 0;
+  plan->prefix_chunks = 1;
+  const int64_t stacked = (int64_t)batch * rows;
+  if (shared_prefix_tokens >= 64 && shared_prefix_tokens <= max_seq_len && batch >= 2 &&
+      rows < 128 && d->mode != KVQ_INT4_GROUP32 && stacked <= (1 << 30)) {
+    plan->shared_groups = shared_prefix_tokens / 64;
+    const int64_t walks = d->num_kv_heads * ((stacked + 127) / 128);
+    int64_t chunks = (auto_waves() / 4 + walks - 1) / walks;
+    if (chunks > kvq::kMaxPrefixChunks) chunks = kvq::kMaxPrefixChunks;
+    if (chunks > plan->shared_groups) chunks = plan->shared_groups;
+    plan->prefix_chunks = (int32_t)chunks;
+  }
+  // one partial per (wavefront range, pair) crossing, numbered wave + pair index; behind them
+  // one per (piece of the shared prefix, pair)
+  const size_t slots =
+      (size_t)plan->num_waves +
+      (size_t)batch * plan->pairs_per_seq * (plan->shared_groups > 0 ? 1 + plan->prefix_chunks : 1);
   const size_t slot_rows = slots * 16 * plan->row_tiles;
   plan->acc_floats = slot_rows * d->head_dim;
   plan->ml_floats = slot_rows * 2;
@@ -176,7 +195,19 @@ size_t paged_decode_attn_workspace_bytes(const kvq_cache_desc_t* desc, int32_t b
                                          int32_t max_seq_len, int32_t chunk_tokens) {
   kvq::AttnPlan plan;
   int err;
-  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, 0, &plan, &err))
+    return 0;
+  return (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
+}
+
+size_t paged_decode_attn_prefix_workspace_bytes(const kvq_cache_desc_t* desc, int32_t batch,
+                                                int32_t q_len, int32_t num_q_heads,
+                                                int32_t max_seq_len, int32_t chunk_tokens,
+                                                int32_t shared_prefix_tokens) {
+  kvq::AttnPlan plan;
+  int err;
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, shared_prefix_tokens,
+                 &plan, &err))
     return 0;
   return (plan.acc_floats + plan.ml_floats + plan.prefix_ints) * sizeof(float);
 }
@@ -227,11 +258,13 @@ __global__ void check_slots_kernel(const int64_t* __restrict__ slot_mapping, int
 }
 
 // entry (b, j): sequence lengths inside [q_len, max_seq_len]; the table entries of every block
-// below ceil(seq_lens[b] / block_size) inside [0, num_blocks)
+// below ceil(seq_lens[b] / block_size) inside [0, num_blocks); the first shared_blocks entries
+// equal to sequence 0's (where both sequences are long enough for the prefix to be used)
 __global__ void check_tables_kernel(const int32_t* __restrict__ block_tables,
                                     const int32_t* __restrict__ seq_lens, int32_t batch,
                                     int32_t max_blocks_per_seq, int32_t num_blocks,
                                     int32_t block_size, int32_t q_len, int32_t max_seq_len,
+                                    int32_t shared_blocks, int32_t shared_tokens,
                                     int* __restrict__ word) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)batch * max_blocks_per_seq) return;
@@ -248,6 +281,11 @@ __global__ void check_tables_kernel(const int32_t* __restrict__ block_tables,
   const int e = block_tables[i];
   if (e < 0 || e >= num_blocks) {
     atomicOr(&word[0], 4);
+    atomicMin(&word[1], b);
+  }
+  if (j < shared_blocks && L >= shared_tokens && seq_lens[0] >= shared_tokens &&
+      e != block_tables[j]) {
+    atomicOr(&word[0], 8);
     atomicMin(&word[1], b);
   }
 }
@@ -294,12 +332,12 @@ int attn_call(const void* q, const void* cache, const float* scales,
               bool own_scratch, void* stream) {
   kvq::AttnPlan plan;
   int err;
-  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, &plan, &err))
+  if (!make_plan(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens, shared_prefix_tokens,
+                 &plan, &err))
     return err;
   if (max_blocks_per_seq < 0 ||
       (int64_t)max_blocks_per_seq * desc->block_size < (int64_t)max_seq_len)
     return KVQ_E_BAD_SHAPE;
-  if (shared_prefix_tokens < 0) return KVQ_E_BAD_SHAPE;
   if (batch == 0) return KVQ_OK;
   if (max_seq_len < q_len) return KVQ_E_BAD_SHAPE;
   if (!q || !cache || !block_tables || !seq_lens || !out) return KVQ_E_NULLPTR;
@@ -324,7 +362,9 @@ int attn_call(const void* q, const void* cache, const float* scales,
         hipLaunchKernelGGL(check_tables_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256),
                            0, (hipStream_t)stream, block_tables, seq_lens, batch,
                            max_blocks_per_seq, desc->num_blocks, desc->block_size, q_len,
-                           max_seq_len, word);
+                           max_seq_len,
+                           (plan.shared_groups * 64 + desc->block_size - 1) / desc->block_size,
+                           plan.shared_groups * 64, word);
       });
       if (rc != KVQ_OK) return rc;
     }
@@ -358,7 +398,8 @@ int attn_call(const void* q, const void* cache, const float* scales,
   a.num_waves = plan.num_waves;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   a.wave_clock = nullptr;
-  a.shared_groups = shared_prefix_tokens / 64;
+  a.shared_groups = plan.shared_groups;
+  a.prefix_chunks = plan.prefix_chunks;
   const hipError_t e = kvq::launch_attn(a, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }

@@ -40,11 +40,8 @@ namespace {
 
 // Position in the flat list of groups: sequence b, pair pr inside the sequence
 // (pr = kv head * row groups + row group), group g of ng, sequence length L.  Wave-uniform.
-// part / end: with a shared prefix of P groups the list is all pairs' first P groups (part 0,
-// g runs over [0, P)) followed by all pairs' remaining groups (part 1, g over [P, ng)); without
-// one there is a single part with g over [0, ng).  `end` is where g stops in the current part.
 struct Cursor {
-  int b, pr, g, ng, L, part, end;
+  int b, pr, g, ng, L;
 };
 
 // Cross-lane scans and reductions on the DPP network (no LDS round trips): Hillis-Steele
@@ -133,10 +130,7 @@ __device__ inline int range_of(const Split& s, int f) {
 // (The second launch bound, two wavefronts per SIMD, for the quantized one-tile kernels: they
 // fit either way, but told so the compiler keeps everything in 200-224 VGPRs instead of parking
 // values in AGPRs and copying them back, 1-2 % faster.)
-//   SHARED = true (instantiated for the int8 and block-scaled fp8 caches): the groups below
-//   p.shared_groups are loaded through the caches rather than past them, because the caller
-//   said that other sequences of the batch read the same blocks (a common prefix).
-template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK, bool SHARED = false>
+template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK>
 __global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN && MODE != KVQ_INT4_GROUP32) ? 2 : 1) void
 attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
@@ -181,52 +175,37 @@ attn_stream_kernel(const AttnArgs p) {
   const int32_t* __restrict__ seq_lens = p.seq_lens;
 
   // ---- this wave's range [f0, f1) of the flat list, and where it starts ----
-  // With the shared-prefix variant and a prefix of P groups that every sequence has, the list
-  // is cut in two parts: first every pair's P prefix groups, then every pair's other groups.
-  // The wavefronts then all work on the prefix at the same time, at the start of the kernel,
-  // each on its own pairs' queries but on the same few blocks, which therefore leave HBM once
-  // per L2 instead of once per sequence.  (Each pair then has a partial result per part.)
+  // With a shared prefix the first P groups of every pair are the prefix kernel's (which reads
+  // them once for many sequences), and the list holds groups P .. ng - 1 of every pair.  P is
+  // the caller's figure if every sequence has that many full groups, else 0; the prefix kernel
+  // takes the same decision from the same lengths.
   Cursor cur;
   int f0, f1;
   int P = 0;
-  auto place = [&](int f, int incl_chunk_base, int Li, int incl, int k0, bool& found) {
-    // f lies in part 1 (or the only part): among the sequences k0 + lane of this piece find
-    // the one that holds it; incl = groups of this part up to and including the lane's sequence
+  auto place = [&](int f, int base, int Li, int incl, int k0) {
+    // among the sequences k0 + lane of this piece find the one that holds list position f;
+    // base + incl = listed groups up to and including the lane's sequence
     const int i = k0 + lane;
-    const int cnt = __popcll(__ballot(i < B && (incl_chunk_base + incl) * Hp <= f));
-    found = cnt < 64 && k0 + cnt < B;
-    if (!found) return;
-    const int before = incl_chunk_base + (cnt ? lane_value(incl, cnt - 1) : 0);
+    const int cnt = __popcll(__ballot(i < B && (base + incl) * Hp <= f));
+    if (cnt == 64 || k0 + cnt >= B) return false;
+    const int before = base + (cnt ? lane_value(incl, cnt - 1) : 0);
     cur.b = k0 + cnt;
     cur.L = lane_value(Li, cnt);
     cur.ng = (cur.L + 63) >> 6;
-    cur.end = cur.ng;
-    const int len = cur.ng - P;  // the pair's groups in this part
+    const int len = cur.ng - P;  // the pair's groups in the list
     const int local = f - before * Hp;
     cur.pr = local / len;
     cur.g = P + (local - cur.pr * len);
+    return true;
   };
-  auto place_prefix = [&](int f) {  // f lies in part 0: uniform arithmetic
-    const int pair = f / P;
-    cur.g = f - pair * P;
-    cur.b = pair / Hp;
-    cur.pr = pair - cur.b * Hp;
-    cur.L = seq_lens[cur.b];
-    cur.ng = (cur.L + 63) >> 6;
-    cur.part = 0;
-    cur.end = P;
-  };
-  cur.part = 0;
   if (B <= 64) {
     // lane i holds sequence i: one load and one scan give the list's length, the prefix sums
     // the reduce wants and, by a ballot, the sequence this wave's range starts in
     const int Li = lane < B ? seq_lens[lane] : 0;
     const int ngi = (Li + 63) >> 6;
     const int incl = wave_incl_scan(ngi);
-    const int flat = lane_value(incl, 63) * Hp;
-    if constexpr (SHARED) {
-      if (p.shared_groups <= wave_min(lane < B ? ngi : 0x7FFFFFFF)) P = p.shared_groups;
-    }
+    if (p.shared_groups <= wave_min(lane < B ? Li >> 6 : 0x7FFFFFFF)) P = p.shared_groups;
+    const int flat = (lane_value(incl, 63) - B * P) * Hp;
     if (!CEIL && w == 0) {
       if (lane < B) p.ws_prefix[lane + 1] = incl;
       if (lane == 0) {
@@ -239,26 +218,17 @@ attn_stream_kernel(const AttnArgs p) {
     f0 = range_begin(split, w);
     f1 = range_begin(split, w + 1);
     if (f0 >= f1) return;
-    const int flat_prefix = B * Hp * P;
-    if (f0 < flat_prefix) {
-      place_prefix(f0);
-    } else {
-      cur.part = P > 0;
-      bool found;
-      place(f0 - flat_prefix, 0, Li, incl - (lane + 1) * P, 0, found);
-    }
+    place(f0, 0, Li, incl - (lane + 1) * P, 0);
   } else {
-    int total = 0, min_ng = 0x7FFFFFFF;
+    int total = 0, min_full = 0x7FFFFFFF;
     for (int k0 = 0; k0 < B; k0 += 64) {
       const int i = k0 + lane;
-      const int ngi = (i < B) ? (seq_lens[i] + 63) >> 6 : 0;
-      total += ngi;
-      if (i < B) min_ng = min(min_ng, ngi);
+      const int Li = (i < B) ? seq_lens[i] : 0;
+      total += (Li + 63) >> 6;
+      if (i < B) min_full = min(min_full, Li >> 6);
     }
-    const int flat = wave_sum(total) * Hp;
-    if constexpr (SHARED) {
-      if (p.shared_groups <= wave_min(min_ng)) P = p.shared_groups;
-    }
+    if (p.shared_groups <= wave_min(min_full)) P = p.shared_groups;
+    const int flat = (wave_sum(total) - B * P) * Hp;
     if (!CEIL && w == 0) {  // for the reduce: 64-token groups of the sequences before each one
       int base = 0;
       for (int k0 = 0; k0 < B; k0 += 64) {
@@ -277,57 +247,27 @@ attn_stream_kernel(const AttnArgs p) {
     f0 = range_begin(split, w);
     f1 = range_begin(split, w + 1);
     if (f0 >= f1) return;
-    const int flat_prefix = B * Hp * P;
-    if (f0 < flat_prefix) {
-      place_prefix(f0);
-    } else {
-      cur.part = P > 0;
-      int base = 0;
-      for (int k0 = 0; k0 < B; k0 += 64) {
-        const int i = k0 + lane;
-        const int Li = (i < B) ? seq_lens[i] : 0;
-        // this part's groups, sequence by sequence (f0 lies inside the list, so the piece that
-        // holds its sequence is reached)
-        const int incl = wave_incl_scan(i < B ? ((Li + 63) >> 6) - P : 0);
-        bool found;
-        place(f0 - flat_prefix, base, Li, incl, k0, found);
-        if (found) break;
-        base += lane_value(incl, 63);
-      }
+    int base = 0;
+    for (int k0 = 0; k0 < B; k0 += 64) {
+      const int i = k0 + lane;
+      const int Li = (i < B) ? seq_lens[i] : 0;
+      // (f0 lies inside the list, so the piece that holds its sequence is reached)
+      const int incl = wave_incl_scan(i < B ? ((Li + 63) >> 6) - P : 0);
+      if (place(f0, base, Li, incl, k0)) break;
+      base += lane_value(incl, 63);
     }
   }
   stamp(9);  // the range and its first group are known
-  // the next group of the list; true if it belongs to another pair or part than the last one
-  auto advance = [&](Cursor& c) {
-    if (++c.g < c.end) return;
-    if (++c.pr < Hp) {
-      c.g = c.part ? P : 0;
-      return;
-    }
+  auto advance = [&](Cursor& c) {  // the next group of the list
+    if (++c.g < c.ng) return;
+    c.g = P;
+    if (++c.pr < Hp) return;
     c.pr = 0;
-    for (;;) {
+    do {  // (a sequence that is nothing but prefix has no groups in the list)
       ++c.b;
-      if (c.b >= B) {
-        if (c.part == 0 && P > 0) {  // the prefix part is done: on to the pairs' other groups
-          c.part = 1;
-          c.b = 0;
-        } else {  // past the end of the list (never computed on): a harmless stand-in
-          c.L = 64;
-          c.ng = 1;
-          c.g = 0;
-          c.end = 1;
-          return;
-        }
-      }
-      c.L = seq_lens[c.b];
+      c.L = (c.b < B) ? seq_lens[c.b] : 64 * (P + 1);
       c.ng = (c.L + 63) >> 6;
-      c.end = c.part == 0 && P > 0 ? P : c.ng;
-      c.g = c.part ? P : 0;
-      if (c.g < c.end) return;  // (a sequence that is all prefix has nothing in the second part)
-    }
-  };
-  auto same_pair = [](const Cursor& a, const Cursor& b) {
-    return a.b == b.b && a.pr == b.pr && a.part == b.part;
+    } while (c.b < B && c.ng <= P);
   };
 
   if (CLOCK && lane == 0)  // slot 1: where the wavefront runs (XCC_ID << 32 | HW_ID)
@@ -372,25 +312,14 @@ attn_stream_kernel(const AttnArgs p) {
                                                            : h;
     const ScaleT* sp = (const ScaleT*)(scales + (size_t)blk_v * s_block_stride + s_lane);
     constexpr uint32_t kSkip = GROUPED ? 4 : 1;  // floats per ScaleT
-    if (SHARED && c.g < p.shared_groups) {  // blocks other sequences read too: keep them cached
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int j = 0; j < KJ; ++j) kt[u][j] = *(const uintx4*)(kbase + u * (4 * RB) + 256 * j);
-      if constexpr (!PLAIN) {
-        sk = *sp;
-        sv = sp[s_kv / kSkip];
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int j = 0; j < KJ; ++j)
-          kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
-      if constexpr (!PLAIN) {
-        sk = __builtin_nontemporal_load(sp);
-        sv = __builtin_nontemporal_load(sp + s_kv / kSkip);
-      }
+      for (int j = 0; j < KJ; ++j)
+        kt[u][j] = __builtin_nontemporal_load((const uintx4*)(kbase + u * (4 * RB) + 256 * j));
+    if constexpr (!PLAIN) {
+      sk = __builtin_nontemporal_load(sp);
+      sv = __builtin_nontemporal_load(sp + s_kv / kSkip);
     }
     if constexpr (PLAIN) {
       sk = 1.0f;
@@ -399,18 +328,10 @@ attn_stream_kernel(const AttnArgs p) {
   };
   // (unquantized: piece 2 tt + half is channel tile tt, tokens 8 half .. 8 half + 7)
   auto load_v = [&](uintx4 (&vt)[VW], const uint8_t* vbase, const Cursor& c) {
-    if (SHARED && c.g < p.shared_groups) {
 #pragma unroll
-      for (int x = 0; x < VW; ++x) {
-        const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
-        vt[x] = *(const uintx4*)(vbase + at);
-      }
-    } else {
-#pragma unroll
-      for (int x = 0; x < VW; ++x) {
-        const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
-        vt[x] = __builtin_nontemporal_load((const uintx4*)(vbase + at));
-      }
+    for (int x = 0; x < VW; ++x) {
+      const int at = PLAIN ? (x & 1) * (16 * D) + 256 * (x >> 1) : 256 * x;
+      vt[x] = __builtin_nontemporal_load((const uintx4*)(vbase + at));
     }
   };
 
@@ -460,13 +381,12 @@ attn_stream_kernel(const AttnArgs p) {
     }
   };
 
-  // leave a pair: final rows if this wave saw all of it, else a partial (numbered so that no
-  // two (wavefront, part, pair) share one: wavefront + position of (part, pair) in list order)
+  // leave a pair: final rows if this wave saw all of it, else a partial
   auto end_pair = [&](const Cursor& c, bool whole) {
     if constexpr (CEIL) return;
     const int h = c.pr / NRG, rg = c.pr - h * NRG;
-    const size_t slot = (size_t)w + (size_t)(c.part * B + c.b) * Hp + c.pr;
-    if (P > 0) whole = false;  // the pair's other part is another partial
+    const size_t slot = (size_t)w + (size_t)c.b * Hp + c.pr;
+    if (P > 0) whole = false;  // the pair's prefix is another partial, the prefix kernel's
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const float l = xor16_sum(l_run[nt]);
@@ -710,8 +630,7 @@ attn_stream_kernel(const AttnArgs p) {
   Cursor nxt = cur;
   if (count > 1) advance(nxt);
   Cursor nn = nxt;
-  // did this wave see the current pair (its share of the current part) from the first group
-  bool from_start = cur.g == (cur.part ? P : 0);
+  bool from_start = cur.g == P;  // did this wave see the current pair from its first listed group
   if constexpr (DEPTH == 1) {
     uintx4 kt[4][KJ], vt[VW];
     ScaleT sk, sv;
@@ -745,7 +664,7 @@ attn_stream_kernel(const AttnArgs p) {
       softmax(S, sk_cur, sv_cur, cur, pb);
       pv(vt, pb, cur);
       load_v(vt, vbase, nxt);
-      if (!same_pair(cur, nxt)) {  // the next group opens another pair
+      if (nxt.g == P) {  // the next group opens another pair
         end_pair(cur, from_start);
         begin_pair(nxt);
         from_start = true;
@@ -779,7 +698,7 @@ attn_stream_kernel(const AttnArgs p) {
     load_k(kta, ska, sva, vbase, cur, tk0, tv0);
     load_v(vta, vbase, cur);
     auto leave = [&](const Cursor& next) {  // after a group: does the next one open another pair
-      if (!same_pair(cur, next)) {
+      if (next.g == P) {
         end_pair(cur, from_start);
         begin_pair(next);
         from_start = true;
@@ -826,7 +745,7 @@ attn_stream_kernel(const AttnArgs p) {
       pv(vta, pb, cur);
     }
   }
-  end_pair(cur, from_start && cur.g == cur.end - 1);
+  end_pair(cur, from_start && cur.g == cur.ng - 1);
   stamp(5);
   stamp(7);
   // (one dword per lane into the accumulator area, which holds at least 16 * D floats per
@@ -854,46 +773,50 @@ __global__ __launch_bounds__(64) void attn_reduce_kernel(const AttnArgs p) {
   const int b = blockIdx.x / p.num_q_heads;
   const int lane = threadIdx.x;
   // where the sequence lies in the flat list: the prefix sums the streaming kernel left, and
-  // the length P (in groups) of the shared prefix it split off (0: one part)
+  // the length P (in groups) of the shared prefix it left to the prefix kernel (0: none)
   const int before = p.ws_prefix[b], next = p.ws_prefix[b + 1], total = p.ws_prefix[p.batch];
   const int P = p.ws_prefix[p.batch + 1];
   const int Hp = p.pairs_per_seq;
   const int all_pairs = p.batch * Hp;
-  const Split split = make_split(p.range_groups, total * Hp, p.num_waves);
+  const Split split = make_split(p.range_groups, (total - p.batch * P) * Hp, p.num_waves);
   const int rt = 16 * p.row_tiles;
   const int h = hq / p.group;
   const int ng = next - before;
+  const int na = P > 0 ? p.prefix_chunks : 0;  // partials the prefix kernel left for this pair
   const float* __restrict__ ws_acc = p.ws_acc + lane * E;
   const float2v* __restrict__ ws_ml = (const float2v*)p.ws_ml;
+  // a range between two non-empty ones can be empty only if the list is shorter than the grid
+  const bool sparse = split.requested == 0 && split.q == 0;
+  int rg_known = -1, wb = 0, nb = 0;
+  // (the wavefront takes the query tokens j = y, y + Y, ... one after the other: their rows
+  // mostly lie in one row group, whose place in the list is then worked out once)
   for (int j = blockIdx.y; j < p.q_len; j += gridDim.y) {
     const int r = j * p.group + (hq - h * p.group);
     const int rg = r / rt, rl = r - rg * rt;
     const int pr = h * p.num_row_groups + rg;
     const int pair = b * Hp + pr;
-    // the wavefront ranges that cover the pair's groups: those of its prefix part, then those
-    // of the rest (with one part: only the latter)
-    int wa = 0, na = 0, wb = 0, nb = 0;
-    if (P > 0) {
-      wa = range_of(split, pair * P);
-      na = range_of(split, pair * P + P - 1) - wa + 1;
-    }
-    if (ng > P) {
-      const int start = all_pairs * P + (before - b * P) * Hp + pr * (ng - P);
+    // the wavefront ranges that cover the pair's listed groups
+    if (rg != rg_known && ng > P) {
+      const int start = (before - b * P) * Hp + pr * (ng - P);
       wb = range_of(split, start);
       nb = range_of(split, start + (ng - P) - 1) - wb + 1;
+      rg_known = rg;
     }
-    if (P == 0 && nb == 1) continue;  // the streaming kernel already wrote the final rows
+    if (na == 0 && nb == 1) continue;  // the streaming kernel already wrote the final rows
     const int n = na + nb;
-    // the e-th partial of the pair: its wavefront and its row in the workspace
-    auto wave_of = [&](int e) { return e < na ? wa + e : wb + (e - na); };
+    // the e-th partial of the pair: the prefix kernel's (one per chunk of the prefix, in slots
+    // behind the streaming kernel's), then one per covering wavefront range
     auto row_of = [&](int e) {
-      return ((size_t)wave_of(e) + (e < na ? 0 : (P > 0 ? all_pairs : 0)) + pair) * rt + rl;
+      const size_t slot = e < na ? (size_t)p.num_waves + (size_t)(e + 1) * all_pairs + pair
+                                 : (size_t)(wb + (e - na)) + pair;
+      return slot * rt + rl;
     };
     // its (max, sum), or (-inf, 0) past the last one and for a range that is empty and left
     // no partial
     auto max_sum = [&](int e) {
-      const int w = wave_of(e);
-      const bool live = e < n && range_begin(split, w) < range_begin(split, w + 1);
+      const int w = wb + (e - na);
+      const bool live =
+          e < n && (e < na || !sparse || range_begin(split, w) < range_begin(split, w + 1));
       return live ? ws_ml[row_of(e)] : float2v{-INFINITY, 0.0f};
     };
     auto load_rows = [&](floatE (&a)[NB], int e0, int count) {
@@ -958,18 +881,6 @@ unsigned long long* g_wave_clock = nullptr;
 template <int MODE, int D, bool CEIL, bool CLOCK>
 void launch_variant(const AttnArgs& a, hipStream_t stream) {
   constexpr int kDepth = MODE == KVQ_BF16_PLAIN ? 1 : 2;
-  // the variant that keeps a shared prefix cached exists for the two benchmark formats
-  constexpr bool kHasShared =
-      !CEIL && !CLOCK && (MODE == KVQ_INT8_TOKEN_HEAD || MODE == KVQ_FP8E4M3_BLOCK_HEAD);
-  if constexpr (kHasShared) {
-    if (a.shared_groups > 0) {
-      if (a.row_tiles == 1)
-        hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, false, 1, false, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
-      else
-        hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 2, false, kDepth, false, true>), dim3(a.num_waves), dim3(64), 0, stream, a);
-      return;
-    }
-  }
   if constexpr (MODE == KVQ_INT4_GROUP32) {  // (the plan gives this format one row tile always)
     hipLaunchKernelGGL((attn_stream_kernel<MODE, D, 1, CEIL, 1, CLOCK>), dim3(a.num_waves), dim3(64), 0, stream, a);
   } else {
@@ -985,7 +896,9 @@ hipError_t launch_stream(const AttnArgs& a0, hipStream_t stream) {
 #ifdef KVQ_PROFILE
   AttnArgs a = a0;
   a.wave_clock = g_wave_clock;
-  if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
+  // (with a shared prefix the first event lies before the prefix kernel)
+  if (g_ev_before && (a.shared_groups == 0 || g_read_ceiling || g_skip_reduce))
+    (void)hipEventRecord(g_ev_before, stream);
   if (g_read_ceiling)
     launch_variant<MODE, D, true, false>(a, stream);
   else if (g_wave_clock)
@@ -1023,6 +936,13 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
 #endif
   if (many_rows_kernel && prefill_applies(a)) return launch_prefill(a, stream);
   hipError_t e;
+  if (a.shared_groups > 0 && !stream_only) {  // the shared prefix, read once for many sequences
+#ifdef KVQ_PROFILE
+    if (g_ev_before) (void)hipEventRecord(g_ev_before, stream);
+#endif
+    e = launch_prefix(a, stream);
+    if (e != hipSuccess) return e;
+  }
   if (a.mode == KVQ_INT8_TOKEN_HEAD)
     e = a.head_dim == 128 ? launch_stream<KVQ_INT8_TOKEN_HEAD, 128>(a, stream)
                           : launch_stream<KVQ_INT8_TOKEN_HEAD, 64>(a, stream);
@@ -1040,7 +960,9 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream) {
     e = a.head_dim == 128 ? launch_stream<KVQ_BF16_PLAIN, 128>(a, stream)
                           : launch_stream<KVQ_BF16_PLAIN, 64>(a, stream);
   if (e != hipSuccess || stream_only) return e;
-  const dim3 rgrid((unsigned)((size_t)a.batch * a.num_q_heads), (unsigned)(a.q_len < 64 ? a.q_len : 64));
+  // (a wavefront per (sequence, query head) and four query tokens, 64 per query head at most)
+  const int per_head = (a.q_len + 3) / 4;
+  const dim3 rgrid((unsigned)((size_t)a.batch * a.num_q_heads), (unsigned)(per_head < 64 ? per_head : 64));
   if (a.head_dim == 128)
     hipLaunchKernelGGL((attn_reduce_kernel<128>), rgrid, dim3(64), 0, stream, a);
   else

@@ -76,6 +76,8 @@ __host__ __device__ inline uint8_t stored_byte(uint8_t code, int mode) {
   return mode == KVQ_INT8_TOKEN_HEAD ? (uint8_t)(code ^ 0x80) : code;
 }
 
+constexpr int kMaxPrefixChunks = 8;  // pieces a shared prefix is cut into at most
+
 struct AttnPlan {
   int32_t rows;            // (num_q_heads / num_kv_heads) * q_len query rows per kv head
   int32_t row_tiles;       // 16-row tiles handled by one wavefront (1 or 2)
@@ -86,6 +88,8 @@ struct AttnPlan {
   size_t acc_floats;       // workspace: accumulators
   size_t ml_floats;        // workspace: (max, sum) pairs
   size_t prefix_ints;      // workspace: groups before each sequence and the prefix length (batch + 2, padded to 4)
+  int32_t shared_groups;   // shared prefix in 64-token groups, 0 where the prefix kernel is not used
+  int32_t prefix_chunks;   // pieces the prefix kernel cuts it into (>= 1)
 };
 
 struct AttnArgs {
@@ -104,7 +108,9 @@ struct AttnArgs {
   int32_t block_size, bs_shift, head_dim, mode;
   int32_t row_tiles, num_row_groups, pairs_per_seq, range_groups, num_waves;
   float scale_log2;  // sm_scale * log2(e)
-  int32_t shared_groups;  // leading 64-token groups of every sequence that other sequences read too
+  int32_t shared_groups;  // leading 64-token groups that all sequences' tables map to the same
+                          // blocks (0: none, or a call the prefix kernel does not serve)
+  int32_t prefix_chunks;  // pieces the prefix kernel cuts those groups into: one partial each
   unsigned long long* wave_clock;  // measurement build: 8 clock readings per wavefront; else null
 };
 
@@ -115,6 +121,10 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t stream);
 // the kernel for 128 and more query rows per kv head (kvq_prefill.hip)
 bool prefill_applies(const AttnArgs& a);
 hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream);
+// the same kernel over a prefix all sequences share, rows of all sequences stacked; leaves
+// partials for the reduce (a.shared_groups > 0, a.prefix_chunks >= 1)
+bool prefix_applies(const AttnArgs& a);
+hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream);
 #ifdef KVQ_PROFILE  // the measurement build's switches (include/kvq_prof.h)
 void set_prefill_kernel(bool on);
 void set_profile_events(hipEvent_t before, hipEvent_t after);

@@ -25,7 +25,23 @@ namespace {
 constexpr int kWavesPerGroup = 4;
 constexpr int kRowsPerWorkgroup = kWavesPerGroup * 32;
 
-template <int MODE, int D>
+// minimum over the wavefront
+__device__ inline int wave_min_int(int v) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) v = min(v, __shfl_xor(v, d, 64));
+  return v;
+}
+
+// PREFIX = true is the kernel for a prefix that every sequence of a decode or verification
+// batch shares (the same physical blocks at the head of every block table; Section 1 and
+// Section 5.2.3: prompt prefixes served from the prefix cache).  The query rows of all
+// sequences are stacked, 128 to a workgroup, so a group of the prefix is read and converted
+// once per 128 rows (four sequences of a 4-token verification step with 8 query heads per kv
+// head) instead of once per sequence.  The prefix is cut into p.prefix_chunks pieces to get
+// enough workgroups; a workgroup walks one piece and leaves, per row, an unnormalised partial
+// (max, sum, accumulator) in the workspace, in the slots behind the streaming kernel's, which
+// the reduce merges with the streaming kernel's partials over the rest of each sequence.
+template <int MODE, int D, bool PREFIX>
 __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: the operands are its bytes
   constexpr bool FP8 = MODE == KVQ_FP8E4M3_BLOCK_HEAD || MODE == KVQ_FP8E4M3_TENSOR;
@@ -50,14 +66,23 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int m16 = lane & 15, g4 = lane >> 4;
   const int H = p.num_kv_heads, G = p.group, bs = p.block_size, bs_shift = p.bs_shift;
-  const int row_blocks = (p.rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
+  // rows a (kv head) has in this kernel: one sequence's, or all sequences' stacked
+  const int all_rows = PREFIX ? p.batch * p.rows : p.rows;
+  const int row_blocks = (all_rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
+  int P = 0;  // PREFIX: the shared groups, if every sequence has that many full ones
+  if constexpr (PREFIX) {
+    int min_full = 0x7FFFFFFF;
+    for (int i = lane; i < p.batch; i += 64) min_full = min(min_full, p.seq_lens[i] >> 6);
+    if (p.shared_groups > wave_min_int(min_full)) return;  // the streaming kernel does it all
+    P = p.shared_groups;
+  }
   // Workgroup -> (sequence, kv head, row block).  The hardware hands consecutive workgroups to
   // the eight XCDs in turn, each with an L2 of its own, and the row blocks of one (sequence,
   // kv head) read the same codes: they are placed on one XCD (workgroups x, x + 8, x + 16, ...)
   // so that the codes leave HBM once, not once per XCD.
-  int pair, rb;
+  int pair, rb;  // PREFIX: pair = (piece of the prefix, kv head)
   {
-    const int pairs = p.batch * H, id = blockIdx.x;
+    const int pairs = (PREFIX ? p.prefix_chunks : p.batch) * H, id = blockIdx.x;
     if (pairs % 8 == 0) {
       const int x = id & 7, k = id >> 3;
       pair = x + 8 * (k / row_blocks);
@@ -68,16 +93,26 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     }
   }
   const int h = pair % H;
-  const int b = pair / H;
-  const int L = p.seq_lens[b];
-
-  // this wavefront's rows, and how far the workgroup has to walk
+  // this wavefront's rows, and the groups [g0, ng) the workgroup has to walk
   const int r0 = rb * kRowsPerWorkgroup + wv * 32;
-  const bool wave_live = r0 < p.rows;
-  const int r_last = min(p.rows, (rb + 1) * kRowsPerWorkgroup) - 1;
-  const int n_max = L - p.q_len + r_last / G + 1;
-  const int ng = (n_max + 63) >> 6;
-  const int n_min = wave_live ? L - p.q_len + r0 / G + 1 : L;  // shortest causal length here
+  const bool wave_live = r0 < all_rows;
+  int b, L, g0, ng, n_min, chunk = 0;
+  if constexpr (PREFIX) {
+    chunk = pair / H;
+    b = rb * kRowsPerWorkgroup / p.rows;  // whose block table: the first row's sequence (all agree)
+    L = P << 6;                           // every position below it exists in every sequence
+    g0 = (int)((long long)chunk * P / p.prefix_chunks);
+    ng = (int)((long long)(chunk + 1) * P / p.prefix_chunks);
+    n_min = 0;  // (set below, from the rows' own causal lengths)
+  } else {
+    b = pair / H;
+    L = p.seq_lens[b];
+    const int r_last = min(p.rows, (rb + 1) * kRowsPerWorkgroup) - 1;
+    const int n_max = L - p.q_len + r_last / G + 1;
+    g0 = 0;
+    ng = (n_max + 63) >> 6;
+    n_min = wave_live ? L - p.q_len + r0 / G + 1 : L;  // shortest causal length here
+  }
 
   const uint8_t* __restrict__ cache = p.cache;
   const float* __restrict__ scales = p.scales;
@@ -98,13 +133,15 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   float m_run[NT], l_run[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int r = r0 + nt * 16 + m16;
-    const bool live = r < p.rows;
+    const int rs = r0 + nt * 16 + m16;  // PREFIX: stacked row = sequence * rows + row
+    const bool live = rs < all_rows;
+    const int br = PREFIX ? (live ? rs / p.rows : 0) : b;
+    const int r = PREFIX ? rs - br * p.rows : rs;
     const int j = live ? r / G : 0;
     const int gi = live ? r - j * G : 0;
-    nrow[nt] = live ? L - p.q_len + j + 1 : L;
+    nrow[nt] = live ? (PREFIX ? p.seq_lens[br] : L) - p.q_len + j + 1 : L;
     const uint16_t* qrow =
-        p.q + (((size_t)b * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
+        p.q + (((size_t)br * p.q_len + j) * p.num_q_heads + (size_t)h * G + gi) * D;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const int d0 = PLAIN || INT4 ? 32 * s + 8 * g4 : 64 * (s >> 1) + 16 * g4 + 8 * (s & 1);
@@ -126,6 +163,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
 #pragma unroll
     for (int tt = 0; tt < DT; ++tt) acc[nt][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
+
+  if constexpr (PREFIX) n_min = wave_min_int(min(nrow[0], nrow[1]));
 
   // ---- producer side: this wavefront's quarter of a group's codes ----
   struct Entries {
@@ -315,16 +354,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
   Entries e_next, e_after;
   {
     Entries e0;
-    fetch_entries(0, e0);
-    fetch_entries(min(1, ng - 1), e_next);
-    issue_loads(0, e0);
+    fetch_entries(g0, e0);
+    fetch_entries(min(g0 + 1, ng - 1), e_next);
+    issue_loads(g0, e0);
   }
-  publish(0, 0);
-  issue_loads(min(1, ng - 1), e_next);
-  fetch_entries(min(2, ng - 1), e_after);
+  publish(g0, 0);
+  issue_loads(min(g0 + 1, ng - 1), e_next);
+  fetch_entries(min(g0 + 2, ng - 1), e_after);
   __syncthreads();
-  for (int g = 0; g < ng; ++g) {
-    const int half = g & 1;
+  for (int g = g0; g < ng; ++g) {
+    const int half = (g - g0) & 1;
     if (wave_live) {
       qk(half);
       if ((g << 6) + 64 > n_min) softmax_impl(std::true_type{}, g, half);
@@ -338,6 +377,30 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 2) void attn_prefill_kernel(co
     __syncthreads();
   }
 
+  if constexpr (PREFIX) {
+    // ---- partials: slot = wavefronts + (1 + piece) * pairs + the row's pair, as the reduce
+    // expects them ----
+    const int rt = 16 * p.row_tiles;
+    const size_t slot0 = (size_t)p.num_waves + (size_t)(chunk + 1) * p.batch * p.pairs_per_seq;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const float l = xor16_sum(l_run[nt]);
+      const int rs = r0 + nt * 16 + m16;
+      if (rs >= all_rows) continue;
+      const int br = rs / p.rows, r = rs - br * p.rows;
+      const int rg = r / rt, rl = r - rg * rt;
+      const size_t row =
+          (slot0 + (size_t)br * p.pairs_per_seq + h * p.num_row_groups + rg) * rt + rl;
+      float* arow = p.ws_acc + row * D;
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt) *(floatx4*)(arow + 16 * tt + 4 * g4) = acc[nt][tt];
+      if (g4 == 0) {
+        p.ws_ml[row * 2] = m_run[nt];
+        p.ws_ml[row * 2 + 1] = l;
+      }
+    }
+    return;
+  }
   // ---- normalised rows ----
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -360,15 +423,16 @@ bool prefill_applies(const AttnArgs& a) {
   return a.rows >= kRowsPerWorkgroup && a.mode != KVQ_INT4_GROUP32;
 }
 
-hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
-  const int row_blocks = (a.rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
-  const dim3 grid((unsigned)((size_t)a.batch * a.num_kv_heads * row_blocks));
+template <bool PREFIX>
+hipError_t launch_many_rows(const AttnArgs& a, int all_rows, int walks, hipStream_t stream) {
+  const int row_blocks = (all_rows + kRowsPerWorkgroup - 1) / kRowsPerWorkgroup;
+  const dim3 grid((unsigned)((size_t)walks * a.num_kv_heads * row_blocks));
   const dim3 block(64 * kWavesPerGroup);
-#define KVQ_LAUNCH_PREFILL(MODE)                                                              \
-  if (a.head_dim == 128)                                                                      \
-    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 128>), grid, block, 0, stream, a);          \
-  else                                                                                        \
-    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 64>), grid, block, 0, stream, a)
+#define KVQ_LAUNCH_PREFILL(MODE)                                                                \
+  if (a.head_dim == 128)                                                                        \
+    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 128, PREFIX>), grid, block, 0, stream, a);    \
+  else                                                                                          \
+    hipLaunchKernelGGL((attn_prefill_kernel<MODE, 64, PREFIX>), grid, block, 0, stream, a)
   if (a.mode == KVQ_INT8_TOKEN_HEAD) {
     KVQ_LAUNCH_PREFILL(KVQ_INT8_TOKEN_HEAD);
   } else if (a.mode == KVQ_FP8E4M3_BLOCK_HEAD) {
@@ -376,12 +440,23 @@ hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
   } else if (a.mode == KVQ_BF16_PLAIN) {
     KVQ_LAUNCH_PREFILL(KVQ_BF16_PLAIN);
   } else if (a.mode == KVQ_INT4_TOKEN_HEAD) {  // (head_dim 128 only)
-    hipLaunchKernelGGL((attn_prefill_kernel<KVQ_INT4_TOKEN_HEAD, 128>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((attn_prefill_kernel<KVQ_INT4_TOKEN_HEAD, 128, PREFIX>), grid, block, 0,
+                       stream, a);
   } else {
     KVQ_LAUNCH_PREFILL(KVQ_FP8E4M3_TENSOR);
   }
 #undef KVQ_LAUNCH_PREFILL
   return hipGetLastError();
+}
+
+hipError_t launch_prefill(const AttnArgs& a, hipStream_t stream) {
+  return launch_many_rows<false>(a, a.rows, a.batch, stream);
+}
+
+// the shared groups of a decode or verification batch (a.shared_groups > 0), ahead of the
+// streaming kernel
+hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream) {
+  return launch_many_rows<true>(a, a.batch * a.rows, a.prefix_chunks, stream);
 }
 
 }  // namespace kvq

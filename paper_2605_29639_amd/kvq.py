@@ -19,7 +19,7 @@ OK, E_NULLPTR, E_BAD_MODE, E_BAD_SHAPE, E_WORKSPACE, E_HIP, E_BAD_INDEX = 0, -1,
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvq.so")
 
 EXPORTS = ("kvq_cache_bytes", "kvq_scales_bytes", "kv_quant_write",
-           "paged_decode_attn_workspace_bytes",
+           "paged_decode_attn_workspace_bytes", "paged_decode_attn_prefix_workspace_bytes",
            "paged_decode_attn", "paged_decode_attn_prefix", "paged_decode_attn_static",
            "kvq_cache_to_canonical", "kvq_cache_from_canonical",
            "kvq_blocks_export", "kvq_blocks_import",
@@ -75,6 +75,8 @@ def _load(path, prof):
     L.kv_quant_write.argtypes = [P, P, P, I32, P, P, D, P]
     L.paged_decode_attn_workspace_bytes.restype = SZ
     L.paged_decode_attn_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32]
+    L.paged_decode_attn_prefix_workspace_bytes.restype = SZ
+    L.paged_decode_attn_prefix_workspace_bytes.argtypes = [D, I32, I32, I32, I32, I32, I32]
     L.paged_decode_attn.restype = C.c_int
     L.paged_decode_attn.argtypes = [P, P, P, D, P, I32, P, I32, I32, I32, I32, C.c_float,
                                     I32, P, P, SZ, P]
@@ -217,14 +219,22 @@ def _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, ou
     return batch
 
 
-def workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0):
+def workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0,
+                    shared_prefix_tokens=0):
+    """Bytes paged_decode_attn needs, or paged_decode_attn_prefix with shared_prefix_tokens."""
+    if shared_prefix_tokens:
+        return int(lib().paged_decode_attn_prefix_workspace_bytes(
+            C.byref(desc), batch, q_len, num_q_heads, max_seq_len, chunk_tokens,
+            int(shared_prefix_tokens)))
     return int(lib().paged_decode_attn_workspace_bytes(C.byref(desc), batch, q_len, num_q_heads,
                                                        max_seq_len, chunk_tokens))
 
 
-def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0, device="cuda"):
+def alloc_workspace(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens=0, device="cuda",
+                    shared_prefix_tokens=0):
     import torch
-    n = workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens)
+    n = workspace_bytes(desc, batch, q_len, num_q_heads, max_seq_len, chunk_tokens,
+                        shared_prefix_tokens)
     return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 
@@ -234,7 +244,8 @@ def paged_decode_attn(q, cache, scales, desc, block_tables, seq_lens, q_len, max
     """paged_decode_attn, or paged_decode_attn_prefix when shared_prefix_tokens is given."""
     import torch
     batch = _check_attn_shapes(q, cache, scales, desc, block_tables, seq_lens, q_len, out)
-    need = workspace_bytes(desc, batch, q_len, q.shape[1], max_seq_len, chunk_tokens)
+    need = workspace_bytes(desc, batch, q_len, q.shape[1], max_seq_len, chunk_tokens,
+                           shared_prefix_tokens)
     if batch > 0 and workspace.numel() * workspace.element_size() < need:
         raise ValueError("workspace holds %d bytes, the call needs %d" % (workspace.numel(), need))
     if shared_prefix_tokens:

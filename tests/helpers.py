@@ -51,7 +51,8 @@ def gpu_attention(wl, cache, scales, desc, chunk_tokens=None, seq_lens=None, q=N
     sl = torch.from_numpy(np.ascontiguousarray(seq_lens, dtype=np.int32)).cuda()
     out = torch.full((qbits.shape[0], qbits.shape[1], wl.head_dim), float("nan"),
                      dtype=torch.float32, device="cuda")
-    ws = kvq.alloc_workspace(desc, len(seq_lens), q_len, qbits.shape[1], max_len, chunk)
+    ws = kvq.alloc_workspace(desc, len(seq_lens), q_len, qbits.shape[1], max_len, chunk,
+                             shared_prefix_tokens=shared_prefix_tokens)
     ws.fill_(0xFF)  # NaN patterns: the kernels must not depend on workspace contents
     kvq.paged_decode_attn(qd, cache, scales, desc, bt, sl, q_len, max_len, wl.sm_scale, out, ws,
                           chunk_tokens=chunk, L=L, shared_prefix_tokens=shared_prefix_tokens)

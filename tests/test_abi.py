@@ -122,12 +122,12 @@ def test_attn_argument_checks():
         assert attn(L, ok, **{name: None}) == kvq.E_NULLPTR
     for name in ("q", "cache", "out"):                     # read and written in 16-byte pieces
         assert attn(L, ok, **{name: C.c_void_p(0x1008)}) == kvq.E_BAD_SHAPE
-    # workspace: one partial slot per (wavefront range, part, pair) crossing (a shared prefix
-    # makes two parts), 16 rows each, and the prefix sums of the sequences' group counts with the
-    # prefix length behind them (batch + 2 ints, padded to a multiple of 4)
+    # workspace: one partial slot per (wavefront range, pair) crossing, 16 rows each, and the
+    # prefix sums of the sequences' group counts with the shared prefix length behind them
+    # (batch + 2 ints, padded to a multiple of 4)
     need = L.paged_decode_attn_workspace_bytes(C.byref(ok), 2, 1, 4, 100, 64)
     flat_max = 2 * 2 * 2                                   # batch * ceil(100/64) * kv heads
-    assert need == (flat_max + 2 * 2 * 2) * 16 * (64 + 2) * 4 + 4 * 4
+    assert need == (flat_max + 2 * 2) * 16 * (64 + 2) * 4 + 4 * 4
     assert attn(L, ok, chunk=64, ws=None) == kvq.E_NULLPTR
     assert attn(L, ok, chunk=64, ws_bytes=need - 1) == kvq.E_WORKSPACE
     assert attn(L, ok, chunk=64, ws=C.c_void_p(0x1004), ws_bytes=need) == kvq.E_BAD_SHAPE
@@ -135,15 +135,31 @@ def test_attn_argument_checks():
     assert auto == need                                    # fewer groups than resident waves
     big = kvq.make_desc(0, 1000, 16, 8, 128)
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 64, 1, 32, 4096, 0) == \
-        (2048 + 2 * 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
+        (2048 + 64 * 8) * 16 * (128 + 2) * 4 + 68 * 4
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 1, 1, 33, 100, 0) == 0
     # the group-scaled int4 format: one row tile whatever the row count, one wavefront per SIMD
     g4 = kvq.make_desc(5, 1000, 16, 8, 128)
     assert L.paged_decode_attn_workspace_bytes(C.byref(g4), 128, 4, 64, 16384, 0) == \
-        (1024 + 2 * 128 * 8 * 2) * 16 * (128 + 2) * 4 + 132 * 4
+        (1024 + 128 * 8 * 2) * 16 * (128 + 2) * 4 + 132 * 4
     # 32 query rows per kv head -> two row tiles -> one resident wavefront per SIMD
     assert L.paged_decode_attn_workspace_bytes(C.byref(big), 128, 4, 64, 16384, 0) == \
-        (1024 + 2 * 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
+        (1024 + 128 * 8) * 32 * (128 + 2) * 4 + 132 * 4
+    # with a shared prefix: the prefix kernel's partials behind them, one per pair and piece;
+    # 8 kv heads x 32 blocks of 128 stacked rows = 256 walks -> 2 pieces for 512 workgroups
+    P = L.paged_decode_attn_prefix_workspace_bytes
+    assert P(C.byref(big), 128, 4, 64, 16384, 0, 1024) == \
+        (1024 + 128 * 8 * (1 + 2)) * 32 * (128 + 2) * 4 + 132 * 4
+    # ... as many pieces as the prefix has 64-token groups at most, and eight at most
+    assert P(C.byref(big), 2, 1, 32, 4096, 0, 100) == (1024 + 2 * 8 * (1 + 1)) * 16 * 130 * 4 + 4 * 4
+    assert P(C.byref(big), 2, 1, 32, 4096, 0, 4096) == (1024 + 2 * 8 * (1 + 8)) * 16 * 130 * 4 + 4 * 4
+    # not used: below 64 tokens, beyond max_seq_len, one sequence, 128 rows and more per kv
+    # head, the group-scaled int4 format
+    plain = L.paged_decode_attn_workspace_bytes
+    for args, desc in (((2, 1, 32, 4096, 0, 63), big), ((2, 1, 32, 4096, 0, 4160), big),
+                       ((1, 1, 32, 4096, 0, 1024), big), ((2, 64, 32, 4096, 0, 1024), big),
+                       ((2, 1, 32, 4096, 0, 1024), g4)):
+        assert P(C.byref(desc), *args) == plain(C.byref(desc), *args[:-1]) > 0, args
+    assert P(C.byref(big), 2, 1, 32, 4096, 0, -1) == 0
 
 
 def test_static_scratch_rejects_what_does_not_fit():
@@ -248,7 +264,7 @@ def test_binding_rejects_shapes_the_device_would_overrun():
     out = torch.zeros((2, 4, 64), dtype=torch.float32)
     bt = torch.zeros((2, 7), dtype=torch.int32)
     sl = torch.ones(2, dtype=torch.int32)
-    ws = torch.zeros(1 << 17, dtype=torch.uint8)
+    ws = torch.zeros(1 << 16, dtype=torch.uint8)
     with pytest.raises(ValueError):
         kvq.paged_decode_attn(q[:1], cache, scales, desc, bt, sl, 1, 100, 0.1, out, ws)
     with pytest.raises(ValueError):

@@ -236,31 +236,35 @@ PREFIX_LENS = {
 }
 
 
-@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16])
+@pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_BF16, W.MODE_INT4])
 @pytest.mark.parametrize("q_len", [1, 4])
 @pytest.mark.parametrize("lens", sorted(PREFIX_LENS))
-def test_shared_prefix_hint_changes_traffic_not_results(mode, q_len, lens):
-    """paged_decode_attn_prefix: sequences that begin with the same physical blocks.  The hint
-    changes the order in which the kernels visit the cache (every pair's prefix groups first)
-    and so the order of the fp32 merges, nothing else: the output stays within the bound of the
-    checker and close to paged_decode_attn's (the probabilities are rounded to 16 bits against a
-    running maximum that depends on the order), also with ranges given by
-    chunk_tokens and where the hint is not a multiple of 64.  A hint longer than the shortest
-    sequence is dropped on the device and a format that ignores it is untouched: bit for bit
-    paged_decode_attn's output."""
+def test_shared_prefix_is_read_through_stacked_rows(mode, q_len, lens):
+    """paged_decode_attn_prefix: sequences that begin with the same physical blocks.  The
+    shared positions go through the many-row kernel with all sequences' rows stacked, the rest
+    through the streaming kernel, and the reduce merges the two: the output stays within the
+    bound of the checker and close to paged_decode_attn's (other order of the fp32 merges; the
+    probabilities are rounded to 16 bits against a running maximum that depends on the order),
+    also with ranges given by chunk_tokens, with a prefix that is not a multiple of 64, with a
+    sequence that is nothing but the prefix (its query rows then mask part of it) and with more
+    sequences than a wavefront has lanes.  A prefix longer than the shortest sequence is dropped
+    (on the host if it exceeds max_seq_len, else on the device), as is one below 64 tokens or
+    with a single sequence: bit for bit paged_decode_attn's output then."""
     wl = W.custom("prefix", mode, PREFIX_LENS[lens], q_len, 8, 2, 128, 16,
                   seed=90 + mode + q_len, shared_prefix=256)
     assert (wl.block_tables[:, :16] == wl.block_tables[0, :16]).all()
     oc, osc = oracle_fill(wl)
     want = oracle_out(wl, oc, osc)
     cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    shortest = min(PREFIX_LENS[lens])
     for chunk in (0, 128, 512):
         plain = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk)
         assert attn_err(plain, want) <= TOL
-        for hint in (256, 200, 64, 4096):
+        for hint in (256, 200, 64, 63, 4096) + ((shortest + 64,) if lens != "one" else ()):
             hinted = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk,
                                    shared_prefix_tokens=hint)
-            if hint > 256 or mode == W.MODE_BF16:
+            used = 64 <= hint and hint // 64 * 64 <= shortest and len(PREFIX_LENS[lens]) > 1
+            if not used:
                 assert np.array_equal(hinted.view(np.uint32), plain.view(np.uint32)), hint
             else:
                 assert attn_err(hinted, want) <= TOL, (chunk, hint)

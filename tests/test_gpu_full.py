@@ -58,11 +58,15 @@ def compare_on_sample(wl, chunks, seqs=None):
                                     np.ascontiguousarray(wl.seq_lens[seqs]), wl.q_len,
                                     wl.sm_scale)
     errs = {}
+    # (a workload with a shared prefix also goes through paged_decode_attn_prefix, as timed)
     for chunk in chunks:
-        got = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk)
-        assert np.isfinite(got).all(), "non-finite output (chunk %d)" % chunk
-        errs[chunk] = attn_err(got[rows], want)
-        assert errs[chunk] <= TOL, "chunk %d: err %.3e on sequences %s" % (chunk, errs[chunk], seqs)
+        for prefix in sorted({0, wl.shared_prefix}):
+            got = gpu_attention(wl, cache, scales, desc, chunk_tokens=chunk,
+                                shared_prefix_tokens=prefix)
+            assert np.isfinite(got).all(), "non-finite output (chunk %d)" % chunk
+            errs[chunk, prefix] = attn_err(got[rows], want)
+            assert errs[chunk, prefix] <= TOL, "chunk %d prefix %d: err %.3e on sequences %s" % (
+                chunk, prefix, errs[chunk, prefix], seqs)
     return errs
 
 
