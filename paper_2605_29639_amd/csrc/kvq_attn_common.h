@@ -155,8 +155,7 @@ __device__ inline void online_softmax(floatx4 (&S)[NT][4], float skp, float lsv,
       const float pr = __builtin_amdgcn_exp2f(S[nt][u][i] - msub);
       if constexpr (MODE == KVQ_INT4_GROUP32) S[nt][u][i] = pr;  // its caller scales them once more
       if constexpr (TOKEN_SCALE) {
-        const float t = pr * row_bcast<tix>(rsv);
-        lsum = lsum + t;
+        lsum = __builtin_fmaf(pr, row_bcast<tix>(rsv), lsum);  // one v_fmac_f32_dpp
       } else {
         lsum = lsum + pr;
       }
