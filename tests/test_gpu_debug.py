@@ -80,6 +80,40 @@ def test_bad_indices_are_reported_not_followed(debug_on, mode):
     assert attn_err(out.cpu().numpy(), want) <= 2e-3
 
 
+def test_a_broken_shared_prefix_promise_is_reported(debug_on):
+    """paged_decode_attn_prefix trusts the caller that the blocks below shared_prefix_tokens
+    are the same in every table; the checks compare them with sequence 0's."""
+    import torch
+    from paper_2605_29639_amd import kvq
+    from helpers import gpu_attention, upload_oracle_cache
+    wl = W.custom("debug_prefix", W.MODE_INT8, [300, 256, 400], 1, 8, 2, 128, 16, seed=5,
+                  shared_prefix=256)
+    oc, osc = oracle_fill(wl)
+    want = oracle.paged_decode_attn(wl.q, oc, osc, wl.mode, wl.block_tables, wl.seq_lens, 1, wl.sm_scale)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    got = gpu_attention(wl, cache, scales, desc, shared_prefix_tokens=256)
+    assert attn_err(got, want) <= 2e-3
+    # sequence 2 maps its fourth block elsewhere (a valid block, but not the shared one)
+    other = int(wl.block_tables[2, 17])
+    broken = _with(wl.block_tables, (2, 3), other)
+    q = bits_to_bf16_tensor(wl.q)
+    out = torch.full((3, 8, 128), 7.0, dtype=torch.float32, device="cuda")
+    ws = kvq.alloc_workspace(desc, 3, 1, 8, wl.max_seq_len, shared_prefix_tokens=256)
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.paged_decode_attn(q, cache, scales, desc, torch.from_numpy(broken).cuda(),
+                              torch.from_numpy(wl.seq_lens).cuda(), 1, wl.max_seq_len, wl.sm_scale,
+                              out, ws, shared_prefix_tokens=256)
+    assert e.value.code == kvq.E_BAD_INDEX
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
+    # the same tables without the promise are a valid call
+    kvq.paged_decode_attn(q, cache, scales, desc, torch.from_numpy(broken).cuda(),
+                          torch.from_numpy(wl.seq_lens).cuda(), 1, wl.max_seq_len, wl.sm_scale,
+                          out, ws)
+    torch.cuda.synchronize()
+    assert np.isfinite(out.cpu().numpy()).all()
+
+
 def _with(a, at, value):
     a = a.copy()
     a[at] = value
