@@ -138,14 +138,12 @@ __device__ inline void online_softmax(floatx4 (&S)[NT][4], float skp, float lsv,
       mx[nt] = fmaxf(mx[nt], ze);
     }
   });
-  bool rescale = false;
   float alpha[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const float m_new = fmaxf(m_run[nt], xor16_max(mx[nt]));
     const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
     alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
-    rescale |= (alpha[nt] != 1.0f);
     m_run[nt] = m_new;
     const float msub = m_safe - kPOffset;
     float lsum = 0.0f;
@@ -184,11 +182,13 @@ __device__ inline void online_softmax(floatx4 (&S)[NT][4], float skp, float lsv,
     if constexpr (FP8) lsum = lsum * rsv;  // one scale per lane
     l_run[nt] = l_run[nt] * alpha[nt] + lsum;
   }
-  if (__any(rescale)) {
+  // (per 16-row tile: a tile none of whose rows' maxima moved keeps its accumulators as they are)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+  for (int nt = 0; nt < NT; ++nt) {
+    if (__any(alpha[nt] != 1.0f)) {
 #pragma unroll
       for (int tt = 0; tt < DT; ++tt) acc[nt][tt] *= alpha[nt];
+    }
   }
 }
 
