@@ -457,6 +457,73 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
 // convert to the same code, that is the exact quotient's code.  The rare elements where they
 // differ (a code boundary lies in between: about one in 60 000), and runs whose scale is below
 // the normal fp32 range, are decided in fp64.
+// Rows r_lo .. r_hi - 1 of the 16-token sub-block at block offset `base`, held in `raw` in the
+// order load_subblock leaves them, encoded under the scale s and stored into the K or V tile.
+template <int D>
+__device__ inline void fp8_encode_subblock(const uint4 (&raw)[16 / (64 / (D / 8))], int kv,
+                                           uint8_t* __restrict__ tile, int base, int r_lo, int r_hi,
+                                           float s, int bs, int lane) {
+  constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
+  constexpr float kUp = 1.0f + 4.76837158203125e-07f, kDown = 1.0f - 4.76837158203125e-07f;  // 2^-21
+  const int c = lane & (CL - 1), g = lane / CL;
+  const bool usable = s > 1e-30f;  // rcp of a denormal is not usable
+  const float inv = usable ? __builtin_amdgcn_rcpf(s) : 0.0f;
+  // four values (element e4[n] of row r4[n]) -> four code bytes in that order
+  auto codes4 = [&](const int (&r4)[4], const int (&e4)[4], int n) -> uint32_t {
+    if (!(s > 0.0f)) return 0u;  // an all-zero run under a zero scale: codes 0x00
+    float q[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+      q[x] = x < n ? __builtin_amdgcn_fmed3f(bf16_of(raw[r4[x]], e4[x]) * inv, -448.0f, 448.0f) : 0.0f;
+    int up = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kUp, q[1] * kUp, 0, false);
+    int down = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kDown, q[1] * kDown, 0, false);
+    if (n > 2) {
+      up = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kUp, q[3] * kUp, up, true);
+      down = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kDown, q[3] * kDown, down, true);
+    }
+    uint32_t word = (uint32_t)up;
+    const uint32_t diff = usable ? word ^ (uint32_t)down : ~0u;
+    if (__builtin_expect(__any(diff != 0), 0)) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        if (x >= n) break;
+        const bool bad = ((diff >> (8 * x)) & 0xFFu) != 0;
+        if (!__any(bad)) continue;  // wave-uniform: nobody asked
+        if (bad) {
+          const uint32_t code = fp8_code((double)bf16_of(raw[r4[x]], e4[x]) / (double)s);
+          word = (word & ~(0xFFu << (8 * x))) | (code << (8 * x));
+        }
+      }
+    }
+    return word;
+  };
+  if (kv == 0) {  // a row's 8 codes are two words of the quad order
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int r = i * G + g;
+      const int r4[4] = {i, i, i, i}, lo[4] = {0, 1, 2, 3}, hi[4] = {4, 5, 6, 7};
+      const uint2 words = make_uint2(codes4(r4, lo, 4), codes4(r4, hi, 4));
+      if (r >= r_lo && r < r_hi) *(uint2*)(tile + k_elem(base + r, 8 * c, bs, D)) = words;
+    }
+  } else {  // a channel's NI tokens are adjacent bytes of its 16-token row
+    const bool whole = r_lo == 0 && r_hi == 16;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int r4[4] = {0, 1 % NI, 2 % NI, 3 % NI}, e4[4] = {e, e, e, e};
+      const uint32_t word = codes4(r4, e4, NI);
+      uint8_t* row = tile + v_elem(base, 8 * c + e, bs, D) + g * NI;
+      if (whole) {
+        if constexpr (NI == 4) *(uint32_t*)row = word;
+        else *(uint16_t*)row = (uint16_t)word;
+      } else {  // byte by byte: the other slots of the row keep their contents
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          if (g * NI + i >= r_lo && g * NI + i < r_hi) row[i] = (uint8_t)(word >> (8 * i));
+      }
+    }
+  }
+}
+
 // One run (the call's consecutive tokens that fall into one block: any start o_min, any length),
 // K and V.  `done` comes back false, and nothing is written, if a block scale grows over older
 // codes: they have to be re-expressed, which the general routine does.
@@ -467,7 +534,6 @@ __device__ inline void fp8_run_fast(const uint16_t* __restrict__ k_src,
                                     float* __restrict__ k_sp, float* __restrict__ v_sp, int o_min,
                                     int run, int bs, int lane, bool tensor_scale, bool& done) {
   constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
-  const int c = lane & (CL - 1), g = lane / CL;
   const int base0 = o_min & ~15;                       // block offset of the first sub-block touched
   const int nsb = ((o_min + run + 15) >> 4) - (o_min >> 4);
   // sub-block j of the run: its valid rows and where its first valid row's token lies
@@ -521,71 +587,12 @@ __device__ inline void fp8_run_fast(const uint16_t* __restrict__ k_src,
     if (o_min > 0 && s_new[kv] > s_prev && s_prev > 0.0f) done = false;
   }
   if (!done) return;
-  constexpr float kUp = 1.0f + 4.76837158203125e-07f, kDown = 1.0f - 4.76837158203125e-07f;  // 2^-21
-
   auto encode = [&](const uint4 (&raw)[NI], int kv, int j) {
-    const float s = s_new[kv];
-    const bool usable = s > 1e-30f;  // rcp of a denormal is not usable
-    const float inv = usable ? __builtin_amdgcn_rcpf(s) : 0.0f;
-    uint8_t* tile = kv ? v_tile : k_tile;
     int r_lo, r_hi;
     ptrdiff_t ft;
     rows_of(j, r_lo, r_hi, ft);
-    const int base = base0 + 16 * j;
-    // four values (element e4[n] of row r4[n]) -> four code bytes in that order
-    auto codes4 = [&](const int (&r4)[4], const int (&e4)[4], int n) -> uint32_t {
-      if (!(s > 0.0f)) return 0u;  // an all-zero run under a zero scale: codes 0x00
-      float q[4];
-#pragma unroll
-      for (int x = 0; x < 4; ++x)
-        q[x] = x < n ? __builtin_amdgcn_fmed3f(bf16_of(raw[r4[x]], e4[x]) * inv, -448.0f, 448.0f) : 0.0f;
-      int up = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kUp, q[1] * kUp, 0, false);
-      int down = __builtin_amdgcn_cvt_pk_fp8_f32(q[0] * kDown, q[1] * kDown, 0, false);
-      if (n > 2) {
-        up = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kUp, q[3] * kUp, up, true);
-        down = __builtin_amdgcn_cvt_pk_fp8_f32(q[2] * kDown, q[3] * kDown, down, true);
-      }
-      uint32_t word = (uint32_t)up;
-      const uint32_t diff = usable ? word ^ (uint32_t)down : ~0u;
-      if (__builtin_expect(__any(diff != 0), 0)) {
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          if (x >= n) break;
-          const bool bad = ((diff >> (8 * x)) & 0xFFu) != 0;
-          if (!__any(bad)) continue;  // wave-uniform: nobody asked
-          if (bad) {
-            const uint32_t code = fp8_code((double)bf16_of(raw[r4[x]], e4[x]) / (double)s);
-            word = (word & ~(0xFFu << (8 * x))) | (code << (8 * x));
-          }
-        }
-      }
-      return word;
-    };
-    if (kv == 0) {  // a row's 8 codes are two words of the quad order
-#pragma unroll
-      for (int i = 0; i < NI; ++i) {
-        const int r = i * G + g;
-        const int r4[4] = {i, i, i, i}, lo[4] = {0, 1, 2, 3}, hi[4] = {4, 5, 6, 7};
-        const uint2 words = make_uint2(codes4(r4, lo, 4), codes4(r4, hi, 4));
-        if (r >= r_lo && r < r_hi) *(uint2*)(tile + k_elem(base + r, 8 * c, bs, D)) = words;
-      }
-    } else {  // a channel's NI tokens are adjacent bytes of its 16-token row
-      const bool whole = r_lo == 0 && r_hi == 16;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int r4[4] = {0, 1 % NI, 2 % NI, 3 % NI}, e4[4] = {e, e, e, e};
-        const uint32_t word = codes4(r4, e4, NI);
-        uint8_t* row = tile + v_elem(base, 8 * c + e, bs, D) + g * NI;
-        if (whole) {
-          if constexpr (NI == 4) *(uint32_t*)row = word;
-          else *(uint16_t*)row = (uint16_t)word;
-        } else {  // byte by byte: the other slots of the row keep their contents
-#pragma unroll
-          for (int i = 0; i < NI; ++i)
-            if (g * NI + i >= r_lo && g * NI + i < r_hi) row[i] = (uint8_t)(word >> (8 * i));
-        }
-      }
-    }
+    fp8_encode_subblock<D>(raw, kv, kv ? v_tile : k_tile, base0 + 16 * j, r_lo, r_hi, s_new[kv], bs,
+                           lane);
   };
   encode(k_first, 0, 0);
   encode(v_first, 1, 0);
@@ -657,6 +664,122 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_bulk_kernel(
     if (!done) {
       fp8_run<D>(k, v, cache, scales, H, bs, 0, h, t0, slot0, run, lane, tensor_scale != 0);
       fp8_run<D>(k, v, cache, scales, H, bs, 1, h, t0, slot0, run, lane, tensor_scale != 0);
+    }
+  }
+}
+
+// Blocks of more than 16 tokens under one scale per block: the block's absmax ties its
+// sub-blocks together, and one wavefront doing them one after the other (as above) leaves the
+// wavefronts of the block's other windows with nothing to do.  Here a workgroup of bs / 16
+// wavefronts owns bs consecutive tokens of the call and one kv head, and handles the runs that
+// start among them: wavefront j loads sub-block j of the run (K and V, kept in registers),
+// the sub-blocks' absmax values meet in LDS, and every wavefront encodes its own sub-block
+// under the block's scale.  A run whose scale would grow over older codes of the block goes to
+// the general routine (wavefront 0), as above.  Every wavefront takes every barrier: the list
+// of runs comes from LDS and the loops over it are uniform.
+template <int D>
+__global__ __launch_bounds__(1024) void write_fp8_block_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int64_t* __restrict__ slot_mapping, int32_t num_tokens, uint8_t* __restrict__ cache,
+    float* __restrict__ scales, int32_t H, int32_t bs) {
+  constexpr int CL = D / 8, G = 64 / CL, NI = 16 / G;
+  __shared__ uint32_t sh_starts[16];
+  __shared__ uint32_t sh_amax[2][16];
+  __shared__ float sh_prev[2];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int nw = bs >> 4;  // wavefronts of the workgroup = sub-blocks of a block
+  const int h = (int)(blockIdx.x % H);
+  const int g0 = (int)(blockIdx.x / H) * bs;  // the workgroup's first token
+  {
+    bool first = false;
+    const int t = g0 + 16 * wv + lane;
+    if (lane < 16 && t < num_tokens) {
+      const int64_t slot = slot_mapping[t];
+      if (slot >= 0)
+        first = !(t > 0 && (slot & (bs - 1)) > 0 && slot_mapping[t - 1] == slot - 1);
+    }
+    const uint32_t starts = (uint32_t)__ballot(first);
+    if (lane == 0) sh_starts[wv] = starts;
+  }
+  __syncthreads();
+  const size_t tstride = (size_t)H * D;
+  for (int ww = 0; ww < nw; ++ww) {
+    uint32_t starts = sh_starts[ww];
+    while (starts) {
+      const int t0 = g0 + 16 * ww + __builtin_ctz(starts);
+      starts &= starts - 1;
+      const int64_t slot0 = slot_mapping[t0];
+      const int o_min = (int)(slot0 & (bs - 1));
+      const int room = bs - o_min;  // slots left in the block
+      int run = 0;
+      for (int base = 0; base < room; base += 64) {  // block sizes reach 256
+        const int j = base + lane;
+        const bool cont = j < room && t0 + j < num_tokens && slot_mapping[t0 + j] == slot0 + j;
+        const unsigned long long m = __ballot(cont);
+        const int n = m == ~0ull ? 64 : __builtin_ctzll(~m);
+        run += n;
+        if (n < 64) break;
+      }
+      const int64_t blk = slot0 >> __builtin_ctz(bs);
+      float* k_sp = scales + ((size_t)blk * 2 + 0) * H + h;
+      float* v_sp = scales + ((size_t)blk * 2 + 1) * H + h;
+      // this wavefront's sub-block of the run: its valid rows, where its first valid row's
+      // token lies
+      const int base0 = o_min & ~15;
+      const int nsb = ((o_min + run + 15) >> 4) - (o_min >> 4);
+      const bool mine = wv < nsb;
+      const int base = base0 + 16 * wv;
+      const int r_lo = max(o_min - base, 0), r_hi = min(o_min + run - base, 16);
+      uint4 k_rows[NI], v_rows[NI];
+      uint32_t amax_k = 0, amax_v = 0;
+      if (mine) {
+        const size_t row = ((size_t)(t0 + (base + r_lo - o_min)) * H + h) * D;
+        load_subblock<D>(k + row, tstride, 0, lane, r_lo, r_hi, k_rows);
+        load_subblock<D>(v + row, tstride, 1, lane, r_lo, r_hi, v_rows);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          amax_k = max(amax_k, absmax8(k_rows[i]));
+          amax_v = max(amax_v, absmax8(v_rows[i]));
+        }
+        amax_k = wave_max_u32(amax_k);
+        amax_v = wave_max_u32(amax_v);
+      }
+      if (lane == 0) {
+        sh_amax[0][wv] = amax_k;
+        sh_amax[1][wv] = amax_v;
+        if (wv == 0) {  // the block's scales before this run (a run from offset 0 starts afresh)
+          sh_prev[0] = o_min > 0 ? *k_sp : 0.0f;
+          sh_prev[1] = o_min > 0 ? *v_sp : 0.0f;
+        }
+      }
+      __syncthreads();
+      float s_new[2];
+      bool done = true;
+#pragma unroll
+      for (int kv = 0; kv < 2; ++kv) {
+        uint32_t amax = 0;
+        for (int j = 0; j < nw; ++j) amax = max(amax, sh_amax[kv][j]);
+        const float s_prev = sh_prev[kv];
+        const float s_cand = (amax == 0) ? 0.0f : __fdiv_rn(bf16_bits_to_float(amax), 448.0f);
+        s_new[kv] = s_prev > s_cand ? s_prev : s_cand;
+        if (o_min > 0 && s_new[kv] > s_prev && s_prev > 0.0f) done = false;
+      }
+      if (done) {
+        if (mine) {
+          fp8_encode_subblock<D>(k_rows, 0, cache + tile_offset(blk, 0, h, H, bs, D), base, r_lo, r_hi,
+                                 s_new[0], bs, lane);
+          fp8_encode_subblock<D>(v_rows, 1, cache + tile_offset(blk, 1, h, H, bs, D), base, r_lo, r_hi,
+                                 s_new[1], bs, lane);
+        }
+        if (wv == 0 && lane == 0) {
+          *k_sp = s_new[0];
+          *v_sp = s_new[1];
+        }
+      } else if (wv == 0) {
+        fp8_run<D>(k, v, cache, scales, H, bs, 0, h, t0, slot0, run, lane, false);
+        fp8_run<D>(k, v, cache, scales, H, bs, 1, h, t0, slot0, run, lane, false);
+      }
+      __syncthreads();  // (the LDS words are written again for the next run)
     }
   }
 }
@@ -940,6 +1063,16 @@ hipError_t launch_write(const void* k, const void* v, const int64_t* slot_mappin
                          num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
     else
       hipLaunchKernelGGL((write_int8_bulk_kernel<64>), dim3(g), block, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+  } else if (bulk && desc.mode == KVQ_FP8E4M3_BLOCK_HEAD && desc.block_size > 16) {
+    // a workgroup per (block_size consecutive tokens, head), a wavefront per sub-block
+    const int64_t groups = ((int64_t)num_tokens + desc.block_size - 1) / desc.block_size;
+    const dim3 grid((unsigned)(groups * desc.num_kv_heads)), wg((unsigned)(desc.block_size / 16 * 64));
+    if (desc.head_dim == 128)
+      hipLaunchKernelGGL((write_fp8_block_kernel<128>), grid, wg, 0, stream, kk, vv, slot_mapping,
+                         num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
+    else
+      hipLaunchKernelGGL((write_fp8_block_kernel<64>), grid, wg, 0, stream, kk, vv, slot_mapping,
                          num_tokens, c, scales, desc.num_kv_heads, desc.block_size);
   } else if (bulk) {
     const unsigned g = (unsigned)((units / 2 + kWaves - 1) / kWaves);  // K and V per wavefront

@@ -68,7 +68,7 @@ def test_ragged_shapes_bulk_write(mode, shape):
 
 @pytest.mark.parametrize("mode", [W.MODE_INT8, W.MODE_FP8, W.MODE_FP8_TENSOR, W.MODE_INT4,
                                   W.MODE_INT4_GROUP])
-@pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1)])
+@pytest.mark.parametrize("bs,D,H", [(16, 128, 2), (64, 64, 3), (32, 128, 1), (256, 128, 1), (128, 64, 2)])
 def test_prefill_of_several_sequences_in_one_call(mode, bs, D, H):
     """Thousands of tokens in one call (the prefill kernels): ragged sequences back to back, so
     that runs start at any token index; one sequence continued from the middle of a block;
