@@ -446,9 +446,10 @@ __global__ __launch_bounds__(kWaves * 64) void write_fp8_kernel(
 // ---- fp8, many tokens per call (prefill) ---------------------------------------------------
 // A run made of whole 16-token sub-blocks whose block scale does not force a re-encode of
 // earlier codes (always so when a block is written at once) is handled with 16-byte loads, a
-// lane owning 8 channels of 16 / G tokens as in the int8 prefill kernel.  The rows of up to four
-// sub-blocks (blocks of up to 64 tokens) stay in registers between the pass that finds the
-// run's absmax and the pass that encodes; longer runs are read a second time.
+// lane owning 8 channels of 16 / G tokens as in the int8 prefill kernel.  The rows of the run's
+// first sub-block stay in registers between the pass that finds the run's absmax and the pass
+// that encodes (a 16-token block is read once); further sub-blocks are read a second time.
+// (Blocks above 16 tokens go to write_fp8_block_kernel below, a wavefront per sub-block.)
 //
 // Rounding x / s to E4M3 with the hardware conversion (v_cvt_pk_fp8_f32: nearest, ties to even,
 // exact for every |value| <= 448 including the subnormals and the sign of zero; above 464 it
