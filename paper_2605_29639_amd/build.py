@@ -15,6 +15,11 @@ LIB_PROF = os.path.join(HERE, "libkvq_prof.so")
 SOURCES = ["kvq_api.hip", "kvq_write.hip", "kvq_attn.hip", "kvq_prefill.hip", "kvq_repack.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # Matrix-instruction results stay in ordinary vector registers.  With the 512-register
+         # budget of a one-wavefront-per-SIMD kernel the compiler otherwise puts them into
+         # accumulation registers, which no vector instruction can address, and copies every
+         # logit and (on each rescale) every output accumulator out and back in.
+         "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Wno-unused-command-line-argument"]
 
 
