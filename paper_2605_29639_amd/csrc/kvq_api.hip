@@ -105,14 +105,14 @@ bool make_plan(const kvq_cache_desc_t* d, int32_t batch, int32_t q_len, int32_t 
   plan->pairs_per_seq = (int32_t)pairs;
   if (chunk_tokens == 0) {
     // even split over as many wavefronts as an MI355X keeps resident at this kernel's
-    // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile) or x 1 (two tiles)
-    // (an unquantized cache needs twice the registers per group: one wavefront per SIMD)
+    // register footprint: 256 CUs x 4 SIMDs x 2 (one 16-row tile, or two at head_dim 64) or
+    // x 1 (two tiles at head_dim 128)
+    // (an unquantized cache needs twice the registers per group: one wavefront per SIMD; so
+    // does the group-scaled int4 cache, for its four accumulators per logit)
     const int64_t waves = auto_waves();
-    // (so does the group-scaled int4 cache, for its four accumulators per logit)
-    const int64_t resident = plan->row_tiles == 1 && d->mode != KVQ_BF16_PLAIN &&
-                                     d->mode != KVQ_INT4_GROUP32
-                                 ? waves
-                                 : waves / 2;
+    const bool two_per_simd = (plan->row_tiles == 1 || d->head_dim == 64) &&
+                              d->mode != KVQ_BF16_PLAIN && d->mode != KVQ_INT4_GROUP32;
+    const int64_t resident = two_per_simd ? waves : waves / 2;
     plan->range_groups = 0;
     plan->num_waves = (int32_t)(flat_max < resident ? flat_max : resident);
   } else {

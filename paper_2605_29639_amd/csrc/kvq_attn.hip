@@ -129,9 +129,10 @@ __device__ inline int range_of(const Split& s, int f) {
 //   CLOCK = true: the kernel itself, every wavefront also storing clock readings at fixed points.
 // (The second launch bound, two wavefronts per SIMD, for the quantized one-tile kernels: they
 // fit either way, but told so the compiler keeps everything in 200-224 VGPRs instead of parking
-// values in AGPRs and copying them back, 1-2 % faster.)
+// values in AGPRs and copying them back, 1-2 % faster.  At head_dim 64 the two-tile kernels,
+// double buffers included, fit 256 registers as well and run two per SIMD too.)
 template <int MODE, int D, int NT, bool CEIL, int DEPTH, bool CLOCK>
-__global__ __launch_bounds__(64, (NT == 1 && MODE != KVQ_BF16_PLAIN && MODE != KVQ_INT4_GROUP32) ? 2 : 1) void
+__global__ __launch_bounds__(64, ((NT == 1 || D == 64) && MODE != KVQ_BF16_PLAIN && MODE != KVQ_INT4_GROUP32) ? 2 : 1) void
 attn_stream_kernel(const AttnArgs p) {
   constexpr bool PLAIN = MODE == KVQ_BF16_PLAIN;  // unquantized cache: 2-byte elements
   // e4m3 codes, one scale per lane and group: the block's, or the whole layer's
