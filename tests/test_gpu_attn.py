@@ -208,6 +208,31 @@ def test_random_shapes(seed):
     check(wl, chunks=(chunk,))
 
 
+@pytest.mark.parametrize("mode,q_len,prefix,batch,spread",
+                         [(W.MODE_INT8, 1, 0, 3000, 200), (W.MODE_FP8, 1, 0, 1500, 200),
+                          (W.MODE_INT8, 4, 0, 3000, 200), (W.MODE_BF16, 1, 0, 3000, 200),
+                          (W.MODE_INT8, 2, 256, 2000, 100), (W.MODE_FP8, 4, 256, 1100, 64)])
+def test_thousands_of_short_sequences(mode, q_len, prefix, batch, spread):
+    """Far more (sequence, kv head) pairs than wavefronts: every range of the flat list crosses
+    many pairs, most pairs lie inside one range and are written without a partial, and the
+    per-sequence bookkeeping (lengths, prefix sums) runs over a batch many times the
+    wavefront's width.  With a prefix: the same through the shared-prefix entry point."""
+    rng = np.random.default_rng(900 + q_len)
+    lo = max(q_len, prefix)
+    lens = [int(x) for x in rng.integers(lo, lo + spread, size=batch)]
+    lens[17] = lo              # the shortest allowed
+    lens[batch - 1] = lo + 700  # and a long one at the very end of the list
+    wl = W.custom("crowd", mode, lens, q_len, 4, 2, 128, 16, seed=77, shared_prefix=prefix)
+    oc, osc = oracle_fill(wl)
+    want = oracle_out(wl, oc, osc)
+    cache, scales, desc = upload_oracle_cache(wl, oc, osc)
+    for hint in ((0,) if prefix == 0 else (prefix, 64, 0)):
+        got = gpu_attention(wl, cache, scales, desc, chunk_tokens=0, shared_prefix_tokens=hint)
+        assert np.isfinite(got).all()
+        e = attn_err(got, want)
+        assert e <= TOL, "shared_prefix_tokens %d: err %.3e" % (hint, e)
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_many_query_rows_through_both_kernels(mode):
     """128 and more query rows per kv head take the kernel that shares the dequantization among
