@@ -233,6 +233,15 @@ def test_thousands_of_short_sequences(mode, q_len, prefix, batch, spread):
         assert e <= TOL, "shared_prefix_tokens %d: err %.3e" % (hint, e)
 
 
+@pytest.mark.parametrize("mode,D", [(W.MODE_INT8, 128), (W.MODE_FP8, 64), (W.MODE_BF16, 128),
+                                    (W.MODE_INT4_GROUP, 128)])
+def test_the_largest_query_length(mode, D):
+    """q_len at the library's limit (1024 query tokens per sequence): a whole prompt of exactly
+    that length, and a chunk of that length over a shorter prefix."""
+    wl = W.custom("longest_chunk", mode, [1024, 1500], 1024, 4, 2, D, 16, seed=31 + mode)
+    check(wl)
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_many_query_rows_through_both_kernels(mode):
     """128 and more query rows per kv head take the kernel that shares the dequantization among
